@@ -1,0 +1,217 @@
+/* fastardiff.h - C ABI of the MI355X (gfx950) speculative-round library.
+ *
+ * One entropy-informed speculative decoding round for continuous-token AR + diffusion-head
+ * generators, after Fast-ARDiff (Alg. 1 of the supplement; Sec. 4.3; Eq. 1; S2.1; S3):
+ *   draft K latent tokens one by one with a small AR transformer and the shared diffusion head,
+ *   stopping a sample at the first draft step whose shallow-layer entropy is below tau_ent;
+ *   verify the surviving drafts in ONE KV-cached forward of the target transformer;
+ *   decode the target-side means with the same per-step noise; accept the longest prefix that
+ *   passes the continuous ratio test.
+ *
+ * Conventions
+ *  - Every function returns FARD_OK (0) or a negative fard_status; none throws, aborts or exits.
+ *    spec_last_error() gives the text of the last failure of a context.
+ *  - Every array argument is CALLER-OWNED DEVICE memory unless the comment says "host".
+ *    The context owns only what spec_round_init allocates (packed weights, KV caches, workspace).
+ *  - All work is enqueued on the HIP stream given to spec_round_init and the calls return
+ *    without synchronising (exceptions are marked "synchronises").  Outputs are valid once the
+ *    caller has synchronised that stream.  Calls on one context must not overlap.
+ *  - "storage type" = the context's dtype: FARD_F32 (float) or FARD_BF16 (bfloat16, arithmetic
+ *    accumulates in fp32).  Latents, noise, means, entropies and uniforms are always fp32.
+ *  - Row-major everywhere.  Shapes in brackets.
+ *  - Token bookkeeping: the caches hold every accepted token except the newest, the PENDING
+ *    token.  Draft step i reads token i-1 (the pending token for i = 1) and produces token i;
+ *    verify row j reads token j and yields the target's distribution of token j+1.
+ *    eps[:, b, j, :] is the noise trajectory of token j+1, shared by draft and target (S3 item 1).
+ */
+#ifndef FASTARDIFF_H
+#define FASTARDIFF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum fard_status {
+  FARD_OK = 0,
+  FARD_EINVAL = -1,     /* null pointer, bad enum value, missing weight */
+  FARD_ESHAPE = -2,     /* sizes the kernels do not support or that disagree with the config */
+  FARD_ECAPACITY = -3,  /* batch, rows or context beyond what init reserved */
+  FARD_ENOMEM = -4,
+  FARD_EHIP = -5,       /* a HIP call failed; text in spec_last_error */
+  FARD_ESTATE = -6
+};
+
+enum { FARD_F32 = 0, FARD_BF16 = 1 };
+enum { FARD_ACT_GELU = 0, FARD_ACT_SWIGLU = 1 };
+enum { FARD_NORM_LAYER = 0, FARD_NORM_RMS = 1 };
+enum { FARD_POS_LEARNED = 0, FARD_POS_ROPE = 1 };
+enum { FARD_ENT_FEATURE = 0, FARD_ENT_ATTN = 1 };
+enum { FARD_TARGET = 0, FARD_DRAFT = 1 };
+
+typedef struct fard_ctx fard_ctx; /* opaque */
+
+/* Pre-norm causal transformer (the AR module z = ART(x_{1:i-1}, c) of Sec. 3.2). */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, d_head, d_ff;
+  int32_t act;        /* FARD_ACT_*: erf-GELU MLP or SwiGLU MLP */
+  int32_t norm;       /* FARD_NORM_*: LayerNorm (gain+bias) or RMSNorm (gain) */
+  int32_t pos;        /* FARD_POS_*: learned absolute table or RoPE (rotate-half pairing) */
+  int32_t has_bias;   /* biases on the QKV / O / MLP projections */
+  float norm_eps, rope_theta;
+  int32_t d_latent;   /* D: width of a latent token */
+  int32_t n_cond_ids; /* rows of the class/text id table, 0 = none */
+  int32_t d_out;      /* feature width after the optional up-projection, 0 = d_model */
+  int32_t max_pos;    /* rows of the learned position table */
+} fard_tf_cfg;
+
+/* Few-step diffusion/flow head x_0 = Diff(x_t | t, z) (Sec. 3.2, Sec. 4.2): AdaLN residual MLP. */
+typedef struct {
+  int32_t n_blocks, width, d_cond, d_latent, n_steps, t_freq_dim;
+  float t_scale, sigma_last, temperature;
+  int32_t renoise; /* 1: re-noise with the shared eps_k between steps, 0: Euler step */
+} fard_head_cfg;
+
+typedef struct {
+  fard_tf_cfg target, draft;
+  fard_head_cfg head;
+  int32_t K;             /* draft length gamma (Alg. 1 input), <= 64 */
+  int32_t max_batch;     /* B <= max_batch in every call */
+  int32_t max_ctx;       /* cache capacity per sample in tokens */
+  int32_t entropy_layer; /* l_s: 1-indexed draft layer whose output feeds the entropy indicator */
+  int32_t entropy_mode;  /* FARD_ENT_FEATURE: softmax over the d channels of the layer output;
+                            FARD_ENT_ATTN: attention rows of that layer, mean over heads (S2.1) */
+  int32_t prefix_rule;   /* must be 1: a failed draft drops itself and every later draft (Alg. 1) */
+  int32_t dtype;         /* FARD_F32 or FARD_BF16 */
+  float tau_ent;         /* default threshold; calls take their own */
+} fard_round_cfg;
+
+/* One named weight.  Matrices are [d_in, d_out] row-major (y = x W + b).  Names:
+ *   <m> in {target, draft}:
+ *     <m>.in.w [D,d]  <m>.in.b [d]  <m>.pos [max_pos,d] (learned)  <m>.cond [n_cond_ids,d]
+ *     <m>.L<i>.n1.g/.n1.b/.n2.g/.n2.b [d] (.b only for LayerNorm)
+ *     <m>.L<i>.wqkv [d,(H+2Hkv)dh] columns = q heads | k heads | v heads,  .bqkv
+ *     <m>.L<i>.wo [H dh,d] .bo ;  GELU: .w1 [d,F] .b1 .w2 [F,d] .b2 ;  SwiGLU: .wg .wu [d,F] .wd [F,d]
+ *     <m>.nf.g/.nf.b [d]   <m>.up.w [d,d_out] (only if d_out != d_model)
+ *   head.in.w [D,w] .in.b  head.c.w [d_cond,w] .c.b  head.t1.w [t_freq,w] .t1.b  head.t2.w [w,w] .t2.b
+ *   head.B<j>.mod.w [w,3w] columns = shift | scale | gate, .mod.b ; .w1 [w,w] .b1 .w2 [w,w] .b2
+ *   head.f.mod.w [w,2w] columns = shift | scale, .f.mod.b ; head.out.w [w,D] .out.b
+ * Biases and gains that are absent default to 0 and 1. */
+typedef struct {
+  const char* name;
+  const void* data;   /* host or device pointer */
+  int64_t numel;
+  int32_t dtype;      /* FARD_F32 or FARD_BF16 (element type of `data`) */
+  int32_t on_device;  /* 0: host memory, 1: device memory */
+} fard_tensor;
+
+/* Alg. 1 inputs (models, gamma, T, temperature, tau_ent): builds the context.  Copies and re-lays
+ * every weight (the caller may free its buffers on return), allocates both KV caches (zeroed,
+ * lengths 0) and the workspace for max_batch * (K+1) rows.  hip_stream: a hipStream_t or NULL for
+ * the default stream.  Synchronises. */
+int spec_round_init(const fard_round_cfg* cfg, const fard_tensor* weights, int32_t n_weights,
+                    void* hip_stream, fard_ctx** out);
+int spec_round_destroy(fard_ctx* ctx);
+
+/* Sets the cached length of every sample of model `which` (FARD_TARGET / FARD_DRAFT).
+ * cache_len: HOST int32 [B] or NULL (all 0).  Does not touch cache contents. */
+int spec_kv_reset(fard_ctx* ctx, int32_t which, const int32_t* cache_len, int32_t B);
+/* Writes positions 0..n-1 of one layer's cache from plain tensors k, v [B, H_kv, n, d_head] in
+ * storage type (synthetic caches).  Lengths are set with spec_kv_reset. */
+int spec_kv_load(fard_ctx* ctx, int32_t which, int32_t layer, const void* k, const void* v,
+                 int32_t B, int32_t n);
+/* Copies the current lengths to HOST int32 [B].  Synchronises. */
+int spec_kv_lengths(fard_ctx* ctx, int32_t which, int32_t* out_host, int32_t B);
+/* cache_len[b] = base_len[b] + 1 + n_accept[b] for both models: the pending token and the accepted
+ * drafts become context (Alg. 1 Step 4).  n_accept: device int32 [B]. `which`: FARD_TARGET,
+ * FARD_DRAFT, or -1 for both.  Uses the lengths recorded at the start of the last
+ * spec_draft / spec_verify of that model. */
+int spec_kv_commit(fard_ctx* ctx, int32_t which, const int32_t* n_accept, int32_t B);
+
+/* KV-cached forward of one model over packed rows (Alg. 1 Step 2 for the target, Step 1 for the
+ * draft; causal structure of Sec. 3.1).  Sample b owns n_q[b] consecutive rows; row j of a sample
+ * sits at position cache_len[b] + j and attends to the cache and to rows 0..j.
+ *   x_in     fp32 [M, D] latent rows         cond_id  int32 [M] or NULL; >= 0: the row is an id row
+ *   n_q      device int32 [B], sum <= M      M <= max_batch*(K+1)
+ *   nq_max   host upper bound of n_q[b]; device values are clamped to it; bf16: nq_max * (H/H_kv) <= 64.
+ *            Capacity (cache_len + nq_max <= max_ctx) is checked against it on the host.
+ *   commit   1: cache_len[b] += n_q[b]
+ *   z_out    storage type [M, d_out]         shallow_out  fp32 [M, d] residual stream after layer
+ *   h_attn_out fp32 [M] head-mean attention-row entropy of layer entropy_layer (either may be NULL) */
+int spec_forward(fard_ctx* ctx, int32_t which, const float* x_in, const int32_t* cond_id,
+                 const int32_t* n_q, int32_t nq_max, int32_t B, int32_t M, int32_t commit, void* z_out,
+                 float* shallow_out, float* h_attn_out);
+
+/* Shallow-layer entropy indicator + pre-filter (abstract; Eq. 1; Sec. 4.3; Alg. 1 Step 1):
+ * H[b,i] = -sum_c p_c ln p_c, p = softmax(feat[b,i,:]); keep[b,i] = all_{j<=i}(H[b,j] >= tau);
+ * n_keep[b] = sum_i keep; surv_idx = ascending flat indices b*K+i of kept drafts; n_surv = count.
+ *   feat storage type [B, K, L]; H fp32 [B,K]; keep uint8 [B,K]; n_keep int32 [B];
+ *   surv_idx int32 [B*K] (first n_surv valid); n_surv int32 [1].  B*K = 0 gives n_surv = 0. */
+int entropy_prefilter(fard_ctx* ctx, const void* feat, int32_t B, int32_t K, int32_t L, float tau,
+                      float* H, uint8_t* keep, int32_t* n_keep, int32_t* surv_idx, int32_t* n_surv);
+/* tau = 0.3 * mean_H - 0.1 * std_H (Sec. 4.3). Host-only helper. */
+float entropy_threshold(float mean_H, float std_H);
+
+/* Few-step head on n rows (Sec. 3.2 head, Sec. 4.2 few steps): S = n_steps sampler steps from
+ * x_{t_0} = temperature * eps[0]; mu = last x_0 estimate; x = mu + sigma_last * temperature * eps[S].
+ *   z storage type [n_max, d_cond]; n_rows device int32 [1] or NULL (= n_max): rows >= *n_rows are
+ *   skipped (so a survivor count can be passed without a host round trip);
+ *   eps fp32 [S+1, n_max, D]; mu, x fp32 [n_max, D]. */
+int diffhead_decode(fard_ctx* ctx, const void* z, const int32_t* n_rows, int32_t n_max,
+                    const float* eps, float* mu, float* x);
+
+/* Alg. 1 Step 1 for a batch: K sequential draft steps with the entropy early stop.
+ *   x_pending fp32 [B, D]; pending_id int32 [B] or NULL (>= 0: the pending token is an id row);
+ *   eps fp32 [S+1, B, K+1, D]; tau: threshold for this call.
+ * Outputs: H fp32 [B,K] (0 after a sample stopped); keep uint8 [B,K]; n_keep int32 [B];
+ *   x_draft, mu_q fp32 [B, K, D] (rows of dropped drafts are left untouched).
+ * The draft cache advances by one token per executed step; spec_kv_commit rolls it back. */
+int spec_draft(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id, const float* eps,
+               float tau, int32_t B, float* H, uint8_t* keep, int32_t* n_keep, float* x_draft,
+               float* mu_q);
+
+/* Alg. 1 Steps 2-4: target forward over [pending, x_1..x_K'] per sample (K' = n_keep[b]), head on
+ * all K'+1 rows with the shared noise, ratio and accept test.
+ *   log_sigma_factor = ln Sigma of S3 item 2; sigma_p, sigma_q: std of the last transition.
+ *   ln rho[b,i] = ln Sigma + D ln(sigma_q/sigma_p) - |x_i - mu_p,i|^2/(2 sigma_p^2) + |x_i - mu_q,i|^2/(2 sigma_q^2)
+ *   acc[b,i] = (ln r[b,i] <= ln rho[b,i]); n_accept[b] = leading run of acc within the first K'.
+ * Outputs: n_accept int32 [B]; log_ratio fp32 [B,K]; mu_p fp32 [B,K+1,D] (row K' is the bonus
+ *   distribution's mean; rows beyond are zero); z_p storage type [B,K+1,d_out] or NULL.
+ * The target cache is written for all K'+1 rows; lengths change only in spec_kv_commit. */
+int spec_verify(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id,
+                const float* x_draft, const float* mu_q, const int32_t* n_keep, const float* r,
+                const float* eps, float log_sigma_factor, float sigma_p, float sigma_q, int32_t B,
+                int32_t* n_accept, float* log_ratio, float* mu_p, void* z_p);
+
+/* The accept test alone (Alg. 1 Steps 3-4) on caller-provided means.  acc uint8 [B,K]. */
+int spec_accept(fard_ctx* ctx, const float* x_draft, const float* mu_p, const float* mu_q,
+                const float* r, const int32_t* n_keep, float log_sigma_factor, float sigma_p,
+                float sigma_q, int32_t B, int32_t* n_accept, float* log_ratio, uint8_t* acc);
+
+/* spec_draft + spec_verify + spec_kv_commit(both) in one call (one round of Alg. 1, Steps 1-4). */
+int spec_round(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id, const float* eps,
+               const float* r, float tau, float log_sigma_factor, float sigma_p, float sigma_q,
+               int32_t B, float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q,
+               int32_t* n_accept, float* log_ratio, float* mu_p);
+
+/* out = act(A W + b) through the library's GEMM kernel, for tests and kernel timing.
+ *   A storage type [M,K]; W storage type [K,N] row-major (re-laid on every call); bias fp32 [N] or
+ *   NULL; act: 0 none, 1 erf-GELU, 2 SiLU; out storage type [M,N].  bf16: K % 64 == 0, N % 32 == 0. */
+int spec_gemm(fard_ctx* ctx, const void* A, const void* W, const float* bias, int32_t M, int32_t K,
+              int32_t N, int32_t act, void* out);
+
+/* Per-kernel timing with HIP events on the context's stream.  enable = 1 brackets every launch of
+ * the named kernel class between two events; spec_profile_read synchronises and returns the
+ * accumulated time (ms) and launch count since enable, then clears them.
+ * class: 0 GEMM, 1 attention, 2 entropy, 3 everything else. */
+int spec_profile_enable(fard_ctx* ctx, int32_t enable);
+int spec_profile_read(fard_ctx* ctx, int32_t kernel_class, float* total_ms, int64_t* launches,
+                      double* flops, double* bytes);
+
+const char* spec_last_error(const fard_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTARDIFF_H */

@@ -1,0 +1,993 @@
+// C-ABI entry points and host-side orchestration of the speculative round (see include/fastardiff.h).
+// No kernel in this file touches the method's arithmetic except two tiny helpers (type conversion
+// at weight upload, cache-length commit); everything else is launched from gemm.hip, attn.hip,
+// rowops.hip.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/fastardiff.h"
+#include "gemm.h"
+#include "kernels.h"
+
+using namespace fard;
+
+namespace {
+
+// ------------------------------------------------------------------------------ small kernels
+template <typename TS, typename TD>
+__global__ void convert_kernel(const TS* __restrict__ src, TD* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = from_f32<TD>(to_f32(src[i]));
+}
+// dst[k, col0 + n] = src[k, n] for a [K, N] block placed inside a [K, ldd] matrix
+template <typename TS, typename TD>
+__global__ void place_kernel(const TS* __restrict__ src, TD* __restrict__ dst, int K, int N, int ldd, int col0) {
+  const size_t total = (size_t)K * N;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const size_t k = i / N, n = i - k * N;
+    dst[k * ldd + col0 + n] = from_f32<TD>(to_f32(src[i]));
+  }
+}
+__global__ void len_commit_kernel(int* len, const int* base, const int* n_accept, int cap_extra, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) {
+    int add = 1 + n_accept[b];
+    if (add > cap_extra) add = cap_extra;      // never beyond what was written this round
+    if (add < 1) add = 1;
+    len[b] = base[b] + add;
+  }
+}
+__global__ void copy_i32_kernel(const int* src, int* dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+__global__ void temb_feat_kernel(float t, float t_scale, int half, float* out) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k < half) {
+    const float omega = powf(10000.0f, -(float)k / (float)half);
+    const float arg = t * t_scale * omega;
+    out[k] = cosf(arg);
+    out[half + k] = sinf(arg);
+  }
+}
+__global__ void mean_heads_kernel(const float* __restrict__ ent_heads, int n_heads, float* __restrict__ out, int M,
+                                  const int* m_dev) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r < eff_rows(M, m_dev)) {
+    float s = 0.f;
+    for (int g = 0; g < n_heads; ++g) s += ent_heads[(size_t)r * n_heads + g];
+    out[r] = s / (float)n_heads;
+  }
+}
+
+// ------------------------------------------------------------------------------ context
+struct LayerW {
+  float *n1g = nullptr, *n1b = nullptr, *n2g = nullptr, *n2b = nullptr;
+  void *wqkv = nullptr, *wo = nullptr, *w1 = nullptr, *w2 = nullptr;   // w1 = up (GELU) or gate|up (SwiGLU), w2 = down
+  float *bqkv = nullptr, *bo = nullptr, *b1 = nullptr, *b2 = nullptr;
+};
+struct Model {
+  fard_tf_cfg c;
+  void *in_w = nullptr, *pos = nullptr, *cond = nullptr, *up = nullptr;
+  float *in_b = nullptr, *nfg = nullptr, *nfb = nullptr;
+  std::vector<LayerW> L;
+  void *kc = nullptr, *vc = nullptr;       // [layer][B][Hkv][ctx_pad][dh]
+  size_t layer_elems = 0;
+  int ctx_pad = 0;
+  int *len = nullptr, *len_base = nullptr; // device [max_batch]
+  int len_hi = 0;                          // host upper bound of any sample's length
+  int written = 0;                         // rows per sample written since len_base was recorded
+  int d_out() const { return c.d_out ? c.d_out : c.d_model; }
+  int qkv_n() const { return (c.n_heads + 2 * c.n_kv_heads) * c.d_head; }
+};
+struct BlockW {
+  void *w1 = nullptr, *w2 = nullptr;
+  float *b1 = nullptr, *b2 = nullptr;
+};
+struct HeadW {
+  void *in_w = nullptr, *c_w = nullptr, *mod_all = nullptr, *out_w = nullptr;
+  float *in_b = nullptr, *c_b = nullptr, *mod_b_all = nullptr, *out_b = nullptr, *temb = nullptr;
+  std::vector<BlockW> B;
+  int mod_n = 0;
+};
+struct Prof {
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+  std::vector<int> cls;
+  size_t used = 0;
+  double flops[4] = {0, 0, 0, 0}, bytes[4] = {0, 0, 0, 0};
+};
+
+}  // namespace
+
+struct fard_ctx {
+  fard_round_cfg cfg;
+  hipStream_t stream = nullptr;
+  int bf16 = 1;
+  size_t esz = 2;
+  int m_max = 0;
+  Model mdl[2];
+  HeadW head;
+  std::vector<void*> allocs;
+  std::string err;
+  Prof prof;
+  // workspace
+  float *h = nullptr, *x_in = nullptr, *ent_heads = nullptr, *h_row = nullptr;
+  void *u = nullptr, *qkv = nullptr, *ao = nullptr, *ff = nullptr, *z = nullptr, *ztmp = nullptr;
+  RowMaps maps{};
+  int *aux_row = nullptr, *row_ids = nullptr;
+  float* x_scratch = nullptr;
+  uint8_t* acc_tmp = nullptr;
+  float *cz = nullptr, *hh = nullptr, *mod = nullptr, *xt = nullptr;
+  void *sc = nullptr, *a1 = nullptr, *a2 = nullptr;
+  int *alive = nullptr, *act_idx = nullptr, *n_act = nullptr, *emap = nullptr, *omap = nullptr;
+  unsigned* ticket = nullptr;
+  void* gemm_tmp = nullptr;
+  size_t gemm_tmp_bytes = 0;
+};
+
+namespace {
+
+int fail(fard_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+#define HIPCHK(ctx, expr)                                                                      \
+  do {                                                                                         \
+    hipError_t e__ = (expr);                                                                   \
+    if (e__ != hipSuccess)                                                                     \
+      return fail(ctx, FARD_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));         \
+  } while (0)
+
+template <typename T>
+int dalloc(fard_ctx* c, T** p, size_t count) {
+  void* q = nullptr;
+  size_t bytes = count * sizeof(T);
+  if (bytes == 0) bytes = 16;
+  hipError_t e = hipMalloc(&q, bytes);
+  if (e != hipSuccess) return fail(c, FARD_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
+  c->allocs.push_back(q);
+  *p = (T*)q;
+  return FARD_OK;
+}
+int dalloc_bytes(fard_ctx* c, void** p, size_t bytes) {
+  char* q = nullptr;
+  int rc = dalloc<char>(c, &q, bytes);
+  *p = q;
+  return rc;
+}
+
+// Launch bracket: when profiling is on, every launch of a class sits between two events.
+struct Bracket {
+  fard_ctx* c;
+  int cls;
+  size_t slot = (size_t)-1;
+  Bracket(fard_ctx* ctx, int k, double fl = 0, double by = 0) : c(ctx), cls(k) {
+    Prof& p = c->prof;
+    if (!p.on) return;
+    if (p.used == p.pool.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+      p.pool.push_back({a, b});
+      p.cls.push_back(0);
+    }
+    slot = p.used++;
+    p.cls[slot] = k;
+    p.flops[k] += fl;
+    p.bytes[k] += by;
+    (void)hipEventRecord(p.pool[slot].first, c->stream);
+  }
+  ~Bracket() {
+    if (slot != (size_t)-1) (void)hipEventRecord(c->prof.pool[slot].second, c->stream);
+  }
+};
+enum { CLS_GEMM = 0, CLS_ATTN = 1, CLS_ENT = 2, CLS_OTHER = 3 };
+
+// ------------------------------------------------------------------------------ weight upload
+struct Loader {
+  fard_ctx* c;
+  std::map<std::string, const fard_tensor*> byname;
+  std::vector<void*> staging;
+
+  const fard_tensor* find(const std::string& n) const {
+    auto it = byname.find(n);
+    return it == byname.end() ? nullptr : it->second;
+  }
+  // device pointer to the tensor's data (uploads host tensors to a staging buffer)
+  int device_src(const fard_tensor* t, const void** out) {
+    if (t->on_device) { *out = t->data; return FARD_OK; }
+    const size_t bytes = (size_t)t->numel * (t->dtype == FARD_BF16 ? 2 : 4);
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+    if (e != hipSuccess) return fail(c, FARD_ENOMEM, "staging hipMalloc failed");
+    staging.push_back(p);
+    HIPCHK(c, hipMemcpy(p, t->data, bytes, hipMemcpyHostToDevice));
+    *out = p;
+    return FARD_OK;
+  }
+  void release_staging() {
+    (void)hipStreamSynchronize(c->stream);
+    for (void* p : staging) (void)hipFree(p);
+    staging.clear();
+  }
+  int need(const std::string& n, int64_t numel, const fard_tensor** out) {
+    const fard_tensor* t = find(n);
+    if (!t) return fail(c, FARD_EINVAL, "missing weight " + n);
+    if (t->numel != numel)
+      return fail(c, FARD_ESHAPE, "weight " + n + ": numel " + std::to_string(t->numel) + " != " + std::to_string(numel));
+    if (t->dtype != FARD_F32 && t->dtype != FARD_BF16) return fail(c, FARD_EINVAL, "weight " + n + ": bad dtype");
+    if (!t->data) return fail(c, FARD_EINVAL, "weight " + n + ": null data");
+    *out = t;
+    return FARD_OK;
+  }
+  // fp32 vector; optional (absent -> filled with `dflt`, or nullptr when allow_null)
+  int vec(const std::string& n, int64_t numel, float dflt, bool required, float** out) {
+    const fard_tensor* t = find(n);
+    if (!t) {
+      if (required) return fail(c, FARD_EINVAL, "missing weight " + n);
+      int rc = dalloc<float>(c, out, (size_t)numel);
+      if (rc) return rc;
+      HIPCHK(c, launch_fill_f32(c->stream, *out, dflt, (size_t)numel));
+      return FARD_OK;
+    }
+    int rc = need(n, numel, &t);
+    if (rc) return rc;
+    const void* src;
+    if ((rc = device_src(t, &src))) return rc;
+    if ((rc = dalloc<float>(c, out, (size_t)numel))) return rc;
+    const unsigned blocks = (unsigned)std::min<size_t>(((size_t)numel + 255) / 256, 4096);
+    if (t->dtype == FARD_BF16)
+      convert_kernel<bf16, float><<<blocks, 256, 0, c->stream>>>((const bf16*)src, *out, (size_t)numel);
+    else
+      convert_kernel<float, float><<<blocks, 256, 0, c->stream>>>((const float*)src, *out, (size_t)numel);
+    HIPCHK(c, hipGetLastError());
+    return FARD_OK;
+  }
+  // table in storage type, row-major as given
+  int table(const std::string& n, int64_t numel, void** out) {
+    const fard_tensor* t;
+    int rc = need(n, numel, &t);
+    if (rc) return rc;
+    const void* src;
+    if ((rc = device_src(t, &src))) return rc;
+    if ((rc = dalloc_bytes(c, out, (size_t)numel * c->esz))) return rc;
+    const unsigned blocks = (unsigned)std::min<size_t>(((size_t)numel + 255) / 256, 4096);
+    const size_t n_ = (size_t)numel;
+    if (c->bf16) {
+      if (t->dtype == FARD_BF16) convert_kernel<bf16, bf16><<<blocks, 256, 0, c->stream>>>((const bf16*)src, (bf16*)*out, n_);
+      else convert_kernel<float, bf16><<<blocks, 256, 0, c->stream>>>((const float*)src, (bf16*)*out, n_);
+    } else {
+      if (t->dtype == FARD_BF16) convert_kernel<bf16, float><<<blocks, 256, 0, c->stream>>>((const bf16*)src, (float*)*out, n_);
+      else convert_kernel<float, float><<<blocks, 256, 0, c->stream>>>((const float*)src, (float*)*out, n_);
+    }
+    HIPCHK(c, hipGetLastError());
+    return FARD_OK;
+  }
+  // GEMM operand: a list of [K, N_i] matrices laid side by side along N (interleave = 32-column
+  // blocks of two matrices alternate, for the SwiGLU epilogue).
+  int gemm_weight(const std::vector<std::string>& names, int K, const std::vector<int>& Ns, bool interleave, void** out) {
+    int Ntot = 0;
+    for (int n : Ns) Ntot += n;
+    int rc = dalloc_bytes(c, out, (size_t)K * Ntot * c->esz);
+    if (rc) return rc;
+    int col0 = 0;
+    for (size_t i = 0; i < names.size(); ++i) {
+      const fard_tensor* t;
+      if ((rc = need(names[i], (int64_t)K * Ns[i], &t))) return rc;
+      const void* src;
+      if ((rc = device_src(t, &src))) return rc;
+      if (c->bf16) {
+        if (K % 64 != 0 || Ns[i] % 32 != 0)
+          return fail(c, FARD_ESHAPE, "weight " + names[i] + ": bf16 GEMM needs K % 64 == 0 and N % 32 == 0");
+        const int off = interleave ? (int)i : col0 / 32;
+        const int stride = interleave ? (int)names.size() : 1;
+        HIPCHK(c, launch_pack_weight(c->stream, src, t->dtype == FARD_BF16, Ns[i], K, Ns[i], *out, off, stride));
+      } else {
+        const size_t total = (size_t)K * Ns[i];
+        const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 4096);
+        if (t->dtype == FARD_BF16)
+          place_kernel<bf16, float><<<blocks, 256, 0, c->stream>>>((const bf16*)src, (float*)*out, K, Ns[i], Ntot, col0);
+        else
+          place_kernel<float, float><<<blocks, 256, 0, c->stream>>>((const float*)src, (float*)*out, K, Ns[i], Ntot, col0);
+        HIPCHK(c, hipGetLastError());
+      }
+      col0 += Ns[i];
+      // keep peak staging memory low for the big models
+      if (staging.size() > 8) release_staging();
+    }
+    return FARD_OK;
+  }
+};
+
+int check_tf(fard_ctx* c, const fard_tf_cfg& t, const char* who) {
+  std::string w(who);
+  if (t.n_layers < 1 || t.d_model < 1 || t.n_heads < 1 || t.n_kv_heads < 1 || t.d_head < 1 || t.d_ff < 1 || t.d_latent < 1)
+    return fail(c, FARD_EINVAL, w + ": non-positive size");
+  if (t.n_heads % t.n_kv_heads != 0) return fail(c, FARD_ESHAPE, w + ": n_heads % n_kv_heads != 0");
+  if (t.d_latent > 16) return fail(c, FARD_ESHAPE, w + ": d_latent > 16 unsupported");
+  if (t.d_head % 2 != 0) return fail(c, FARD_ESHAPE, w + ": odd d_head");
+  if (c->bf16) {
+    if (t.d_head != 32 && t.d_head != 64 && t.d_head != 128) return fail(c, FARD_ESHAPE, w + ": bf16 d_head must be 32, 64 or 128");
+    if (t.d_model % 64 != 0 || t.d_ff % 64 != 0 || (t.n_heads * t.d_head) % 64 != 0)
+      return fail(c, FARD_ESHAPE, w + ": bf16 widths must be multiples of 64");
+    if (t.d_out && t.d_out % 32 != 0) return fail(c, FARD_ESHAPE, w + ": d_out % 32 != 0");
+  }
+  if (t.act != FARD_ACT_GELU && t.act != FARD_ACT_SWIGLU) return fail(c, FARD_EINVAL, w + ": act");
+  if (t.norm != FARD_NORM_LAYER && t.norm != FARD_NORM_RMS) return fail(c, FARD_EINVAL, w + ": norm");
+  if (t.pos != FARD_POS_LEARNED && t.pos != FARD_POS_ROPE) return fail(c, FARD_EINVAL, w + ": pos");
+  if (t.pos == FARD_POS_LEARNED && t.max_pos < 1) return fail(c, FARD_EINVAL, w + ": learned positions need max_pos");
+  return FARD_OK;
+}
+
+int load_model(fard_ctx* c, Loader& ld, int which) {
+  Model& m = c->mdl[which];
+  const fard_tf_cfg& t = m.c;
+  const std::string p = which == FARD_TARGET ? "target." : "draft.";
+  const int d = t.d_model, F = t.d_ff, D = t.d_latent, HD = t.n_heads * t.d_head, QN = m.qkv_n();
+  int rc;
+  if ((rc = ld.table(p + "in.w", (int64_t)D * d, &m.in_w))) return rc;
+  if ((rc = ld.vec(p + "in.b", d, 0.f, false, &m.in_b))) return rc;
+  if (t.pos == FARD_POS_LEARNED && (rc = ld.table(p + "pos", (int64_t)t.max_pos * d, &m.pos))) return rc;
+  if (t.n_cond_ids > 0 && (rc = ld.table(p + "cond", (int64_t)t.n_cond_ids * d, &m.cond))) return rc;
+  m.L.resize(t.n_layers);
+  const bool ln = t.norm == FARD_NORM_LAYER;
+  for (int i = 0; i < t.n_layers; ++i) {
+    LayerW& L = m.L[i];
+    const std::string q = p + "L" + std::to_string(i) + ".";
+    if ((rc = ld.vec(q + "n1.g", d, 1.f, false, &L.n1g))) return rc;
+    if ((rc = ld.vec(q + "n2.g", d, 1.f, false, &L.n2g))) return rc;
+    if (ln) {
+      if ((rc = ld.vec(q + "n1.b", d, 0.f, false, &L.n1b))) return rc;
+      if ((rc = ld.vec(q + "n2.b", d, 0.f, false, &L.n2b))) return rc;
+    }
+    if ((rc = ld.gemm_weight({q + "wqkv"}, d, {QN}, false, &L.wqkv))) return rc;
+    if ((rc = ld.gemm_weight({q + "wo"}, HD, {d}, false, &L.wo))) return rc;
+    if (t.has_bias) {
+      if ((rc = ld.vec(q + "bqkv", QN, 0.f, false, &L.bqkv))) return rc;
+      if ((rc = ld.vec(q + "bo", d, 0.f, false, &L.bo))) return rc;
+    }
+    if (t.act == FARD_ACT_GELU) {
+      if ((rc = ld.gemm_weight({q + "w1"}, d, {F}, false, &L.w1))) return rc;
+      if ((rc = ld.gemm_weight({q + "w2"}, F, {d}, false, &L.w2))) return rc;
+      if (t.has_bias) {
+        if ((rc = ld.vec(q + "b1", F, 0.f, false, &L.b1))) return rc;
+        if ((rc = ld.vec(q + "b2", d, 0.f, false, &L.b2))) return rc;
+      }
+    } else {
+      if ((rc = ld.gemm_weight({q + "wg", q + "wu"}, d, {F, F}, true, &L.w1))) return rc;
+      if ((rc = ld.gemm_weight({q + "wd"}, F, {d}, false, &L.w2))) return rc;
+    }
+  }
+  if ((rc = ld.vec(p + "nf.g", d, 1.f, false, &m.nfg))) return rc;
+  if (ln && (rc = ld.vec(p + "nf.b", d, 0.f, false, &m.nfb))) return rc;
+  if (t.d_out && t.d_out != d && (rc = ld.gemm_weight({p + "up.w"}, d, {t.d_out}, false, &m.up))) return rc;
+
+  // KV cache, zeroed: masked positions multiply V by an exact 0, which needs finite V
+  m.ctx_pad = c->bf16 ? ((c->cfg.max_ctx + 31) / 32) * 32 : c->cfg.max_ctx;
+  m.layer_elems = (size_t)c->cfg.max_batch * t.n_kv_heads * m.ctx_pad * t.d_head;
+  const size_t bytes = m.layer_elems * t.n_layers * c->esz;
+  if ((rc = dalloc_bytes(c, &m.kc, bytes))) return rc;
+  if ((rc = dalloc_bytes(c, &m.vc, bytes))) return rc;
+  HIPCHK(c, hipMemsetAsync(m.kc, 0, bytes, c->stream));
+  HIPCHK(c, hipMemsetAsync(m.vc, 0, bytes, c->stream));
+  if ((rc = dalloc<int>(c, &m.len, c->cfg.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &m.len_base, c->cfg.max_batch))) return rc;
+  HIPCHK(c, launch_fill_i32(c->stream, m.len, 0, c->cfg.max_batch));
+  HIPCHK(c, launch_fill_i32(c->stream, m.len_base, 0, c->cfg.max_batch));
+  m.len_hi = 0;
+  return FARD_OK;
+}
+
+hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, void* out, int ldo, int M,
+                int N, int K, const int* m_dev, int epi, int act, const float* gate = nullptr, int ldg = 0) {
+  GemmArgs a;
+  a.A = A; a.lda = lda; a.W = W; a.bias = bias; a.out = out; a.ldo = ldo; a.gate = gate; a.ldg = ldg;
+  a.M = M; a.N = N; a.K = K; a.m_dev = m_dev; a.act = act; a.epi = epi;
+  const double fl = 2.0 * M * (double)N * K;
+  const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
+  Bracket br(c, CLS_GEMM, fl, by);
+  return c->bf16 ? launch_gemm_bf16(c->stream, a) : launch_gemm_f32(c->stream, a);
+}
+
+int load_head(fard_ctx* c, Loader& ld) {
+  const fard_head_cfg& hc = c->cfg.head;
+  HeadW& hw = c->head;
+  const int w = hc.width, D = hc.d_latent, Nb = hc.n_blocks, S = hc.n_steps;
+  int rc;
+  if ((rc = ld.table("head.in.w", (int64_t)D * w, &hw.in_w))) return rc;
+  if ((rc = ld.vec("head.in.b", w, 0.f, false, &hw.in_b))) return rc;
+  if ((rc = ld.gemm_weight({"head.c.w"}, hc.d_cond, {w}, false, &hw.c_w))) return rc;
+  if ((rc = ld.vec("head.c.b", w, 0.f, false, &hw.c_b))) return rc;
+  // all modulation projections share their input silu(c): one wide GEMM [w, (3 Nb + 2) w]
+  std::vector<std::string> names;
+  std::vector<int> Ns;
+  for (int j = 0; j < Nb; ++j) { names.push_back("head.B" + std::to_string(j) + ".mod.w"); Ns.push_back(3 * w); }
+  names.push_back("head.f.mod.w");
+  Ns.push_back(2 * w);
+  hw.mod_n = (3 * Nb + 2) * w;
+  if ((rc = ld.gemm_weight(names, w, Ns, false, &hw.mod_all))) return rc;
+  if ((rc = dalloc<float>(c, &hw.mod_b_all, hw.mod_n))) return rc;
+  HIPCHK(c, launch_fill_f32(c->stream, hw.mod_b_all, 0.f, hw.mod_n));
+  for (int j = 0; j <= Nb; ++j) {
+    const std::string n = j < Nb ? "head.B" + std::to_string(j) + ".mod.b" : std::string("head.f.mod.b");
+    const int cnt = j < Nb ? 3 * w : 2 * w;
+    if (!ld.find(n)) continue;
+    float* tmp;
+    if ((rc = ld.vec(n, cnt, 0.f, true, &tmp))) return rc;
+    HIPCHK(c, hipMemcpyAsync(hw.mod_b_all + (size_t)3 * w * j, tmp, (size_t)cnt * 4, hipMemcpyDeviceToDevice, c->stream));
+  }
+  hw.B.resize(Nb);
+  for (int j = 0; j < Nb; ++j) {
+    const std::string q = "head.B" + std::to_string(j) + ".";
+    if ((rc = ld.gemm_weight({q + "w1"}, w, {w}, false, &hw.B[j].w1))) return rc;
+    if ((rc = ld.gemm_weight({q + "w2"}, w, {w}, false, &hw.B[j].w2))) return rc;
+    if ((rc = ld.vec(q + "b1", w, 0.f, false, &hw.B[j].b1))) return rc;
+    if ((rc = ld.vec(q + "b2", w, 0.f, false, &hw.B[j].b2))) return rc;
+  }
+  if ((rc = ld.table("head.out.w", (int64_t)w * D, &hw.out_w))) return rc;
+  if ((rc = ld.vec("head.out.b", D, 0.f, false, &hw.out_b))) return rc;
+
+  // time embedding of the S fixed sampler times t_k = 1 - k/S, computed once
+  void *t1w, *t2w;
+  float *t1b, *t2b, *feat, *hid;
+  if ((rc = ld.table("head.t1.w", (int64_t)hc.t_freq_dim * w, &t1w))) return rc;
+  if ((rc = ld.table("head.t2.w", (int64_t)w * w, &t2w))) return rc;
+  if ((rc = ld.vec("head.t1.b", w, 0.f, false, &t1b))) return rc;
+  if ((rc = ld.vec("head.t2.b", w, 0.f, false, &t2b))) return rc;
+  if ((rc = dalloc<float>(c, &feat, hc.t_freq_dim))) return rc;
+  if ((rc = dalloc<float>(c, &hid, w))) return rc;
+  if ((rc = dalloc<float>(c, &hw.temb, (size_t)S * w))) return rc;
+  for (int k = 0; k < S; ++k) {
+    const float t = 1.0f - (float)k / (float)S;
+    const int half = hc.t_freq_dim / 2;
+    temb_feat_kernel<<<(half + 255) / 256, 256, 0, c->stream>>>(t, hc.t_scale, half, feat);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, launch_matvec(c->stream, c->bf16, feat, t1w, t1b, hc.t_freq_dim, w, ACT_SILU, hid));
+    HIPCHK(c, launch_matvec(c->stream, c->bf16, hid, t2w, t2b, w, w, ACT_NONE, hw.temb + (size_t)k * w));
+  }
+  return FARD_OK;
+}
+
+int alloc_workspace(fard_ctx* c) {
+  const fard_round_cfg& g = c->cfg;
+  const int M = c->m_max;
+  int dmax = 0, qmax = 0, hdmax = 0, fmax = 0, omax = 0, hmax = 0;
+  for (int i = 0; i < 2; ++i) {
+    const Model& m = c->mdl[i];
+    dmax = std::max(dmax, m.c.d_model);
+    qmax = std::max(qmax, m.qkv_n());
+    hdmax = std::max(hdmax, m.c.n_heads * m.c.d_head);
+    fmax = std::max(fmax, m.c.d_ff);
+    omax = std::max(omax, m.d_out());
+    hmax = std::max(hmax, m.c.n_heads);
+  }
+  const int w = g.head.width, D = g.head.d_latent;
+  int rc;
+  if ((rc = dalloc<float>(c, &c->h, (size_t)M * dmax))) return rc;
+  if ((rc = dalloc<float>(c, &c->x_in, (size_t)M * 16))) return rc;
+  if ((rc = dalloc<float>(c, &c->ent_heads, (size_t)M * hmax))) return rc;
+  if ((rc = dalloc<float>(c, &c->h_row, (size_t)M))) return rc;
+  if ((rc = dalloc_bytes(c, &c->u, (size_t)M * dmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->qkv, (size_t)M * qmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ao, (size_t)M * hdmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ff, (size_t)M * fmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->z, (size_t)M * omax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ztmp, (size_t)M * dmax * c->esz))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_start, g.max_batch + 2))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_sample, M))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_j, M))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_pos, M))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.m_total, 4))) return rc;
+  if ((rc = dalloc<int>(c, &c->aux_row, M))) return rc;
+  if ((rc = dalloc<int>(c, &c->row_ids, M))) return rc;
+  if ((rc = dalloc<float>(c, &c->x_scratch, (size_t)M * 16))) return rc;
+  if ((rc = dalloc<uint8_t>(c, &c->acc_tmp, (size_t)g.max_batch * g.K))) return rc;
+  if ((rc = dalloc<float>(c, &c->cz, (size_t)M * w))) return rc;
+  if ((rc = dalloc<float>(c, &c->hh, (size_t)M * w))) return rc;
+  if ((rc = dalloc<float>(c, &c->mod, (size_t)M * c->head.mod_n))) return rc;
+  if ((rc = dalloc<float>(c, &c->xt, (size_t)M * D))) return rc;
+  if ((rc = dalloc_bytes(c, &c->sc, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->a1, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->a2, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc<int>(c, &c->alive, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->act_idx, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->n_act, 4))) return rc;
+  if ((rc = dalloc<int>(c, &c->emap, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->omap, g.max_batch))) return rc;
+  if ((rc = dalloc<unsigned>(c, &c->ticket, 4))) return rc;
+  HIPCHK(c, hipMemsetAsync(c->ticket, 0, 16, c->stream));
+  return FARD_OK;
+}
+
+KvGeom kv_geom(fard_ctx* c, Model& m, int layer) {
+  KvGeom g;
+  g.k = (char*)m.kc + (size_t)layer * m.layer_elems * c->esz;
+  g.v = (char*)m.vc + (size_t)layer * m.layer_elems * c->esz;
+  g.n_kv_heads = m.c.n_kv_heads;
+  g.d_head = m.c.d_head;
+  g.ctx_pad = m.ctx_pad;
+  g.is_bf16 = c->bf16;
+  return g;
+}
+
+// Layers [l0, l1) of one model over the packed rows described by c->maps (h in, h out).
+int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max, const int* m_dev, int ent_layer) {
+  Model& m = c->mdl[which];
+  const fard_tf_cfg& t = m.c;
+  hipStream_t s = c->stream;
+  const int d = t.d_model, F = t.d_ff, HD = t.n_heads * t.d_head, QN = m.qkv_n();
+  for (int l = l0; l < l1; ++l) {
+    const LayerW& L = m.L[l];
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, nullptr, nullptr, 0, nullptr, c->u)); }
+    HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
+    KvGeom kg = kv_geom(c, m, l);
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE, t.rope_theta, c->maps.row_sample,
+                                   c->maps.row_pos, M, m_dev)); }
+    { Bracket br(c, CLS_ATTN);
+      HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, m.len, c->maps.row_start, B, nq_max, c->ao, HD,
+                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr)); }
+    HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u)); }
+    if (t.act == FARD_ACT_GELU) {
+      HIPCHK(c, gemm(c, c->u, d, L.w1, L.b1, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU));
+    } else {
+      HIPCHK(c, gemm(c, c->u, d, L.w1, nullptr, c->ff, F, M, 2 * F, d, m_dev, EPI_SWIGLU, ACT_NONE));
+    }
+    HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
+  }
+  return FARD_OK;
+}
+
+// Final norm (optionally gathering rows through in_map) and up-projection -> z [n, d_out] storage type.
+int run_final(fard_ctx* c, int which, int n, const int* n_dev, const int* in_map, void* z_out) {
+  Model& m = c->mdl[which];
+  const fard_tf_cfg& t = m.c;
+  const bool up = m.up != nullptr;
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_norm(c->stream, c->bf16, c->h, t.d_model, n, n_dev, t.norm, t.norm_eps, m.nfg, m.nfb, nullptr, nullptr,
+                          0, in_map, up ? c->ztmp : z_out)); }
+  if (up) HIPCHK(c, gemm(c, c->ztmp, t.d_model, m.up, nullptr, z_out, t.d_out, n, t.d_out, t.d_model, n_dev, EPI_STORE, ACT_NONE));
+  return FARD_OK;
+}
+
+int cap_nq(const fard_ctx* c, int which) {
+  const fard_tf_cfg& t = c->mdl[which].c;
+  return c->bf16 ? 64 / (t.n_heads / t.n_kv_heads) : 1 << 20;
+}
+
+// S sampler steps of the head over n rows of z (compact), noise / output rows through emap / omap.
+int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* eps, size_t eps_step_stride,
+             const int* emap, const int* omap, float* mu, float* x) {
+  const fard_head_cfg& hc = c->cfg.head;
+  HeadW& hw = c->head;
+  hipStream_t s = c->stream;
+  const int w = hc.width, D = hc.d_latent, Nb = hc.n_blocks, S = hc.n_steps;
+  HIPCHK(c, gemm(c, z, hc.d_cond, hw.c_w, hw.c_b, c->cz, w, n, w, hc.d_cond, n_dev, EPI_STORE_F32, ACT_NONE));
+  for (int k = 0; k < S; ++k) {
+    const float t = 1.0f - (float)k / (float)S;
+    const float t_next = 1.0f - (float)(k + 1) / (float)S;
+    { Bracket br(c, CLS_OTHER);
+      if (k == 0)
+        HIPCHK(c, launch_head_prep(s, c->bf16, eps, emap, hc.temperature, D, hw.in_w, hw.in_b, c->cz, hw.temb, c->hh, c->sc,
+                                   c->xt, w, n, n_dev));
+      else
+        HIPCHK(c, launch_head_prep(s, c->bf16, c->xt, nullptr, 1.0f, D, hw.in_w, hw.in_b, c->cz, hw.temb + (size_t)k * w,
+                                   c->hh, c->sc, nullptr, w, n, n_dev)); }
+    HIPCHK(c, gemm(c, c->sc, w, hw.mod_all, hw.mod_b_all, c->mod, hw.mod_n, n, hw.mod_n, w, n_dev, EPI_STORE_F32, ACT_NONE));
+    for (int j = 0; j < Nb; ++j) {
+      const float* mj = c->mod + (size_t)3 * w * j;
+      { Bracket br(c, CLS_OTHER);
+        HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1)); }
+      HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
+      HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n));
+    }
+    HeadStepArgs a;
+    a.hh = c->hh; a.w = w;
+    a.shift = c->mod + (size_t)3 * w * Nb; a.scale = a.shift + w; a.ldm = hw.mod_n;
+    a.w_out = hw.out_w; a.b_out = hw.out_b; a.D = D;
+    a.xt = c->xt;
+    a.eps_next = eps + (size_t)(k + 1) * eps_step_stride;
+    a.emap = emap; a.omap = omap;
+    a.t = t; a.t_next = t_next;
+    a.last = (k == S - 1);
+    a.renoise = hc.renoise;
+    a.sigma = hc.sigma_last * hc.temperature;
+    a.mu = mu; a.x = x;
+    a.n = n; a.n_dev = n_dev;
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_head_out(s, c->bf16, a)); }
+  }
+  return FARD_OK;
+}
+
+int check_ctx(fard_ctx* c) { return c ? FARD_OK : FARD_EINVAL; }
+
+}  // namespace
+
+// ====================================================================================== C ABI
+extern "C" {
+
+int spec_round_init(const fard_round_cfg* cfg, const fard_tensor* weights, int32_t n_weights, void* hip_stream,
+                    fard_ctx** out) {
+  if (!cfg || !out || (!weights && n_weights > 0) || n_weights < 0) return FARD_EINVAL;
+  *out = nullptr;
+  fard_ctx* c = new (std::nothrow) fard_ctx();
+  if (!c) return FARD_ENOMEM;
+  c->cfg = *cfg;
+  c->stream = (hipStream_t)hip_stream;
+  int rc = FARD_OK;
+  auto bail = [&](int code) {
+    // keep the message reachable: the caller gets no context on failure, so print it
+    fprintf(stderr, "spec_round_init: %s\n", c->err.c_str());
+    for (void* p : c->allocs) (void)hipFree(p);
+    delete c;
+    return code;
+  };
+  if (cfg->dtype != FARD_F32 && cfg->dtype != FARD_BF16) return bail(fail(c, FARD_EINVAL, "dtype"));
+  c->bf16 = cfg->dtype == FARD_BF16;
+  c->esz = c->bf16 ? 2 : 4;
+  if (cfg->K < 1 || cfg->K > 64 || cfg->max_batch < 1 || cfg->max_ctx < cfg->K + 1)
+    return bail(fail(c, FARD_EINVAL, "K in [1,64], max_batch >= 1, max_ctx >= K+1 required"));
+  if (cfg->prefix_rule != 1) return bail(fail(c, FARD_EINVAL, "prefix_rule must be 1"));
+  if (cfg->entropy_mode != FARD_ENT_FEATURE && cfg->entropy_mode != FARD_ENT_ATTN) return bail(fail(c, FARD_EINVAL, "entropy_mode"));
+  if (cfg->entropy_layer < 1 || cfg->entropy_layer > cfg->draft.n_layers) return bail(fail(c, FARD_EINVAL, "entropy_layer outside the draft"));
+  c->mdl[0].c = cfg->target;
+  c->mdl[1].c = cfg->draft;
+  if ((rc = check_tf(c, cfg->target, "target")) || (rc = check_tf(c, cfg->draft, "draft"))) return bail(rc);
+  const fard_head_cfg& hc = cfg->head;
+  if (hc.n_blocks < 1 || hc.width < 1 || hc.n_steps < 1 || hc.t_freq_dim < 2 || hc.t_freq_dim % 2)
+    return bail(fail(c, FARD_EINVAL, "head sizes"));
+  if (hc.d_latent != cfg->target.d_latent || hc.d_latent != cfg->draft.d_latent) return bail(fail(c, FARD_ESHAPE, "d_latent differs"));
+  if (hc.d_cond != c->mdl[0].d_out() || hc.d_cond != c->mdl[1].d_out())
+    return bail(fail(c, FARD_ESHAPE, "head.d_cond must equal both models' feature width"));
+  if (c->bf16 && (hc.width % 64 != 0 || hc.d_cond % 64 != 0)) return bail(fail(c, FARD_ESHAPE, "bf16 head widths must be multiples of 64"));
+  if (!(hc.sigma_last > 0.f)) return bail(fail(c, FARD_EINVAL, "sigma_last must be > 0"));
+  c->m_max = cfg->max_batch * (cfg->K + 1);
+
+  Loader ld;
+  ld.c = c;
+  for (int i = 0; i < n_weights; ++i) {
+    if (!weights[i].name) return bail(fail(c, FARD_EINVAL, "unnamed weight"));
+    ld.byname[weights[i].name] = &weights[i];
+  }
+  if ((rc = load_model(c, ld, FARD_TARGET)) || (rc = load_model(c, ld, FARD_DRAFT)) || (rc = load_head(c, ld)) ||
+      (rc = alloc_workspace(c))) {
+    ld.release_staging();
+    return bail(rc);
+  }
+  ld.release_staging();
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return bail(fail(c, FARD_EHIP, std::string("init sync: ") + hipGetErrorString(e)));
+  *out = c;
+  return FARD_OK;
+}
+
+int spec_round_destroy(fard_ctx* c) {
+  if (!c) return FARD_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto& ev : c->prof.pool) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
+  if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
+  for (void* p : c->allocs) (void)hipFree(p);
+  delete c;
+  return FARD_OK;
+}
+
+const char* spec_last_error(const fard_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+float entropy_threshold(float mean_H, float std_H) { return 0.3f * mean_H - 0.1f * std_H; }
+
+int spec_kv_reset(fard_ctx* c, int32_t which, const int32_t* cache_len, int32_t B) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  Model& m = c->mdl[which];
+  int hi = 0;
+  if (cache_len) {
+    for (int b = 0; b < B; ++b) {
+      if (cache_len[b] < 0 || cache_len[b] > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "cache_len outside [0, max_ctx]");
+      hi = std::max(hi, cache_len[b]);
+    }
+    HIPCHK(c, hipMemcpyAsync(m.len, cache_len, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));   // the host array may go away after return
+  } else {
+    HIPCHK(c, launch_fill_i32(c->stream, m.len, 0, c->cfg.max_batch));
+  }
+  m.len_hi = hi;
+  m.written = 0;
+  return FARD_OK;
+}
+
+int spec_kv_load(fard_ctx* c, int32_t which, int32_t layer, const void* k, const void* v, int32_t B, int32_t n) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
+  Model& m = c->mdl[which];
+  if (layer < 0 || layer >= m.c.n_layers) return fail(c, FARD_EINVAL, "layer");
+  if (B < 0 || B > c->cfg.max_batch || n < 0 || n > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "B or n beyond capacity");
+  if (B == 0 || n == 0) return FARD_OK;
+  if (!k || !v) return fail(c, FARD_EINVAL, "null k/v");
+  HIPCHK(c, launch_kv_load(c->stream, kv_geom(c, m, layer), k, v, B, n));
+  return FARD_OK;
+}
+
+int spec_kv_lengths(fard_ctx* c, int32_t which, int32_t* out_host, int32_t B) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if ((which != FARD_TARGET && which != FARD_DRAFT) || !out_host) return fail(c, FARD_EINVAL, "which/out");
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  HIPCHK(c, hipMemcpyAsync(out_host, c->mdl[which].len, (size_t)B * 4, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return FARD_OK;
+}
+
+int spec_kv_commit(fard_ctx* c, int32_t which, const int32_t* n_accept, int32_t B) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (!n_accept) return fail(c, FARD_EINVAL, "n_accept");
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (B == 0) return FARD_OK;
+  for (int w = 0; w < 2; ++w) {
+    if (which != -1 && which != w) continue;
+    Model& m = c->mdl[w];
+    if (m.written < 1) return fail(c, FARD_ESTATE, "spec_kv_commit without a preceding spec_draft / spec_verify");
+    len_commit_kernel<<<(B + 255) / 256, 256, 0, c->stream>>>(m.len, m.len_base, n_accept, m.written, B);
+    HIPCHK(c, hipGetLastError());
+    m.written = 0;
+  }
+  return FARD_OK;
+}
+
+int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* cond_id, const int32_t* n_q, int32_t nq_max,
+                 int32_t B, int32_t M, int32_t commit, void* z_out, float* shallow_out, float* h_attn_out) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (M < 0 || M > c->m_max) return fail(c, FARD_ECAPACITY, "M > max_batch*(K+1)");
+  if (B == 0 || M == 0) return FARD_OK;
+  if (!x_in || !n_q || !z_out) return fail(c, FARD_EINVAL, "null x_in / n_q / z_out");
+  Model& m = c->mdl[which];
+  if (cond_id && !m.cond) return fail(c, FARD_EINVAL, "cond_id given but the model has no id table");
+  if (nq_max < 1) return fail(c, FARD_EINVAL, "nq_max < 1");
+  if (nq_max > cap_nq(c, which)) return fail(c, FARD_ESHAPE, "nq_max * (n_heads / n_kv_heads) > 64");
+  const int cap = std::min(nq_max, M);
+  if (m.len_hi + cap > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "cache_len + n_q may exceed max_ctx");
+  if (m.c.pos == FARD_POS_LEARNED && m.len_hi + cap > m.c.max_pos) return fail(c, FARD_ECAPACITY, "position beyond the learned table");
+  hipStream_t s = c->stream;
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_build_rows(s, n_q, 0, B, c->cfg.K, m.c.d_latent, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, M, cap)); }
+  const int* md = c->maps.m_total;
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_embed(s, c->bf16, x_in, m.c.d_latent, m.c.d_latent, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, cond_id,
+                           c->h, m.c.d_model, M, md)); }
+  const int ls = c->cfg.entropy_layer;
+  const bool want_sh = (shallow_out || h_attn_out) && ls <= m.c.n_layers;
+  int rc;
+  if (want_sh) {
+    if ((rc = run_layers(c, which, 0, ls, B, M, cap, md, h_attn_out ? ls : 0))) return rc;
+    if (shallow_out) {
+      Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_scatter_rows(s, c->h, shallow_out, nullptr, m.c.d_model, 4, M, md));
+    }
+    if (h_attn_out) {
+      Bracket br(c, CLS_ENT);
+      mean_heads_kernel<<<(M + 255) / 256, 256, 0, s>>>(c->ent_heads, m.c.n_heads, h_attn_out, M, md);
+      HIPCHK(c, hipGetLastError());
+    }
+    if ((rc = run_layers(c, which, ls, m.c.n_layers, B, M, cap, md, 0))) return rc;
+  } else {
+    if ((rc = run_layers(c, which, 0, m.c.n_layers, B, M, cap, md, 0))) return rc;
+  }
+  if ((rc = run_final(c, which, M, md, nullptr, z_out))) return rc;
+  if (commit) {
+    HIPCHK(c, launch_len_add(s, m.len, n_q, 0, B));
+    m.len_hi += cap;
+  }
+  return FARD_OK;
+}
+
+int entropy_prefilter(fard_ctx* c, const void* feat, int32_t B, int32_t K, int32_t L, float tau, float* H, uint8_t* keep,
+                      int32_t* n_keep, int32_t* surv_idx, int32_t* n_surv) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B < 0 || K < 0 || L < 1) return fail(c, FARD_ESHAPE, "B, K >= 0 and L >= 1 required");
+  if (!n_surv) return fail(c, FARD_EINVAL, "null n_surv");
+  if ((long)B * K == 0) {
+    HIPCHK(c, launch_fill_i32(c->stream, n_surv, 0, 1));
+    if (B > 0 && n_keep) HIPCHK(c, launch_fill_i32(c->stream, n_keep, 0, B));
+    return FARD_OK;
+  }
+  if (!feat || !H || !keep || !n_keep || !surv_idx) return fail(c, FARD_EINVAL, "null argument");
+  Bracket br(c, CLS_ENT, 0, (double)B * K * L * c->esz);
+  HIPCHK(c, launch_entropy_prefilter(c->stream, c->bf16, feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, c->ticket));
+  return FARD_OK;
+}
+
+int diffhead_decode(fard_ctx* c, const void* z, const int32_t* n_rows, int32_t n_max, const float* eps, float* mu, float* x) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (n_max < 0 || n_max > c->m_max) return fail(c, FARD_ECAPACITY, "n_max > max_batch*(K+1)");
+  if (n_max == 0) return FARD_OK;
+  if (!z || !eps || !mu || !x) return fail(c, FARD_EINVAL, "null argument");
+  return run_head(c, z, n_max, n_rows, eps, (size_t)n_max * c->cfg.head.d_latent, nullptr, nullptr, mu, x);
+}
+
+int spec_accept(fard_ctx* c, const float* x_draft, const float* mu_p, const float* mu_q, const float* r, const int32_t* n_keep,
+                float log_sigma_factor, float sigma_p, float sigma_q, int32_t B, int32_t* n_accept, float* log_ratio,
+                uint8_t* acc) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B < 0) return fail(c, FARD_ESHAPE, "B < 0");
+  if (B == 0) return FARD_OK;
+  if (!x_draft || !mu_p || !mu_q || !r || !n_keep || !n_accept || !log_ratio || !acc) return fail(c, FARD_EINVAL, "null argument");
+  if (!(sigma_p > 0.f) || !(sigma_q > 0.f)) return fail(c, FARD_EINVAL, "sigma must be > 0");
+  Bracket br(c, CLS_OTHER);
+  HIPCHK(c, launch_accept(c->stream, x_draft, mu_p, mu_q, r, n_keep, log_sigma_factor, sigma_p, sigma_q, B, c->cfg.K,
+                          c->cfg.head.d_latent, n_accept, log_ratio, acc));
+  return FARD_OK;
+}
+
+int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, float tau, int32_t B,
+               float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (B == 0) return FARD_OK;
+  if (!x_pending || !eps || !H || !keep || !n_keep || !x_draft || !mu_q) return fail(c, FARD_EINVAL, "null argument");
+  Model& m = c->mdl[FARD_DRAFT];
+  if (pending_id && !m.cond) return fail(c, FARD_EINVAL, "pending_id given but the draft has no id table");
+  const int K = c->cfg.K, D = m.c.d_latent, d = m.c.d_model, ls = c->cfg.entropy_layer;
+  if (m.len_hi + K > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "draft cache_len + K exceeds max_ctx");
+  if (m.c.pos == FARD_POS_LEARNED && m.len_hi + K > m.c.max_pos) return fail(c, FARD_ECAPACITY, "draft position beyond the learned table");
+  hipStream_t s = c->stream;
+  const size_t eps_stride = (size_t)B * (K + 1) * D;
+  int rc;
+  { Bracket br(c, CLS_OTHER);
+    copy_i32_kernel<<<(B + 255) / 256, 256, 0, s>>>(m.len, m.len_base, B);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, launch_fill_i32(s, c->alive, 1, B));
+    HIPCHK(c, launch_fill_i32(s, n_keep, 0, B));
+    // dropped drafts keep finite values: they still travel through the dense draft rows
+    HIPCHK(c, launch_fill_f32(s, x_draft, 0.f, (size_t)B * K * D));
+    HIPCHK(c, launch_fill_f32(s, mu_q, 0.f, (size_t)B * K * D)); }
+  for (int i = 0; i < K; ++i) {
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_build_rows(s, nullptr, 1, B, K, D, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, B, 1)); }
+    const float* xs = (i == 0) ? x_pending : x_draft + (size_t)(i - 1) * D;
+    const int ldx = (i == 0) ? D : K * D;
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_embed(s, c->bf16, xs, ldx, D, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, i == 0 ? pending_id : nullptr,
+                             c->h, d, B, nullptr)); }
+    const bool attn_mode = c->cfg.entropy_mode == FARD_ENT_ATTN;
+    if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0))) return rc;
+    { Bracket br(c, CLS_ENT, 0, (double)B * d * 4);
+      if (!attn_mode) HIPCHK(c, launch_entropy_rows_f32(s, c->h, d, B, d, c->h_row));
+      HIPCHK(c, launch_entropy_step(s, attn_mode ? c->ent_heads : nullptr, m.c.n_heads, c->h_row, B, K, i, tau, H, keep, c->alive,
+                                    n_keep, c->act_idx, c->n_act, c->emap, c->omap)); }
+    if ((rc = run_layers(c, FARD_DRAFT, ls, m.c.n_layers, B, B, 1, nullptr, 0))) return rc;
+    // only samples that are still speculating reach the head
+    if ((rc = run_final(c, FARD_DRAFT, B, c->n_act, c->act_idx, c->z))) return rc;
+    if ((rc = run_head(c, c->z, B, c->n_act, eps, eps_stride, c->emap, c->omap, mu_q, x_draft))) return rc;
+    HIPCHK(c, launch_len_add(s, m.len, nullptr, 1, B));
+  }
+  m.len_hi += K;
+  m.written = K;
+  return FARD_OK;
+}
+
+int spec_verify(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* x_draft, const float* mu_q,
+                const int32_t* n_keep, const float* r, const float* eps, float log_sigma_factor, float sigma_p, float sigma_q,
+                int32_t B, int32_t* n_accept, float* log_ratio, float* mu_p, void* z_p) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (B == 0) return FARD_OK;
+  if (!x_pending || !x_draft || !mu_q || !n_keep || !r || !eps || !n_accept || !log_ratio || !mu_p)
+    return fail(c, FARD_EINVAL, "null argument");
+  if (!(sigma_p > 0.f) || !(sigma_q > 0.f)) return fail(c, FARD_EINVAL, "sigma must be > 0");
+  Model& m = c->mdl[FARD_TARGET];
+  if (pending_id && !m.cond) return fail(c, FARD_EINVAL, "pending_id given but the target has no id table");
+  const int K = c->cfg.K, D = m.c.d_latent, M = B * (K + 1);
+  if (K + 1 > cap_nq(c, FARD_TARGET)) return fail(c, FARD_ESHAPE, "(K+1) * (n_heads / n_kv_heads) > 64");
+  if (m.len_hi + K + 1 > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "target cache_len + K + 1 exceeds max_ctx");
+  if (m.c.pos == FARD_POS_LEARNED && m.len_hi + K + 1 > m.c.max_pos) return fail(c, FARD_ECAPACITY, "target position beyond the learned table");
+  hipStream_t s = c->stream;
+  int rc;
+  { Bracket br(c, CLS_OTHER);
+    copy_i32_kernel<<<(B + 255) / 256, 256, 0, s>>>(m.len, m.len_base, B);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, launch_build_rows(s, n_keep, 1, B, K, D, m.len, c->maps, x_pending, x_draft, c->x_in, c->aux_row, M, K + 1));
+    HIPCHK(c, launch_fill_f32(s, mu_p, 0.f, (size_t)B * (K + 1) * D)); }
+  const int* md = c->maps.m_total;
+  int* cid = nullptr;
+  { Bracket br(c, CLS_OTHER);
+    if (pending_id) {
+      // per-row ids: row 0 of each sample carries the pending id, every other row is a latent row
+      cid = c->row_ids;
+      HIPCHK(c, launch_fill_i32(s, cid, -1, M));
+      HIPCHK(c, launch_scatter_rows(s, pending_id, cid, c->maps.row_start, 1, 4, B, nullptr));
+    }
+    HIPCHK(c, launch_embed(s, c->bf16, c->x_in, D, D, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, cid, c->h, m.c.d_model, M, md)); }
+  if ((rc = run_layers(c, FARD_TARGET, 0, m.c.n_layers, B, M, K + 1, md, 0))) return rc;
+  if ((rc = run_final(c, FARD_TARGET, M, md, nullptr, c->z))) return rc;
+  if (z_p) {
+    Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_scatter_rows(s, c->z, z_p, c->aux_row, m.d_out(), (int)c->esz, M, md));
+  }
+  if ((rc = run_head(c, c->z, M, md, eps, (size_t)B * (K + 1) * D, c->aux_row, c->aux_row, mu_p, c->x_scratch)))
+    return rc;
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_accept(s, x_draft, mu_p, mu_q, r, n_keep, log_sigma_factor, sigma_p, sigma_q, B, K, D, n_accept, log_ratio,
+                            c->acc_tmp)); }
+  m.written = K + 1;
+  return FARD_OK;
+}
+
+int spec_round(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, const float* r, float tau,
+               float log_sigma_factor, float sigma_p, float sigma_q, int32_t B, float* H, uint8_t* keep, int32_t* n_keep,
+               float* x_draft, float* mu_q, int32_t* n_accept, float* log_ratio, float* mu_p) {
+  int rc = spec_draft(c, x_pending, pending_id, eps, tau, B, H, keep, n_keep, x_draft, mu_q);
+  if (rc) return rc;
+  rc = spec_verify(c, x_pending, pending_id, x_draft, mu_q, n_keep, r, eps, log_sigma_factor, sigma_p, sigma_q, B, n_accept,
+                   log_ratio, mu_p, nullptr);
+  if (rc) return rc;
+  return spec_kv_commit(c, -1, n_accept, B);
+}
+
+int spec_gemm(fard_ctx* c, const void* A, const void* W, const float* bias, int32_t M, int32_t K, int32_t N, int32_t act, void* out) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (M < 0 || K < 1 || N < 1) return fail(c, FARD_ESHAPE, "M >= 0, K, N >= 1 required");
+  if (M == 0) return FARD_OK;
+  if (!A || !W || !out) return fail(c, FARD_EINVAL, "null argument");
+  if (act < 0 || act > 2) return fail(c, FARD_EINVAL, "act");
+  const void* Wk = W;
+  if (c->bf16) {
+    if (K % 64 != 0 || N % 32 != 0) return fail(c, FARD_ESHAPE, "bf16 GEMM needs K % 64 == 0 and N % 32 == 0");
+    const size_t bytes = (size_t)K * N * 2;
+    if (bytes > c->gemm_tmp_bytes) {
+      HIPCHK(c, hipStreamSynchronize(c->stream));
+      if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
+      c->gemm_tmp = nullptr;
+      c->gemm_tmp_bytes = 0;
+      HIPCHK(c, hipMalloc(&c->gemm_tmp, bytes));
+      c->gemm_tmp_bytes = bytes;
+    }
+    HIPCHK(c, launch_pack_weight(c->stream, W, 1, N, K, N, c->gemm_tmp, 0, 1));
+    Wk = c->gemm_tmp;
+  }
+  HIPCHK(c, gemm(c, A, K, Wk, bias, out, N, M, N, K, nullptr, EPI_STORE, act));
+  return FARD_OK;
+}
+
+int spec_profile_enable(fard_ctx* c, int32_t enable) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->prof.on = enable != 0;
+  c->prof.used = 0;
+  for (int i = 0; i < 4; ++i) c->prof.flops[i] = c->prof.bytes[i] = 0;
+  return FARD_OK;
+}
+
+int spec_profile_read(fard_ctx* c, int32_t kernel_class, float* total_ms, int64_t* launches, double* flops, double* bytes) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (kernel_class < 0 || kernel_class > 3) return fail(c, FARD_EINVAL, "kernel_class");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  float tot = 0.f;
+  int64_t n = 0;
+  for (size_t i = 0; i < c->prof.used; ++i) {
+    if (c->prof.cls[i] != kernel_class) continue;
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, c->prof.pool[i].first, c->prof.pool[i].second));
+    tot += ms;
+    ++n;
+  }
+  if (total_ms) *total_ms = tot;
+  if (launches) *launches = n;
+  if (flops) *flops = c->prof.flops[kernel_class];
+  if (bytes) *bytes = c->prof.bytes[kernel_class];
+  return FARD_OK;
+}
+
+}  // extern "C"

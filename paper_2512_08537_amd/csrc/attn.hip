@@ -1,0 +1,298 @@
+// KV-cached causal attention for the few query rows of a speculative block.
+//
+// bf16 path.  One workgroup of 4 waves per (sample, kv head); the waves take the 32-position
+// blocks of the cache round-robin and merge their partial results through LDS at the end.
+// The products are computed transposed so that nothing but Q passes through a layout change:
+//   S^T = K Q^T    A operand = one K block (keys as rows) read as contiguous 1 KiB fragments,
+//                  B operand = Q^T held in registers for the whole kernel;
+//   O^T = V^T P^T  A operand = one V block (dims as rows, keys along k), B operand = P^T taken
+//                  directly from the S^T accumulators (the cache stores V with its keys permuted
+//                  to the accumulator order, see rowops.hip), so probabilities never leave registers.
+// Every output column of both products is one query row, i.e. one lane pair (lane, lane+32):
+// the running softmax triple (m, l, a) with a = sum e^{s-m}(s-m) lives in those lanes; the row
+// entropy ln l - a/l of the attention distribution (Eq. 1 / S2.1 indicator) falls out for free.
+// With grouped KV heads the G query heads of a KV head are packed into the columns (G*n_q <= 64).
+//
+// fp32 path: one wave per (row, head), scores staged in LDS; for the small fp32 configuration.
+#include "kernels.h"
+
+namespace fard {
+
+namespace {
+
+template <int DH, int NQB>
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
+                                                        const int* __restrict__ cache_len,
+                                                        const int* __restrict__ row_start, bf16* __restrict__ out,
+                                                        int ldo, float* __restrict__ ent_heads) {
+  constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
+  constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
+  constexpr int NCOL = 32 * NQB;
+  __shared__ float s_m[4][NCOL], s_l[4][NCOL], s_a[4][NCOL];
+  __shared__ float s_o[DH * NCOL];
+
+  const int Hk = kv.n_kv_heads;
+  const int G = n_heads / Hk;
+  const int b = blockIdx.x / Hk, hk = blockIdx.x - b * Hk;
+  const int r0 = row_start[b];
+  const int nq = row_start[b + 1] - r0;
+  if (nq <= 0) return;
+  const int p0 = cache_len[b];
+  const int ncols = nq * G;                       // column c <-> (query head hk*G + c / nq, row c % nq)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cl = lane & 31, g = lane >> 5;
+  const float scale = rsqrtf((float)DH);
+
+  // Q^T fragments: lane supplies column cl (+32*qb), dims 16*dc + 8*g .. +7
+  bf16x8 qf[DC][NQB];
+  int jrow[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int c = cl + 32 * qb;
+    const bool ok = c < ncols;
+    const int gq = ok ? c / nq : 0;
+    const int j = ok ? c - gq * nq : 0;
+    jrow[qb] = ok ? j : -1;
+    const bf16* qp = qkv + (size_t)(r0 + j) * ld + (size_t)(hk * G + gq) * DH + 8 * g;
+#pragma unroll
+    for (int dc = 0; dc < DC; ++dc) {
+      bf16x8 v;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = (bf16)0.f;
+      if (ok) v = *(const bf16x8*)(qp + 16 * dc);
+      qf[dc][qb] = v;
+    }
+  }
+
+  const size_t head_elems = (size_t)kv.ctx_pad * DH;
+  const bf16* Kb = (const bf16*)kv.k + ((size_t)b * Hk + hk) * head_elems;
+  const bf16* Vb = (const bf16*)kv.v + ((size_t)b * Hk + hk) * head_elems;
+
+  float m_run[NQB], l_run[NQB], a_run[NQB];
+  f32x16 o[DB][NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+    a_run[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[db][qb][e] = 0.f;
+  }
+
+  const int n_keys = p0 + nq;
+  const int n_blocks = (n_keys + 31) >> 5;
+  for (int kb = wave; kb < n_blocks; kb += 4) {
+    const bf16x8* kblk = (const bf16x8*)(Kb + (size_t)kb * 32 * DH);
+    const bf16x8* vblk = (const bf16x8*)(Vb + (size_t)kb * 32 * DH);
+    bf16x8 kf[DC];
+#pragma unroll
+    for (int dc = 0; dc < DC; ++dc) kf[dc] = kblk[dc * 64 + lane];
+    bf16x8 vf[DB][2];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) vf[db][hf] = vblk[(db * 2 + hf) * 64 + lane];
+
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      f32x16 s;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+      for (int dc = 0; dc < DC; ++dc) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[dc], qf[dc][qb], s, 0, 0, 0);
+      // register e holds key 32*kb + 8*(e/4) + 4*g + e%4 for query column cl
+      const int lim = (jrow[qb] >= 0) ? p0 + jrow[qb] : -1;     // last visible position
+      float bmax = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = kb * 32 + 8 * (e >> 2) + 4 * g + (e & 3);
+        s[e] = (key <= lim) ? s[e] * scale : -INFINITY;
+        bmax = fmaxf(bmax, s[e]);
+      }
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
+      const float m_new = fmaxf(m_run[qb], bmax);
+      float psum = 0.f, asum = 0.f;
+      bf16x8 pf[2];
+      if (m_new == -INFINITY) {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) pf[hf][i] = (bf16)0.f;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float t = s[e] - m_new;                       // -inf for masked keys
+          const float p = (s[e] == -INFINITY) ? 0.f : __expf(t);
+          psum += p;
+          asum += (s[e] == -INFINITY) ? 0.f : p * t;
+          pf[e >> 3][e & 7] = (bf16)p;
+        }
+        psum += __shfl_xor(psum, 32, WAVE);
+        asum += __shfl_xor(asum, 32, WAVE);
+        float corr = 1.f;
+        if (m_run[qb] != -INFINITY) {
+          const float dl = m_run[qb] - m_new;
+          corr = __expf(dl);
+          a_run[qb] = corr * (a_run[qb] + dl * l_run[qb]);
+          l_run[qb] = corr * l_run[qb];
+        }
+        a_run[qb] += asum;
+        l_run[qb] += psum;
+        m_run[qb] = m_new;
+        if (corr != 1.f) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[db][qb][e] *= corr;
+        }
+      }
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+          o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][hf], pf[hf], o[db][qb], 0, 0, 0);
+    }
+  }
+
+  // ---- merge the four waves
+  if (g == 0) {
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      s_m[wave][cl + 32 * qb] = m_run[qb];
+      s_l[wave][cl + 32 * qb] = l_run[qb];
+      s_a[wave][cl + 32 * qb] = a_run[qb];
+    }
+  }
+  for (int i = tid; i < DH * NCOL; i += 256) s_o[i] = 0.f;
+  __syncthreads();
+  float f_me[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int c = cl + 32 * qb;
+    float mstar = -INFINITY;
+    for (int w = 0; w < 4; ++w) mstar = fmaxf(mstar, s_m[w][c]);
+    f_me[qb] = (m_run[qb] == -INFINITY) ? 0.f : __expf(m_run[qb] - mstar);
+  }
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
+            s_o[dim * NCOL + cl + 32 * qb] += o[db][qb][e] * f_me[qb];
+          }
+    }
+    __syncthreads();
+  }
+  // ---- normalise and write: thread -> (column, 8 consecutive dims)
+  constexpr int D8 = DH / 8;
+  for (int idx = tid; idx < NCOL * D8; idx += 256) {
+    const int c = idx / D8, d8 = idx - c * D8;
+    if (c >= ncols) continue;
+    float mstar = -INFINITY;
+    for (int w = 0; w < 4; ++w) mstar = fmaxf(mstar, s_m[w][c]);
+    float lstar = 0.f, astar = 0.f;
+    for (int w = 0; w < 4; ++w) {
+      const float mw = s_m[w][c];
+      if (mw == -INFINITY) continue;
+      const float dl = mw - mstar, f = __expf(dl);
+      lstar += f * s_l[w][c];
+      astar += f * (s_a[w][c] + dl * s_l[w][c]);
+    }
+    const float inv = 1.0f / lstar;
+    const int gq = c / nq, j = c - gq * nq;
+    const int head = hk * G + gq;
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (bf16)(s_o[(d8 * 8 + i) * NCOL + c] * inv);
+    *(bf16x8*)(out + (size_t)(r0 + j) * ldo + (size_t)head * DH + d8 * 8) = v;
+    if (ent_heads != nullptr && d8 == 0) ent_heads[(size_t)(r0 + j) * n_heads + head] = logf(lstar) - astar * inv;
+  }
+}
+
+// fp32 path: one wave per (row, head).
+__global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
+                                                      const int* __restrict__ cache_len,
+                                                      const int* __restrict__ row_start, int B, float* __restrict__ out,
+                                                      int ldo, float* __restrict__ ent_heads, int max_keys) {
+  extern __shared__ float s_p[];                 // [max_keys] scores / probabilities
+  const int head = blockIdx.x, b = blockIdx.z, j = blockIdx.y;
+  const int r0 = row_start[b];
+  const int nq = row_start[b + 1] - r0;
+  if (j >= nq) return;
+  const int Hk = kv.n_kv_heads, dh = kv.d_head;
+  const int hk = (head * Hk) / n_heads;
+  const int lane = threadIdx.x;
+  const int vis = cache_len[b] + j + 1;
+  const float* q = qkv + (size_t)(r0 + j) * ld + (size_t)head * dh;
+  const float* Kc = (const float*)kv.k + ((size_t)b * Hk + hk) * (size_t)kv.ctx_pad * dh;
+  const float* Vc = (const float*)kv.v + ((size_t)b * Hk + hk) * (size_t)kv.ctx_pad * dh;
+  const float scale = 1.0f / sqrtf((float)dh);
+  float mx = -INFINITY;
+  for (int c = lane; c < vis; c += WAVE) {
+    float s = 0.f;
+    for (int d = 0; d < dh; ++d) s += q[d] * Kc[(size_t)c * dh + d];
+    s *= scale;
+    s_p[c] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = wave_max(mx);
+  float l = 0.f, a = 0.f;
+  for (int c = lane; c < vis; c += WAVE) {
+    const float t = s_p[c] - mx, e = expf(t);
+    s_p[c] = e;
+    l += e;
+    a += e * t;
+  }
+  l = wave_sum(l);
+  a = wave_sum(a);
+  __syncthreads();
+  const float inv = 1.0f / l;
+  for (int d = lane; d < dh; d += WAVE) {
+    float acc = 0.f;
+    for (int c = 0; c < vis; ++c) acc += s_p[c] * Vc[(size_t)c * dh + d];
+    out[(size_t)(r0 + j) * ldo + (size_t)head * dh + d] = acc * inv;
+  }
+  if (ent_heads != nullptr && lane == 0) ent_heads[(size_t)(r0 + j) * n_heads + head] = logf(l) - a * inv;
+}
+
+}  // namespace
+
+hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv, const int* cache_len,
+                            const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads) {
+  if (B <= 0 || nq_max <= 0) return hipSuccess;
+  if (!kv.is_bf16) {
+    dim3 grid(n_heads, nq_max, B);
+    const size_t smem = (size_t)kv.ctx_pad * sizeof(float);
+    if (smem > 64 * 1024) return hipErrorInvalidValue;
+    attn_f32_kernel<<<grid, 64, smem, s>>>((const float*)qkv, ld, n_heads, kv, cache_len, row_start, B, (float*)out,
+                                           ldo, ent_heads, kv.ctx_pad);
+    return hipGetLastError();
+  }
+  const int G = n_heads / kv.n_kv_heads;
+  const int cols = G * nq_max;
+  if (cols > 64 || n_heads % kv.n_kv_heads != 0) return hipErrorInvalidValue;
+  const int grid = B * kv.n_kv_heads;
+  const bf16* q = (const bf16*)qkv;
+  bf16* o = (bf16*)out;
+  if (kv.d_head == 64) {
+    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+  } else if (kv.d_head == 128) {
+    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+  } else if (kv.d_head == 32) {
+    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace fard

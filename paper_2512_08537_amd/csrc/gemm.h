@@ -1,0 +1,44 @@
+// Host-side interface of the GEMM kernels (bf16 MFMA path and fp32 path).
+#pragma once
+#include "common.h"
+
+namespace fard {
+
+// What the epilogue does with acc[m, n] = sum_k A[m, k] W[k, n].
+enum Epi {
+  EPI_STORE = 0,       // out_T[m, n]   = act(acc + bias[n])                (activation storage type)
+  EPI_STORE_F32 = 1,   // out_f32[m, n] = act(acc + bias[n])
+  EPI_RESID = 2,       // out_f32[m, n] += acc + bias[n]                    (residual stream update)
+  EPI_GATE_RESID = 3,  // out_f32[m, n] += gate[m, n] * (acc + bias[n])
+  EPI_SWIGLU = 4,      // out_T[m, j]   = silu(acc[m, gate col j]) * acc[m, up col j]  (interleaved columns)
+};
+
+struct GemmArgs {
+  const void* A;       // [M, K] row-major, leading dimension lda (elements); bf16 or fp32 per path
+  int lda;
+  const void* W;       // bf16 path: fragment-packed weights; fp32 path: [K, N] row-major
+  const float* bias;   // [N] or nullptr
+  void* out;
+  int ldo;
+  const float* gate;   // [M, ldg] fp32, EPI_GATE_RESID only
+  int ldg;
+  int M, N, K;         // N counts weight columns (2F for EPI_SWIGLU)
+  const int* m_dev;    // optional device-side row count (rows >= *m_dev are skipped)
+  int act;
+  int epi;
+};
+
+// Packed bf16 weight size in elements for a [K, N] matrix (K % 16 == 0, N % 32 == 0).
+inline size_t packed_elems(int K, int N) { return (size_t)K * (size_t)N; }
+
+// Returns hipSuccess or the launch error.  K % 64 == 0 and N % 32 == 0 are required (bf16 path).
+hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a);
+hipError_t launch_gemm_f32(hipStream_t s, const GemmArgs& a);
+
+// Re-lay a row-major [K, N] matrix (src_is_bf16: bf16 else fp32; leading dimension ld) into MFMA
+// fragment order.  Destination n-block index = nb_offset + nb * nb_stride (lets two matrices be
+// interleaved block by block for the SwiGLU epilogue).
+hipError_t launch_pack_weight(hipStream_t s, const void* src, int src_is_bf16, int ld, int K, int N,
+                              void* dst, int nb_offset, int nb_stride);
+
+}  // namespace fard

@@ -1,0 +1,124 @@
+// Host-side launchers of the non-GEMM kernels.  T is the activation/weight storage type:
+// `is_bf16` selects bf16 (MFMA path, fragment-packed KV cache) or fp32 (plain layouts).
+#pragma once
+#include "common.h"
+
+namespace fard {
+
+// ------------------------------------------------------------------ KV cache geometry
+// bf16 path: per (layer, sample, kv head) the K region and the V region are each
+// ctx_pad * d_head elements (ctx_pad a multiple of 32), stored in blocks of 32 positions laid
+// out in MFMA operand order (see attn.hip).  fp32 path: plain [pos][d_head].
+struct KvGeom {
+  void* k;            // base of this layer's K storage
+  void* v;
+  int n_kv_heads, d_head, ctx_pad;
+  int is_bf16;
+};
+
+// ------------------------------------------------------------------ row maps of a packed batch
+struct RowMaps {
+  int* row_start;     // [B+1] exclusive scan of n_q
+  int* row_sample;    // [M]
+  int* row_j;         // [M] index inside the sample's rows
+  int* row_pos;       // [M] absolute position = cache_len[sample] + row_j
+  int* m_total;       // [1] number of packed rows
+};
+
+// n_q = n_base[b] + add (n_base may be null -> n_q = add).  Also gathers the fp32 latent rows when
+// x_first/x_rest are given: row j = 0 takes x_first[b, :], row j >= 1 takes x_rest[b, j-1, :]
+// (x_rest is [B, K, D]); aux_row[r] = b * (K+1) + j indexes per-token side tensors.  n_q is clamped
+// to nq_cap and rows beyond m_max are dropped, so downstream kernels never index out of bounds.
+hipError_t launch_build_rows(hipStream_t s, const int* n_base, int add, int B, int K, int D,
+                             const int* cache_len, RowMaps maps, const float* x_first,
+                             const float* x_rest, float* x_out, int* aux_row, int m_max, int nq_cap);
+
+// h[r, :] = x[r, :] W_in + b_in (+ pos[row_pos[r], :]) ; rows with cond_id[r] >= 0 take cond[id, :].
+hipError_t launch_embed(hipStream_t s, int is_bf16, const float* x, int ldx, int D, const void* w_in,
+                        const float* b_in, const void* pos_table, const int* row_pos,
+                        const void* cond_table, const int* cond_id, float* h, int d, int M,
+                        const int* m_dev);
+
+// out_T[r, :] = norm(h[r, :]) with optional affine (g, b) and optional AdaLN modulation
+// (1 + scale[r, :]) / shift[r, :] read with row stride ldm.  norm_type 0 LayerNorm, 1 RMSNorm.
+// in_map (optional) gathers: output row r is computed from input row in_map[r].
+hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M, const int* m_dev,
+                       int norm_type, float eps, const float* g, const float* b, const float* shift,
+                       const float* scale, int ldm, const int* in_map, void* out);
+
+// Splits qkv[M, (H+2Hkv) dh] rows: optional RoPE on q (in place) and k, then stores k, v at
+// position row_pos[r] of sample row_sample[r] in the cache.
+hipError_t launch_rope_append(hipStream_t s, void* qkv, int ld, int n_heads, KvGeom kv, int rope,
+                              float rope_theta, const int* row_sample, const int* row_pos, int M,
+                              const int* m_dev);
+
+// Copies plain [B, Hkv, n, dh] tensors (storage type of the context) into the cache at positions 0..n-1.
+hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v, int B, int n);
+
+// Cached causal attention.  q rows come from qkv (row r, head g at column g*dh); output
+// out_T[r, g*dh + :].  ent_heads[r, g] (optional) receives the entropy of the attention row.
+hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv,
+                            const int* cache_len, const int* row_start, int B, int nq_max,
+                            void* out, int ldo, float* ent_heads);
+
+// Shallow-feature entropy + threshold + prefix rule + compaction (one launch).
+// feat: [B, K, L] storage type; prior_alive (optional, [B]) masks samples that already stopped.
+hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L,
+                                    float tau, float* H, uint8_t* keep, int* n_keep, int* surv_idx,
+                                    int* n_surv, unsigned* ticket);
+
+// H[r] = softmax entropy of the fp32 row feat[r*ld .. r*ld+L) (one wave per row).
+hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H);
+
+// One draft step's threshold on per-row entropies already computed elsewhere (ATTN mode) or per
+// head (mean over heads taken here): alive[b] &= (H >= tau); n_keep[b] += alive[b]; writes H and keep
+// at column `step` of [B, K] arrays and compacts the alive sample indices into act_idx / n_act with the
+// matching noise rows emap = b*(K+1)+step and output rows omap = b*K+step.
+hipError_t launch_entropy_step(hipStream_t s, const float* ent_heads, int n_heads, const float* H_in,
+                               int B, int K, int step, float tau, float* H, uint8_t* keep,
+                               int* alive, int* n_keep, int* act_idx, int* n_act, int* emap, int* omap);
+
+// Head pieces.
+// hh[r, :] = x_t[r, :] W_in + b_in ; sc[r, :] = T(silu(cz[r, :] + temb[:])).  x_t comes from
+// xsrc[xmap ? xmap[r] : r] * xscale.
+hipError_t launch_head_prep(hipStream_t s, int is_bf16, const float* xsrc, const int* xmap, float xscale,
+                            int D, const void* w_in, const float* b_in, const float* cz,
+                            const float* temb, float* hh, void* sc, float* xt_out, int w, int n,
+                            const int* n_dev);
+
+struct HeadStepArgs {
+  const float* hh; int w;            // residual stream of the head [n, w]
+  const float* shift; const float* scale; int ldm;   // final modulation
+  const void* w_out; const float* b_out; int D;      // [w, D] storage type
+  float* xt;                          // [n, D] current x_t (updated in place for the next step)
+  const float* eps_next;              // noise of the next transition, row-mapped (may be null)
+  const int* emap;                    // row -> row of eps (null = identity)
+  const int* omap;                    // row -> row of mu / x (null = identity)
+  float t, t_next;                    // current / next time
+  int last;                           // 1: write mu, x ; 0: advance x_t
+  int renoise;
+  float sigma;                        // sigma_last * temperature (last step)
+  float* mu; float* x;                // outputs of the last step, row-mapped
+  int n; const int* n_dev;
+};
+hipError_t launch_head_out(hipStream_t s, int is_bf16, const HeadStepArgs& a);
+
+// out[n] = act(sum_k in[k] W[k, n] + b[n]) for one fp32 vector (time embedding at init).
+hipError_t launch_matvec(hipStream_t s, int is_bf16, const float* in, const void* W, const float* b,
+                         int K, int N, int act, float* out);
+
+// ln rho, acc flags and the length of the leading accepted run.
+hipError_t launch_accept(hipStream_t s, const float* x, const float* mu_p, const float* mu_q,
+                         const float* r, const int* n_keep, float log_sigma, float sigma_p,
+                         float sigma_q, int B, int K, int D, int* n_accept, float* log_ratio,
+                         uint8_t* acc);
+
+// cache_len[b] += base + (n ? n[b] : 0)
+hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B);
+hipError_t launch_fill_i32(hipStream_t s, int* p, int v, int n);
+hipError_t launch_fill_f32(hipStream_t s, float* p, float v, size_t n);
+// copy rows: dst[dmap ? dmap[r] : r, :] = src[r, :] for r < n (fp32 or storage type by elem_size)
+hipError_t launch_scatter_rows(hipStream_t s, const void* src, void* dst, const int* dmap, int width,
+                               int elem_size, int n, const int* n_dev);
+
+}  // namespace fard

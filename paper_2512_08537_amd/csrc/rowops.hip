@@ -1,0 +1,699 @@
+// Row-wise kernels around the GEMMs: row maps, embedding, norms, RoPE + KV append, entropy
+// pre-filter, head sampler pieces, accept test.  Memory-bound or tiny; one wave or one
+// workgroup per row, fp32 arithmetic, vector loads where rows are long.
+#include "kernels.h"
+
+namespace fard {
+
+namespace {
+
+// ================================================================== KV cache addressing
+// bf16 cache, blocks of 32 positions.  K block: [d/16][lane][8] with lane = (pos%32) + 32*((d%16)/8):
+// the A operand of v_mfma_f32_32x32x16_bf16 with keys as rows.  V block: [d/32][half][lane][8] with
+// lane = d%32 + 32*g, holding the 8 keys {16*half + 8*(i/4) + 4*g + i%4}: the A operand of the
+// P*V product with dims as rows, keys ordered the way the score accumulators hold them.
+__device__ __forceinline__ size_t k_offset_bf16(int pos, int d, int dh) {
+  const int kb = pos >> 5, lr = pos & 31;
+  const int dc = d >> 4, g = (d >> 3) & 1, i = d & 7;
+  return (size_t)kb * 32 * dh + ((size_t)(dc * 64 + lr + 32 * g) << 3) + i;
+}
+__device__ __forceinline__ size_t v_offset_bf16(int pos, int d, int dh) {
+  const int kb = pos >> 5, pk = pos & 31;
+  const int hf = pk >> 4, rem = pk & 15;
+  const int g = (rem >> 2) & 1, i = ((rem >> 3) << 2) | (rem & 3);
+  const int db = d >> 5, lane = (d & 31) + 32 * g;
+  return (size_t)kb * 32 * dh + ((size_t)((db * 2 + hf) * 64 + lane) << 3) + i;
+}
+
+// ================================================================== row maps
+__global__ __launch_bounds__(256) void build_rows_kernel(const int* n_base, int add, int B, int K, int D,
+                                                         const int* cache_len, RowMaps maps,
+                                                         const float* x_first, const float* x_rest,
+                                                         float* x_out, int* aux_row, int m_max, int nq_cap) {
+  __shared__ int s_scan[256];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < B; base += 256) {
+    const int b = base + tid;
+    int nq = 0;
+    if (b < B) {
+      nq = (n_base ? n_base[b] : 0) + add;
+      if (nq < 0) nq = 0;
+      if (nq > nq_cap) nq = nq_cap;
+    }
+    s_scan[tid] = nq;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {          // inclusive Hillis-Steele scan
+      int v = (tid >= o) ? s_scan[tid - o] : 0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
+    }
+    const int carry = s_carry;
+    const int start = carry + s_scan[tid] - nq;
+    if (b < B) {
+      maps.row_start[b] = start < m_max ? start : m_max;
+      const int len = cache_len[b];
+      for (int j = 0; j < nq; ++j) {
+        const int r = start + j;
+        if (r >= m_max) break;
+        maps.row_sample[r] = b;
+        maps.row_j[r] = j;
+        maps.row_pos[r] = len + j;
+        if (aux_row) aux_row[r] = b * (K + 1) + j;
+        if (x_out) {
+          const float* src = (j == 0) ? x_first + (size_t)b * D : x_rest + ((size_t)b * K + (j - 1)) * D;
+          for (int c = 0; c < D; ++c) x_out[(size_t)r * D + c] = src[c];
+        }
+      }
+    }
+    __syncthreads();
+    if (tid == 255) s_carry = carry + s_scan[255];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    int total = s_carry;
+    if (total > m_max) total = m_max;
+    maps.row_start[B] = total;
+    *maps.m_total = total;
+  }
+}
+
+// ================================================================== embedding
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const float* __restrict__ x, int ldx, int D, const T* __restrict__ w_in,
+                                                    const float* __restrict__ b_in, const T* __restrict__ pos_table,
+                                                    const int* __restrict__ row_pos, const T* __restrict__ cond_table,
+                                                    const int* __restrict__ cond_id, float* __restrict__ h, int d,
+                                                    int M, const int* m_dev) {
+  const int Me = eff_rows(M, m_dev);
+  const int r = blockIdx.y;
+  if (r >= Me) return;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= d) return;
+  float v;
+  const int id = cond_id ? cond_id[r] : -1;
+  if (id >= 0) {
+    v = to_f32(cond_table[(size_t)id * d + c]);
+  } else {
+    v = b_in ? b_in[c] : 0.f;
+    for (int k = 0; k < D; ++k) v += x[(size_t)r * ldx + k] * to_f32(w_in[(size_t)k * d + c]);
+    if (pos_table) v += to_f32(pos_table[(size_t)row_pos[r] * d + c]);
+  }
+  h[(size_t)r * d + c] = v;
+}
+
+// ================================================================== norms
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  float t = 0.f;
+  const int nw = blockDim.x >> 6;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, int d, int M, const int* m_dev,
+                                                   int norm_type, float eps, const float* __restrict__ g,
+                                                   const float* __restrict__ b, const float* __restrict__ shift,
+                                                   const float* __restrict__ scale, int ldm,
+                                                   const int* __restrict__ in_map, T* __restrict__ out) {
+  __shared__ float red[8];
+  const int Me = eff_rows(M, m_dev);
+  const int r = blockIdx.x;
+  if (r >= Me) return;
+  const float* row = h + (size_t)(in_map ? in_map[r] : r) * d;
+  float mean = 0.f;
+  if (norm_type == 0) {
+    float s = 0.f;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) s += row[c];
+    mean = block_sum(s, red) / (float)d;
+  }
+  float q = 0.f;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    const float t = row[c] - mean;
+    q += t * t;
+  }
+  const float var = block_sum(q, red) / (float)d;
+  const float rstd = 1.0f / sqrtf(var + eps);
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float y = (row[c] - mean) * rstd;
+    if (g) y *= g[c];
+    if (b) y += b[c];
+    if (scale) y = y * (1.0f + scale[(size_t)r * ldm + c]) + shift[(size_t)r * ldm + c];
+    out[(size_t)r * d + c] = from_f32<T>(y);
+  }
+}
+
+// ================================================================== RoPE + KV append
+template <typename T>
+__global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
+                                                          int rope, float theta, const int* __restrict__ row_sample,
+                                                          const int* __restrict__ row_pos, int M, const int* m_dev) {
+  const int Me = eff_rows(M, m_dev);
+  const int r = blockIdx.x;
+  if (r >= Me) return;
+  const int dh = kv.d_head, Hk = kv.n_kv_heads, half = dh >> 1;
+  const int b = row_sample[r], pos = row_pos[r];
+  T* row = qkv + (size_t)r * ld;
+  const int n_rot_heads = n_heads + Hk;         // q heads then k heads are rotated
+  if (rope) {
+    for (int idx = threadIdx.x; idx < n_rot_heads * half; idx += blockDim.x) {
+      const int hd = idx / half, c = idx - hd * half;
+      const float inv = powf(theta, -2.0f * (float)c / (float)dh);
+      float sn, cs;
+      sincosf((float)pos * inv, &sn, &cs);
+      T* p = row + (size_t)hd * dh;
+      const float a = to_f32(p[c]), bb = to_f32(p[c + half]);
+      p[c] = from_f32<T>(a * cs - bb * sn);
+      p[c + half] = from_f32<T>(bb * cs + a * sn);
+    }
+    __syncthreads();
+  }
+  const T* ksrc = row + (size_t)n_heads * dh;
+  const T* vsrc = ksrc + (size_t)Hk * dh;
+  const size_t head_elems = (size_t)kv.ctx_pad * dh;
+  for (int idx = threadIdx.x; idx < Hk * dh; idx += blockDim.x) {
+    const int hk = idx / dh, d = idx - hk * dh;
+    const size_t base = ((size_t)b * Hk + hk) * head_elems;
+    size_t ko, vo;
+    if (kv.is_bf16) {
+      ko = k_offset_bf16(pos, d, dh);
+      vo = v_offset_bf16(pos, d, dh);
+    } else {
+      ko = vo = (size_t)pos * dh + d;
+    }
+    ((T*)kv.k)[base + ko] = ksrc[idx];
+    ((T*)kv.v)[base + vo] = vsrc[idx];
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void kv_load_kernel(KvGeom kv, const T* __restrict__ k, const T* __restrict__ v,
+                                                      int B, int n) {
+  const int dh = kv.d_head, Hk = kv.n_kv_heads;
+  const size_t total = (size_t)B * Hk * n * dh;
+  const size_t head_elems = (size_t)kv.ctx_pad * dh;
+  for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (size_t)gridDim.x * blockDim.x) {
+    const int d = (int)(idx % dh);
+    const size_t t = idx / dh;
+    const int pos = (int)(t % n);
+    const size_t bh = t / n;                     // b * Hk + hk
+    size_t ko, vo;
+    if (kv.is_bf16) {
+      ko = k_offset_bf16(pos, d, dh);
+      vo = v_offset_bf16(pos, d, dh);
+    } else {
+      ko = vo = (size_t)pos * dh + d;
+    }
+    ((T*)kv.k)[bh * head_elems + ko] = k[idx];
+    ((T*)kv.v)[bh * head_elems + vo] = v[idx];
+  }
+}
+
+// ================================================================== entropy pre-filter
+// Online softmax-entropy of one row held by one wave: every lane folds its elements into a
+// running (m, l, a) with a = sum e^{x-m} (x-m); lanes are merged with a butterfly; H = ln l - a/l.
+struct Mla { float m, l, a; };
+__device__ __forceinline__ Mla mla_merge(Mla p, Mla q) {
+  const float m = fmaxf(p.m, q.m);
+  Mla r;
+  r.m = m;
+  float l = 0.f, a = 0.f;
+  if (p.l > 0.f) { const float dl = p.m - m, e = expf(dl); l += e * p.l; a += e * (p.a + dl * p.l); }
+  if (q.l > 0.f) { const float dl = q.m - m, e = expf(dl); l += e * q.l; a += e * (q.a + dl * q.l); }
+  r.l = l;
+  r.a = a;
+  return r;
+}
+__device__ __forceinline__ void mla_push(Mla& s, float x) {
+  if (x > s.m) {
+    if (s.l > 0.f) { const float dl = s.m - x, e = expf(dl); s.a = e * (s.a + dl * s.l); s.l = e * s.l; }
+    s.m = x;
+  }
+  const float t = x - s.m, e = expf(t);
+  s.l += e;
+  s.a += e * t;
+}
+template <typename T>
+__device__ __forceinline__ float row_entropy_wave(const T* __restrict__ row, int L, int lane) {
+  Mla s{-INFINITY, 0.f, 0.f};
+  if constexpr (sizeof(T) == 2) {
+    const int nvec = L >> 3;                      // 16-byte chunks of 8 bf16
+    const bf16x8* rv = (const bf16x8*)row;
+    const bool aligned = (((uintptr_t)row) & 15) == 0;
+    if (aligned) {
+      for (int c = lane; c < nvec; c += WAVE) {
+        const bf16x8 v = rv[c];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) mla_push(s, (float)v[i]);
+      }
+      for (int c = (nvec << 3) + lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
+    } else {
+      for (int c = lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
+    }
+  } else {
+    for (int c = lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    Mla q;
+    q.m = __shfl_xor(s.m, o, WAVE);
+    q.l = __shfl_xor(s.l, o, WAVE);
+    q.a = __shfl_xor(s.a, o, WAVE);
+    s = mla_merge(s, q);
+  }
+  return logf(s.l) - s.a / s.l;
+}
+
+// Threshold, prefix rule and compaction over [B, K] entropies, by one workgroup.
+__device__ void prefilter_tail(const float* H, int B, int K, float tau, uint8_t* keep, int* n_keep,
+                               int* surv_idx, int* n_surv, int* s_scan, int* s_carry) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  if (tid == 0) *s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < B; base += nt) {
+    const int b = base + tid;
+    int cnt = 0;
+    if (b < B) {
+      bool alive = true;
+      for (int i = 0; i < K; ++i) {
+        const float hv = __hip_atomic_load(&H[(size_t)b * K + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        alive = alive && !(hv < tau);
+        keep[(size_t)b * K + i] = alive ? 1 : 0;
+        cnt += alive ? 1 : 0;
+      }
+      n_keep[b] = cnt;
+    }
+    s_scan[tid] = cnt;
+    __syncthreads();
+    for (int o = 1; o < nt; o <<= 1) {
+      int v = (tid >= o) ? s_scan[tid - o] : 0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
+    }
+    const int carry = *s_carry;
+    if (b < B) {
+      const int start = carry + s_scan[tid] - cnt;
+      for (int i = 0; i < cnt; ++i) surv_idx[start + i] = b * K + i;   // kept drafts are a prefix
+    }
+    __syncthreads();
+    if (tid == nt - 1) *s_carry = carry + s_scan[nt - 1];
+    __syncthreads();
+  }
+  if (tid == 0) *n_surv = *s_carry;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void entropy_prefilter_kernel(const T* __restrict__ feat, int B, int K, int L,
+                                                                float tau, float* __restrict__ H, uint8_t* keep,
+                                                                int* n_keep, int* surv_idx, int* n_surv,
+                                                                unsigned* ticket) {
+  __shared__ int s_scan[256];
+  __shared__ int s_carry;
+  __shared__ int s_last;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const long rows = (long)B * K;
+  for (long r = (long)blockIdx.x * 4 + wave; r < rows; r += (long)gridDim.x * 4) {
+    const float h = row_entropy_wave(feat + (size_t)r * L, L, lane);
+    if (lane == 0) H[r] = h;
+  }
+  // the workgroup that finishes last sees every H and runs the scan
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned t = atomicAdd(ticket, 1u);
+    s_last = (t == gridDim.x - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  if (threadIdx.x == 0) *ticket = 0;             // ready for the next launch
+  prefilter_tail(H, B, K, tau, keep, n_keep, surv_idx, n_surv, s_scan, &s_carry);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void entropy_rows_kernel(const T* __restrict__ feat, int ld, int rows, int L,
+                                                           float* __restrict__ H) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= rows) return;
+  const float h = row_entropy_wave(feat + (size_t)r * ld, L, lane);
+  if (lane == 0) H[r] = h;
+}
+
+__global__ __launch_bounds__(256) void entropy_step_kernel(const float* __restrict__ ent_heads, int n_heads,
+                                                           const float* __restrict__ H_in, int B, int K, int step,
+                                                           float tau, float* __restrict__ H, uint8_t* keep, int* alive,
+                                                           int* n_keep, int* act_idx, int* n_act, int* emap,
+                                                           int* omap) {
+  __shared__ int s_scan[256];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < B; base += 256) {
+    const int b = base + tid;
+    int now = 0;
+    if (b < B) {
+      float h;
+      if (ent_heads) {
+        float s = 0.f;
+        for (int g = 0; g < n_heads; ++g) s += ent_heads[(size_t)b * n_heads + g];
+        h = s / (float)n_heads;
+      } else {
+        h = H_in[b];
+      }
+      const int was = alive[b];
+      now = (was && !(h < tau)) ? 1 : 0;
+      H[(size_t)b * K + step] = was ? h : 0.f;
+      keep[(size_t)b * K + step] = (uint8_t)now;
+      alive[b] = now;
+      n_keep[b] += now;
+    }
+    s_scan[tid] = now;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {
+      int v = (tid >= o) ? s_scan[tid - o] : 0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
+    }
+    const int carry = s_carry;
+    if (now) {
+      const int r = carry + s_scan[tid] - 1;
+      act_idx[r] = b;
+      emap[r] = b * (K + 1) + step;
+      omap[r] = b * K + step;
+    }
+    __syncthreads();
+    if (tid == 255) s_carry = carry + s_scan[255];
+    __syncthreads();
+  }
+  if (tid == 0) *n_act = s_carry;
+}
+
+// ================================================================== head pieces
+template <typename T>
+__global__ __launch_bounds__(256) void head_prep_kernel(const float* __restrict__ xsrc, const int* __restrict__ xmap,
+                                                        float xscale, int D, const T* __restrict__ w_in,
+                                                        const float* __restrict__ b_in, const float* __restrict__ cz,
+                                                        const float* __restrict__ temb, float* __restrict__ hh,
+                                                        T* __restrict__ sc, float* __restrict__ xt_out, int w, int n,
+                                                        const int* n_dev) {
+  const int ne = eff_rows(n, n_dev);
+  const int r = blockIdx.y;
+  if (r >= ne) return;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const float* xr = xsrc + (size_t)(xmap ? xmap[r] : r) * D;
+  if (c < w) {
+    float v = b_in[c];
+    for (int k = 0; k < D; ++k) v += (xr[k] * xscale) * to_f32(w_in[(size_t)k * w + c]);
+    hh[(size_t)r * w + c] = v;
+    sc[(size_t)r * w + c] = from_f32<T>(silu(cz[(size_t)r * w + c] + temb[c]));
+  }
+  if (xt_out && blockIdx.x == 0 && threadIdx.x < D) xt_out[(size_t)r * D + threadIdx.x] = xr[threadIdx.x] * xscale;
+}
+
+// One wave per row: final AdaLN, output projection to D <= 16 components, sampler update.
+template <typename T>
+__global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
+  const int ne = eff_rows(a.n, a.n_dev);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= ne) return;
+  const int w = a.w, D = a.D;
+  const float* row = a.hh + (size_t)r * w;
+  float s = 0.f;
+  for (int c = lane; c < w; c += WAVE) s += row[c];
+  const float mean = wave_sum(s) / (float)w;
+  float q = 0.f;
+  for (int c = lane; c < w; c += WAVE) { const float t = row[c] - mean; q += t * t; }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)w + 1e-6f);
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+  const T* W = (const T*)a.w_out;
+  for (int c = lane; c < w; c += WAVE) {
+    const float y = (row[c] - mean) * rstd * (1.0f + a.scale[(size_t)r * a.ldm + c]) + a.shift[(size_t)r * a.ldm + c];
+#pragma unroll
+    for (int k = 0; k < 16; ++k)
+      if (k < D) acc[k] += y * to_f32(W[(size_t)c * D + k]);
+  }
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = wave_sum(acc[k]);
+  if (lane < D) {
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v = (lane == k) ? acc[k] : v;
+    v += a.b_out[lane];
+    const size_t xi = (size_t)r * D + lane;
+    const size_t ei = (size_t)(a.emap ? a.emap[r] : r) * D + lane;
+    const size_t oi = (size_t)(a.omap ? a.omap[r] : r) * D + lane;
+    const float xt = a.xt[xi];
+    const float x0 = xt - a.t * v;
+    if (a.last) {
+      a.mu[oi] = x0;
+      a.x[oi] = x0 + a.sigma * a.eps_next[ei];
+    } else {
+      const float e = a.renoise ? a.eps_next[ei] : xt + (1.0f - a.t) * v;
+      a.xt[xi] = (1.0f - a.t_next) * x0 + a.t_next * e;
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void matvec_kernel(const float* __restrict__ in, const T* __restrict__ W,
+                                                     const float* __restrict__ b, int K, int N, int act,
+                                                     float* __restrict__ out) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float v = b ? b[n] : 0.f;
+  for (int k = 0; k < K; ++k) v += in[k] * to_f32(W[(size_t)k * N + n]);
+  out[n] = apply_act(v, act);
+}
+
+// ================================================================== accept test
+__global__ __launch_bounds__(64) void accept_kernel(const float* __restrict__ x, const float* __restrict__ mu_p,
+                                                    const float* __restrict__ mu_q, const float* __restrict__ r,
+                                                    const int* __restrict__ n_keep, float log_sigma, float sigma_p,
+                                                    float sigma_q, int B, int K, int D, int* n_accept,
+                                                    float* log_ratio, uint8_t* acc) {
+  __shared__ int s_acc[256];
+  const int b = blockIdx.x, i = threadIdx.x;
+  const float cst = log_sigma + (float)D * (logf(sigma_q) - logf(sigma_p));
+  const float ip = 1.0f / (2.0f * sigma_p * sigma_p), iq = 1.0f / (2.0f * sigma_q * sigma_q);
+  for (int base = 0; base < K; base += 64) {
+    const int t = base + i;
+    if (t < K) {
+      const float* xv = x + ((size_t)b * K + t) * D;
+      const float* mp = mu_p + ((size_t)b * (K + 1) + t) * D;
+      const float* mq = mu_q + ((size_t)b * K + t) * D;
+      float dp = 0.f, dq = 0.f;
+      for (int c = 0; c < D; ++c) {
+        const float a = xv[c] - mp[c], e = xv[c] - mq[c];
+        dp += a * a;
+        dq += e * e;
+      }
+      const float lr = cst - dp * ip + dq * iq;
+      const int ok = (logf(r[(size_t)b * K + t]) <= lr) ? 1 : 0;
+      log_ratio[(size_t)b * K + t] = lr;
+      acc[(size_t)b * K + t] = (uint8_t)ok;
+      s_acc[t] = ok;
+    }
+  }
+  __syncthreads();
+  if (i == 0) {
+    const int lim = n_keep[b] < K ? n_keep[b] : K;
+    int n = 0;
+    while (n < lim && s_acc[n]) ++n;
+    n_accept[b] = n;
+  }
+}
+
+__global__ void len_add_kernel(int* cache_len, const int* n, int base, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) cache_len[b] += base + (n ? n[b] : 0);
+}
+__global__ void fill_i32_kernel(int* p, int v, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void fill_f32_kernel(float* p, float v, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+template <typename E>
+__global__ void scatter_rows_kernel(const E* __restrict__ src, E* __restrict__ dst, const int* __restrict__ dmap,
+                                    int width, int n, const int* n_dev) {
+  const int ne = eff_rows(n, n_dev);
+  const int r = blockIdx.y;
+  if (r >= ne) return;
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c < width) dst[(size_t)(dmap ? dmap[r] : r) * width + c] = src[(size_t)r * width + c];
+}
+
+}  // namespace
+
+// ====================================================================== launchers
+hipError_t launch_build_rows(hipStream_t s, const int* n_base, int add, int B, int K, int D, const int* cache_len,
+                             RowMaps maps, const float* x_first, const float* x_rest, float* x_out, int* aux_row,
+                             int m_max, int nq_cap) {
+  build_rows_kernel<<<1, 256, 0, s>>>(n_base, add, B, K, D, cache_len, maps, x_first, x_rest, x_out, aux_row, m_max,
+                                      nq_cap);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed(hipStream_t s, int is_bf16, const float* x, int ldx, int D, const void* w_in, const float* b_in,
+                        const void* pos_table, const int* row_pos, const void* cond_table, const int* cond_id,
+                        float* h, int d, int M, const int* m_dev) {
+  if (M <= 0) return hipSuccess;
+  dim3 grid((d + 255) / 256, M);
+  if (is_bf16)
+    embed_kernel<bf16><<<grid, 256, 0, s>>>(x, ldx, D, (const bf16*)w_in, b_in, (const bf16*)pos_table, row_pos,
+                                            (const bf16*)cond_table, cond_id, h, d, M, m_dev);
+  else
+    embed_kernel<float><<<grid, 256, 0, s>>>(x, ldx, D, (const float*)w_in, b_in, (const float*)pos_table, row_pos,
+                                             (const float*)cond_table, cond_id, h, d, M, m_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M, const int* m_dev, int norm_type,
+                       float eps, const float* g, const float* b, const float* shift, const float* scale, int ldm,
+                       const int* in_map, void* out) {
+  if (M <= 0) return hipSuccess;
+  if (is_bf16)
+    norm_kernel<bf16><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out);
+  else
+    norm_kernel<float><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_append(hipStream_t s, void* qkv, int ld, int n_heads, KvGeom kv, int rope, float rope_theta,
+                              const int* row_sample, const int* row_pos, int M, const int* m_dev) {
+  if (M <= 0) return hipSuccess;
+  if (kv.is_bf16)
+    rope_append_kernel<bf16><<<M, 256, 0, s>>>((bf16*)qkv, ld, n_heads, kv, rope, rope_theta, row_sample, row_pos, M, m_dev);
+  else
+    rope_append_kernel<float><<<M, 256, 0, s>>>((float*)qkv, ld, n_heads, kv, rope, rope_theta, row_sample, row_pos, M, m_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v, int B, int n) {
+  const size_t total = (size_t)B * kv.n_kv_heads * n * kv.d_head;
+  if (total == 0) return hipSuccess;
+  size_t blocks = (total + 255) / 256;
+  if (blocks > 65535) blocks = 65535;
+  if (kv.is_bf16)
+    kv_load_kernel<bf16><<<(unsigned)blocks, 256, 0, s>>>(kv, (const bf16*)k, (const bf16*)v, B, n);
+  else
+    kv_load_kernel<float><<<(unsigned)blocks, 256, 0, s>>>(kv, (const float*)k, (const float*)v, B, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L, float tau,
+                                    float* H, uint8_t* keep, int* n_keep, int* surv_idx, int* n_surv,
+                                    unsigned* ticket) {
+  const long rows = (long)B * K;
+  long blocks = (rows + 3) / 4;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 8192) blocks = 8192;              // grid-stride beyond this: 32 workgroups per CU
+  if (is_bf16)
+    entropy_prefilter_kernel<bf16><<<(unsigned)blocks, 256, 0, s>>>((const bf16*)feat, B, K, L, tau, H, keep, n_keep,
+                                                                    surv_idx, n_surv, ticket);
+  else
+    entropy_prefilter_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const float*)feat, B, K, L, tau, H, keep, n_keep,
+                                                                     surv_idx, n_surv, ticket);
+  return hipGetLastError();
+}
+
+hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H) {
+  if (rows <= 0) return hipSuccess;
+  entropy_rows_kernel<float><<<(rows + 3) / 4, 256, 0, s>>>(feat, ld, rows, L, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_entropy_step(hipStream_t s, const float* ent_heads, int n_heads, const float* H_in, int B, int K,
+                               int step, float tau, float* H, uint8_t* keep, int* alive, int* n_keep, int* act_idx,
+                               int* n_act, int* emap, int* omap) {
+  entropy_step_kernel<<<1, 256, 0, s>>>(ent_heads, n_heads, H_in, B, K, step, tau, H, keep, alive, n_keep, act_idx,
+                                        n_act, emap, omap);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_prep(hipStream_t s, int is_bf16, const float* xsrc, const int* xmap, float xscale, int D,
+                            const void* w_in, const float* b_in, const float* cz, const float* temb, float* hh,
+                            void* sc, float* xt_out, int w, int n, const int* n_dev) {
+  if (n <= 0) return hipSuccess;
+  dim3 grid((w + 255) / 256, n);
+  if (is_bf16)
+    head_prep_kernel<bf16><<<grid, 256, 0, s>>>(xsrc, xmap, xscale, D, (const bf16*)w_in, b_in, cz, temb, hh,
+                                                (bf16*)sc, xt_out, w, n, n_dev);
+  else
+    head_prep_kernel<float><<<grid, 256, 0, s>>>(xsrc, xmap, xscale, D, (const float*)w_in, b_in, cz, temb, hh,
+                                                 (float*)sc, xt_out, w, n, n_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_out(hipStream_t s, int is_bf16, const HeadStepArgs& a) {
+  if (a.n <= 0) return hipSuccess;
+  if (a.D > 16) return hipErrorInvalidValue;
+  if (is_bf16)
+    head_out_kernel<bf16><<<(a.n + 3) / 4, 256, 0, s>>>(a);
+  else
+    head_out_kernel<float><<<(a.n + 3) / 4, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_matvec(hipStream_t s, int is_bf16, const float* in, const void* W, const float* b, int K, int N,
+                         int act, float* out) {
+  if (is_bf16)
+    matvec_kernel<bf16><<<(N + 255) / 256, 256, 0, s>>>(in, (const bf16*)W, b, K, N, act, out);
+  else
+    matvec_kernel<float><<<(N + 255) / 256, 256, 0, s>>>(in, (const float*)W, b, K, N, act, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_accept(hipStream_t s, const float* x, const float* mu_p, const float* mu_q, const float* r,
+                         const int* n_keep, float log_sigma, float sigma_p, float sigma_q, int B, int K, int D,
+                         int* n_accept, float* log_ratio, uint8_t* acc) {
+  if (B <= 0) return hipSuccess;
+  accept_kernel<<<B, 64, 0, s>>>(x, mu_p, mu_q, r, n_keep, log_sigma, sigma_p, sigma_q, B, K, D, n_accept, log_ratio, acc);
+  return hipGetLastError();
+}
+
+hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B) {
+  len_add_kernel<<<(B + 255) / 256, 256, 0, s>>>(cache_len, n, base, B);
+  return hipGetLastError();
+}
+hipError_t launch_fill_i32(hipStream_t s, int* p, int v, int n) {
+  if (n <= 0) return hipSuccess;
+  fill_i32_kernel<<<(n + 255) / 256, 256, 0, s>>>(p, v, n);
+  return hipGetLastError();
+}
+hipError_t launch_fill_f32(hipStream_t s, float* p, float v, size_t n) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  fill_f32_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, v, n);
+  return hipGetLastError();
+}
+hipError_t launch_scatter_rows(hipStream_t s, const void* src, void* dst, const int* dmap, int width, int elem_size,
+                               int n, const int* n_dev) {
+  if (n <= 0) return hipSuccess;
+  dim3 grid((width + 255) / 256, n);
+  if (elem_size == 4)
+    scatter_rows_kernel<float><<<grid, 256, 0, s>>>((const float*)src, (float*)dst, dmap, width, n, n_dev);
+  else
+    scatter_rows_kernel<bf16><<<grid, 256, 0, s>>>((const bf16*)src, (bf16*)dst, dmap, width, n, n_dev);
+  return hipGetLastError();
+}
+
+}  // namespace fard

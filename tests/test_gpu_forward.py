@@ -1,0 +1,128 @@
+"""GPU parity of the KV-cached transformer forward (spec_forward) against the CPU oracle."""
+import numpy as np
+import pytest
+
+from synth import gen
+from synth.configs import DT_BF16, DT_F32
+from tests.harness import build_case, make_ctx, oracle_caches, rel_inf
+
+pytestmark = pytest.mark.gpu
+
+TOL = {DT_BF16: 2e-2, DT_F32: 2e-4}
+
+
+def _oracle_forward(case, which, xs, ids=None, commit=False, shallow=None, caches=None):
+    from oracle import transformer as tf
+    tc, dc = caches or oracle_caches(case)
+    cfg, cache, prefix = (case.rc.target, tc, "target") if which == 0 else (case.rc.draft, dc, "draft")
+    return tf.forward(cfg, case.W, prefix, cache, xs, ids=ids, commit=commit, shallow_layer=shallow)
+
+
+def _pack(xs):
+    return np.concatenate([x for x in xs if len(x)], axis=0).astype(np.float32)
+
+
+@pytest.mark.parametrize("kind", ["ln-gelu-bf16", "gqa-rope-bf16", "ln-gelu-f32", "mid-bf16"])
+@pytest.mark.parametrize("which", [0, 1])
+def test_forward_matches_oracle_with_ragged_rows(kind, which):
+    case = build_case(kind, seed=21, std_overrides={"wqkv": 0.15})
+    rc = case.rc
+    ctx = make_ctx(case)
+    B, K, D = case.B, rc.K, rc.target.d_latent
+    rng = np.random.default_rng(3)
+    n_q = rng.integers(0, K + 2, size=B)
+    n_q[0] = K + 1
+    if B > 1:
+        n_q[1] = 0                                       # an empty sample in the middle
+    xs = [gen.bf16_round(rng.normal(size=(n, D)).astype(np.float32)) for n in n_q]
+    z, sh, ha = ctx.spec_forward(which, ctx.dev_f32(_pack(xs)), n_q, commit=False, want_shallow=True,
+                                 want_h_attn=True)
+    ctx.sync()
+    zo, sho, hao = _oracle_forward(case, which, xs, shallow=rc.entropy_layer)
+    zo, sho, hao = np.concatenate(zo), np.concatenate(sho), np.concatenate(hao)
+    tol = TOL[rc.dtype]
+    assert rel_inf(z.float().cpu().numpy(), zo) < tol
+    assert rel_inf(sh.cpu().numpy(), sho) < tol
+    assert np.abs(ha.cpu().numpy() - hao).max() < (5e-3 if rc.dtype == DT_BF16 else 1e-4)
+    # commit=False leaves lengths alone
+    assert np.array_equal(ctx.spec_kv_lengths(which, B), np.full(B, case.n_ctx))
+    ctx.close()
+
+
+@pytest.mark.parametrize("kind", ["ln-gelu-bf16", "gqa-rope-bf16", "ln-gelu-f32"])
+def test_chunked_prefill_equals_one_shot_and_oracle(kind):
+    """Cache built by the library's own forward in chunks (3 + 1 + 4 rows ...) must give the same
+    features as the oracle's full recompute: cached == recompute on the GPU path."""
+    from oracle import loops
+    case = build_case(kind, seed=22, std_overrides={"wqkv": 0.15})
+    rc = case.rc
+    ctx = make_ctx(case)
+    B, D = case.B, rc.target.d_latent
+    rng = np.random.default_rng(4)
+    n_tot = 33 if kind != "gqa-rope-bf16" else 30
+    x_all = gen.bf16_round(rng.normal(size=(B, n_tot, D)).astype(np.float32))
+    ctx.spec_kv_reset(0, np.zeros(B, np.int32))
+    outs = [[] for _ in range(B)]
+    start = 0
+    cmax = rc.K + 1                                     # rows per sample the workspace holds
+    chunks, left, pat = [], n_tot, [3, 1, cmax, 2, cmax]
+    while left > 0:
+        c = min(pat[len(chunks) % len(pat)], left)
+        chunks.append(c)
+        left -= c
+    for c in chunks:
+        xs = x_all[:, start:start + c].reshape(B * c, D)
+        z, _, _ = ctx.spec_forward(0, ctx.dev_f32(xs), np.full(B, c), commit=True)
+        ctx.sync()
+        zz = z.float().cpu().numpy().reshape(B, c, -1)
+        for b in range(B):
+            outs[b].append(zz[b])
+        start += c
+    assert np.array_equal(ctx.spec_kv_lengths(0, B), np.full(B, n_tot))
+    for b in (0, B - 1):
+        zo, _, _ = loops.full_recompute(rc.target, case.W, "target", x_all[b])
+        assert rel_inf(np.concatenate(outs[b]), zo) < TOL[rc.dtype]
+    ctx.close()
+
+
+def test_class_id_rows():
+    case = build_case("ln-gelu-bf16", seed=23)
+    rc = case.rc
+    ctx = make_ctx(case)
+    B, D = case.B, rc.target.d_latent
+    ctx.spec_kv_reset(0, np.zeros(B, np.int32))
+    rng = np.random.default_rng(5)
+    xs = [gen.bf16_round(rng.normal(size=(3, D)).astype(np.float32)) for _ in range(B)]
+    ids = [np.array([b + 2, -1, -1]) for b in range(B)]
+    z, _, _ = ctx.spec_forward(0, ctx.dev_f32(_pack(xs)), np.full(B, 3), cond_id=ctx.dev_i32(np.concatenate(ids)),
+                               commit=False)
+    ctx.sync()
+    from oracle import transformer as tf
+    cache = tf.KVCache(rc.target, B)
+    zo, _, _ = tf.forward(rc.target, case.W, "target", cache, xs, ids=ids, commit=False)
+    assert rel_inf(z.float().cpu().numpy(), np.concatenate(zo)) < 2e-2
+    ctx.close()
+
+
+def test_capacity_and_argument_errors():
+    from paper_2512_08537_amd.binding import FardError
+    case = build_case("ln-gelu-bf16", seed=24)
+    ctx = make_ctx(case)
+    B, D = case.B, 16
+    x = ctx.dev_f32(np.zeros((B, D), np.float32))
+    ctx.spec_kv_reset(0, np.full(B, case.rc.max_ctx, np.int32))
+    with pytest.raises(FardError) as e:
+        ctx.spec_forward(0, x, np.ones(B))
+    assert e.value.code == -3
+    with pytest.raises(FardError) as e:
+        ctx.spec_kv_reset(0, np.full(B, case.rc.max_ctx + 1, np.int32))
+    assert e.value.code == -3
+    big = ctx.dev_f32(np.zeros((case.rc.max_batch * (case.rc.K + 1) + 1, D), np.float32))
+    ctx.spec_kv_reset(0, np.zeros(B, np.int32))
+    with pytest.raises(FardError) as e:
+        ctx.spec_forward(0, big, np.ones(B))
+    assert e.value.code == -3
+    with pytest.raises(FardError) as e:
+        ctx.spec_kv_commit(-1, ctx.dev_i32(np.zeros(B)))
+    assert e.value.code == -6
+    ctx.close()

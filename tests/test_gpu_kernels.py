@@ -1,0 +1,254 @@
+"""GPU parity of the single kernels behind the C-ABI: GEMM, entropy pre-filter, head, accept.
+Each result is compared element by element with the CPU oracle on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+
+from synth import gen
+from synth.configs import reduced, config, DT_BF16, DT_F32, clone
+from tests.harness import build_case, make_ctx, rel_inf, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx_bf16():
+    case = build_case("ln-gelu-bf16", seed=3)
+    ctx = make_ctx(case)
+    yield ctx, case
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def ctx_f32():
+    case = build_case("ln-gelu-f32", seed=3)
+    ctx = make_ctx(case)
+    yield ctx, case
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("M,K,N", [(1, 64, 32), (5, 64, 32), (32, 128, 128), (33, 192, 96), (96, 256, 256),
+                                   (97, 128, 160), (288, 1024, 1024), (72, 512, 2048), (200, 2048, 320)])
+@pytest.mark.parametrize("act", [0, 1, 2])
+def test_gemm_bf16_matches_fp64(ctx_bf16, M, K, N, act):
+    from oracle import transformer as otf
+    ctx, _ = ctx_bf16
+    A = gen.normal(11, f"A{M}{K}", (M, K), 1.0, DT_BF16)
+    W = gen.normal(11, f"W{K}{N}", (K, N), 0.05, DT_BF16)
+    b = gen.normal(11, f"b{N}", (N,), 0.1, DT_F32)
+    out = ctx.spec_gemm(ctx.dev_store(A), ctx.dev_store(W), ctx.dev_f32(b), act)
+    ctx.sync()
+    ref = A.astype(np.float64) @ W.astype(np.float64) + b
+    ref = {0: lambda x: x, 1: otf.gelu_erf, 2: otf.silu}[act](ref)
+    got = out.float().cpu().numpy()
+    # fp32 accumulation, one bf16 rounding of the result
+    assert np.allclose(got, ref, rtol=2 ** -7, atol=2e-3 * np.abs(ref).max())
+    assert rel_inf(got, ref) < 1e-2
+
+
+def test_gemm_f32_matches_fp64(ctx_f32):
+    ctx, _ = ctx_f32
+    for (M, K, N) in [(5, 16, 7), (33, 100, 65), (16, 256, 48)]:
+        A = gen.normal(12, f"A{M}", (M, K), 1.0, DT_F32)
+        W = gen.normal(12, f"W{N}", (K, N), 0.05, DT_F32)
+        out = ctx.spec_gemm(ctx.dev_store(A), ctx.dev_store(W), None, 0)
+        ctx.sync()
+        ref = A.astype(np.float64) @ W.astype(np.float64)
+        assert rel_inf(out.cpu().numpy(), ref) < 1e-5
+
+
+# ----------------------------------------------------------------------------- entropy pre-filter
+def _check_prefilter(ctx, feat, tau, dtype_tol=1e-3):
+    from oracle import entropy as ent
+    B, K, L = feat.shape
+    H, keep, n_keep, surv, n_surv = ctx.entropy_prefilter(ctx.dev_store(feat), tau)
+    ctx.sync()
+    H, keep, n_keep, surv, n_surv = (t.cpu().numpy() for t in (H, keep, n_keep, surv, n_surv))
+    Ho = ent.softmax_entropy(feat.astype(np.float64))
+    assert np.abs(H - Ho).max() <= dtype_tol, np.abs(H - Ho).max()
+    ko, nko, so, nso = ent.prefilter(Ho, tau)
+    near = np.abs(Ho - tau) <= 1e-3                      # decisions this close to tau may flip
+    if not near.any():
+        assert np.array_equal(keep, ko)
+        assert np.array_equal(n_keep, nko)
+        assert int(n_surv[0]) == nso and np.array_equal(surv[:nso], so)
+    else:
+        # off-threshold rows before the first near-threshold row of a sample must agree
+        for b in range(B):
+            first = np.argmax(near[b]) if near[b].any() else K
+            assert np.array_equal(keep[b, :first], ko[b, :first])
+    # what is unique regardless of ties: consistency of the outputs with the kernel's own H
+    kg, nkg, sg, nsg = ent.prefilter(H.astype(np.float64), np.float32(tau))
+    assert np.array_equal(keep, kg) and np.array_equal(n_keep, nkg)
+    assert int(n_surv[0]) == nsg and np.array_equal(surv[:nsg], sg)
+    return H, Ho
+
+
+@pytest.mark.parametrize("B,K,L", [(1, 4, 256), (32, 8, 1024), (64, 8, 1280), (8, 8, 2048), (3, 5, 130), (2, 1, 1),
+                                   (7, 3, 9)])
+def test_prefilter_shapes(ctx_bf16, B, K, L):
+    ctx, _ = ctx_bf16
+    feat = gen.normal(5, f"feat{B}{K}{L}", (B, K, L), 2.0, DT_BF16)
+    from oracle import entropy as ent
+    Ho = ent.softmax_entropy(feat.astype(np.float64))
+    tau = float(np.median(Ho)) if Ho.size > 1 else 0.0
+    _check_prefilter(ctx, feat, tau + 3e-3)
+
+
+def test_prefilter_stress_fractions(ctx_bf16):
+    """Features built so that 0/25/50/75/100 % of drafts fall below the threshold (uniform and ragged)."""
+    from oracle import entropy as ent
+    ctx, _ = ctx_bf16
+    B, K, d = 256, 8, 1280
+    cal = gen.stress_features(1, 64, K, d, np.full(64, K), DT_BF16)
+    Hc = ent.softmax_entropy(cal.astype(np.float64))
+    tau = ent.threshold(Hc)
+    assert abs(tau - 0.3 * 7.12) < 0.02
+    for frac in (0.0, 0.25, 0.5, 0.75, 1.0):
+        for ragged in (False, True):
+            cut = gen.cuts_for_fraction(2, B, K, frac, ragged)
+            feat = gen.stress_features(2, B, K, d, cut, DT_BF16)
+            H, keep, n_keep, surv, n_surv = ctx.entropy_prefilter(ctx.dev_store(feat), tau)
+            ctx.sync()
+            assert np.array_equal(n_keep.cpu().numpy(), cut)
+            assert int(n_surv.cpu()[0]) == int(cut.sum())
+            assert abs(cut.sum() / (B * K) - (1 - frac)) < 1e-9 or ragged
+            Ho = ent.softmax_entropy(feat.astype(np.float64))
+            assert np.abs(H.cpu().numpy() - Ho).max() < 1e-3
+
+
+def test_prefilter_closed_forms_and_edges(ctx_bf16):
+    ctx, _ = ctx_bf16
+    B, K, L = 4, 3, 512
+    feat = np.zeros((B, K, L), np.float32)
+    feat[1, 1, 7] = 60.0                                   # one-hot row: H = 0 -> sample 1 keeps 1 draft
+    feat[2, 0, :] = 3.25                                   # constant rows are uniform: H = ln L
+    H, keep, n_keep, surv, n_surv = ctx.entropy_prefilter(ctx.dev_store(feat), 1.0)
+    ctx.sync()
+    H = H.cpu().numpy()
+    assert np.allclose(np.delete(H.reshape(-1), 4), math.log(L), atol=1e-4)
+    assert abs(H[1, 1]) < 1e-6
+    assert n_keep.cpu().tolist() == [3, 1, 3, 3]
+    assert surv.cpu().numpy()[:int(n_surv.cpu()[0])].tolist() == [0, 1, 2, 3, 6, 7, 8, 9, 10, 11]
+    # everything filtered / empty batch
+    H, keep, n_keep, surv, n_surv = ctx.entropy_prefilter(ctx.dev_store(feat), 100.0)
+    ctx.sync()
+    assert int(n_surv.cpu()[0]) == 0 and not keep.cpu().numpy().any()
+    import torch
+    empty = torch.empty((0, 3, 16), dtype=ctx.tdtype, device=ctx.dev)
+    H, keep, n_keep, surv, n_surv = ctx.entropy_prefilter(empty, 1.0)
+    ctx.sync()
+    assert int(n_surv.cpu()[0]) == 0
+
+
+def test_prefilter_near_threshold_rows(ctx_bf16):
+    """Rows whose entropy is bisected onto tau +- 1e-3: only those may disagree with the oracle."""
+    from oracle import entropy as ent
+    ctx, _ = ctx_bf16
+    B, K, d = 16, 8, 1280
+    tau = 2.14
+    rng = np.random.default_rng(0)
+    feat = gen.stress_features(4, B, K, d, np.full(B, K), DT_BF16)
+    for b in range(0, B, 2):
+        i = int(rng.integers(0, K))
+        base = feat[b, i].astype(np.float64).copy()
+        j = int(rng.integers(0, d))
+        lo, hi = 0.0, 14.0
+        target = tau + 1e-3 * rng.uniform(-1, 1)
+        for _ in range(60):
+            mid = 0.5 * (lo + hi)
+            row = base.copy()
+            row[j] += mid
+            if ent.softmax_entropy(gen.bf16_round(row.astype(np.float32))) > target:
+                lo = mid
+            else:
+                hi = mid
+        base[j] += lo
+        feat[b, i] = gen.bf16_round(base.astype(np.float32))
+    _check_prefilter(ctx, feat, tau)
+
+
+def test_prefilter_f32(ctx_f32):
+    ctx, _ = ctx_f32
+    feat = gen.normal(6, "featf32", (4, 4, 256), 3.0, DT_F32)
+    _check_prefilter(ctx, feat, 3.0, dtype_tol=1e-4)
+
+
+# ----------------------------------------------------------------------------- head
+@pytest.mark.parametrize("fix", ["ctx_bf16", "ctx_f32"])
+def test_diffhead_decode_matches_oracle(fix, request):
+    from oracle import head as ohd
+    ctx, case = request.getfixturevalue(fix)
+    rc = case.rc
+    n, D, S = 11, rc.head.d_latent, rc.head.n_steps
+    z = gen.normal(8, "z", (n, rc.head.d_cond), 1.0, rc.dtype)
+    eps = gen.noise(8, "eps", (S + 1, n, D))
+    mu, x = ctx.diffhead_decode(ctx.dev_store(z), ctx.dev_f32(eps))
+    ctx.sync()
+    mu_o, x_o = ohd.decode(rc.head, case.W, z, eps)
+    tol = 2e-2 if rc.dtype == DT_BF16 else 1e-4
+    assert rel_inf(mu.cpu().numpy(), mu_o) < tol
+    assert rel_inf(x.cpu().numpy(), x_o) < tol
+    # device-side row count: rows beyond it stay untouched (zero-initialised by the binding)
+    import torch
+    cnt = torch.tensor([4], dtype=torch.int32, device=ctx.dev)
+    mu2, x2 = ctx.diffhead_decode(ctx.dev_store(z), ctx.dev_f32(eps), n_rows=cnt)
+    ctx.sync()
+    assert rel_inf(mu2.cpu().numpy()[:4], mu_o[:4]) < tol
+    assert not mu2.cpu().numpy()[4:].any()
+
+
+def test_head_closed_form_zero_weights():
+    """All head weights zero except the output bias: mu = temperature*eps0 - b_out (1 step)."""
+    case = build_case("ln-gelu-bf16", seed=1)
+    case.rc.head.n_steps = 1
+    for k in list(case.W):
+        if k.startswith("head."):
+            case.W[k] = np.zeros_like(case.W[k])
+    b = gen.bf16_round(np.linspace(-1, 1, 16).astype(np.float32))
+    case.W["head.out.b"] = b
+    ctx = make_ctx(case)
+    eps = gen.noise(9, "e", (2, 5, 16))
+    z = gen.normal(9, "z", (5, case.rc.head.d_cond), 1.0, DT_BF16)
+    mu, x = ctx.diffhead_decode(ctx.dev_store(z), ctx.dev_f32(eps))
+    ctx.sync()
+    assert np.allclose(mu.cpu().numpy(), eps[0] - b, atol=1e-6)
+    assert np.allclose(x.cpu().numpy(), eps[0] - b + 0.25 * eps[1], atol=1e-6)
+    ctx.close()
+
+
+# ----------------------------------------------------------------------------- accept
+def test_accept_matches_oracle_on_identical_inputs(ctx_bf16):
+    from oracle import accept as oac
+    ctx, case = ctx_bf16
+    K, D, B = case.rc.K, 16, 64
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(B, K, D)).astype(np.float32)
+    mu_q = (x + 0.2 * rng.normal(size=(B, K, D))).astype(np.float32)
+    mu_p = np.concatenate([mu_q + 0.08 * rng.normal(size=(B, K, D)), rng.normal(size=(B, 1, D))], 1).astype(np.float32)
+    r = rng.random((B, K)).astype(np.float32)
+    r[0, 0] = 0.0
+    n_keep = rng.integers(0, K + 1, size=B).astype(np.int32)
+    for (ls, sp, sq) in [(0.0, 0.25, 0.25), (0.3, 0.3, 0.25)]:
+        n_acc, lr, acc = ctx.spec_accept(ctx.dev_f32(x), ctx.dev_f32(mu_p), ctx.dev_f32(mu_q), ctx.dev_f32(r),
+                                         ctx.dev_i32(n_keep), ls, sp, sq)
+        ctx.sync()
+        n_o, lr_o, acc_o = oac.accept(x, mu_p, mu_q, r, n_keep, ls, sp, sq)
+        lr = lr.cpu().numpy()
+        assert np.allclose(lr, lr_o, rtol=1e-4, atol=1e-3)
+        with np.errstate(divide="ignore"):
+            margin = np.abs(lr_o - np.log(r.astype(np.float64)))
+        safe = margin > 1e-3 * np.maximum(1.0, np.abs(lr_o))
+        assert np.array_equal(acc.cpu().numpy()[safe], acc_o[safe])
+        rows_safe = safe.all(axis=1)
+        assert np.array_equal(n_acc.cpu().numpy()[rows_safe], n_o[rows_safe])
+        assert rows_safe.sum() > B // 2
+    # equal means: ratio 1, everything kept is accepted
+    mu_same = np.concatenate([mu_q, mu_q[:, :1]], 1)
+    n_acc, lr, _ = ctx.spec_accept(ctx.dev_f32(x), ctx.dev_f32(mu_same), ctx.dev_f32(mu_q), ctx.dev_f32(r),
+                                   ctx.dev_i32(n_keep), 0.0, 0.25, 0.25)
+    ctx.sync()
+    assert np.array_equal(n_acc.cpu().numpy(), n_keep)
+    assert np.abs(lr.cpu().numpy()).max() == 0.0
