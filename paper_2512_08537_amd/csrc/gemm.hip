@@ -1,12 +1,18 @@
 // GEMM kernels: out = epilogue(A[M,K] * W[K,N]).
 //
-// bf16 path (gfx950 MFMA): weights are pre-laid in v_mfma_f32_32x32x16_bf16 B-fragment order so
-// that every wave streams them from HBM straight into registers with fully contiguous 1 KiB
-// loads (no LDS round trip for the operand that dominates the bytes when M is a few hundred
-// rows).  The small activation tile goes through LDS, double-buffered, and is shared by the
-// waves of a workgroup, each of which owns its own 32*WN output columns.  Workgroups are
-// numbered so that all M-tiles of one weight panel land on the same XCD (ids are dealt to the
-// 8 XCDs round-robin) and the panel is fetched from HBM once per L2.
+// bf16 path (gfx950 MFMA).  The GEMMs of a speculative round are skinny (M = a few hundred rows at
+// most) and small (2-50 MB of weights each), so one launch lives or dies by how many weight bytes
+// it keeps in flight, not by MFMA issue rate.  Design:
+//  * weights are pre-laid in v_mfma_f32_32x32x16_bf16 B-fragment order, so every wave streams them
+//    from HBM straight into registers as fully contiguous 1 KiB loads, through a register ring that
+//    keeps P k-steps (8-16 KiB per wave) in flight; they never touch LDS;
+//  * the activation panel of a workgroup (BM rows x KC = 256 k) is staged in LDS once per chunk and
+//    shared by the 4 waves, each of which owns its own 32*WN output columns; the next chunk is
+//    prefetched into registers while the current one is consumed, so the inner loop has no barrier;
+//  * K is split across workgroups when the tile grid alone cannot cover the chip (residual-stream
+//    epilogues add their partial sums with fp32 atomics);
+//  * workgroups are numbered so that all M-tiles of one weight panel land on the same XCD (ids are
+//    dealt to the 8 XCDs round-robin): the panel is fetched from HBM once per L2.
 //
 // fp32 path: a plain LDS-tiled FMA kernel, used by the small all-fp32 configuration.
 #include "gemm.h"
@@ -15,17 +21,76 @@ namespace fard {
 
 namespace {
 
-constexpr int BK = 64;                 // k per pipeline step (4 MFMA k-blocks of 16)
-constexpr int LDS_STRIDE = BK + 8;     // bf16 per LDS row: 144 B keeps 16-byte reads conflict-poor
+// KC: k per staged activation chunk (template parameter, 256 or 512).  LDS rows are KC + 8 bf16 long
+// (528 / 1040 B): the 16-byte reads of 32 consecutive rows spread over all banks.
 
-template <int WM, int WN, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_bf16_kernel(GemmArgs a, int n_tiles, int m_tiles,
-                                                            int splits, int steps_per_split) {
+// Register e of a 32x32 accumulator holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+template <int KIND, bool FULL, int WM, int WN>
+__device__ __forceinline__ void epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN], int m0, int M, int nb0, int nblocks,
+                                         int cl, int rhalf, bool add_bias, bool atomic) {
+  if constexpr (KIND == EPI_SWIGLU) {
+    if constexpr (WN == 2) {
+      if (nb0 + 1 >= nblocks) return;
+      const int col = (nb0 >> 1) * 32 + cl;
+      bf16* out = (bf16*)a.out;
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = m0 + 32 * i + 8 * (e >> 2) + rhalf + (e & 3);
+          if (FULL || row < M) out[(size_t)row * a.ldo + col] = (bf16)(silu(acc[i][0][e]) * acc[i][1][e]);
+        }
+    }
+    return;
+  } else {
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      if (nb0 + j >= nblocks) continue;
+      const int col = (nb0 + j) * 32 + cl;
+      const float bv = (a.bias != nullptr && add_bias) ? a.bias[col] : 0.f;
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = m0 + 32 * i + 8 * (e >> 2) + rhalf + (e & 3);
+          if (!FULL && row >= M) continue;
+          float v = acc[i][j][e] + bv;
+          const size_t o = (size_t)row * a.ldo + col;
+          if constexpr (KIND == EPI_STORE) {
+            ((bf16*)a.out)[o] = (bf16)apply_act(v, a.act);
+          } else if constexpr (KIND == EPI_STORE_F32) {
+            ((float*)a.out)[o] = apply_act(v, a.act);
+          } else {
+            if constexpr (KIND == EPI_GATE_RESID) v *= a.gate[(size_t)row * a.ldg + col];
+            float* dst = (float*)a.out + o;
+            if (atomic) atomicAdd(dst, v);       // partial sums of a split K range meet in memory
+            else *dst += v;
+          }
+        }
+    }
+  }
+}
+
+// WM x WN: 32x32 accumulator blocks per wave.  KW: waves of the workgroup that share the same output
+// columns and split every chunk's 16 k-steps between them (their partial sums meet in LDS at the end);
+// the other 4/KW waves sit side by side along N.  P: ring depth in k-steps of one wave.
+template <int WM, int WN, int KW, int P, int KC>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles, int m_tiles, int splits,
+                                                        int chunks_per_split) {
+  constexpr int KSTEPS = KC / 16;                          // MFMA k-steps per chunk
+  constexpr int LDS_STRIDE = KC + 8;
+  constexpr int RPP = KC / 8;                              // 16-byte pieces per row of a chunk
+  constexpr int NWN = 4 / KW;                              // waves along N
+  constexpr int SPW = KSTEPS / KW;                         // k-steps per wave per chunk
+  constexpr int G = (P > SPW) ? P : SPW;                   // k-steps per unrolled group (both powers of two)
   constexpr int BM = 32 * WM;
-  constexpr int THREADS = 64 * NW;
-  constexpr int CHUNKS = BM * (BK / 8);                    // 16-byte chunks in one A tile
-  constexpr int CPT = (CHUNKS + THREADS - 1) / THREADS;    // chunks per thread
-  __shared__ __attribute__((aligned(16))) bf16 lds[2][BM * LDS_STRIDE];
+  constexpr int PIECES = BM * (KC / 8);                    // 16-byte pieces in one A chunk
+  constexpr int PPT = PIECES / 256;                        // pieces per thread (BM multiple of 32 -> exact)
+  constexpr int RED_FLOATS = (KW > 1) ? NWN * WM * WN * 16 * 64 : 0;
+  constexpr int LDS_BYTES = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
+  static_assert(G % P == 0 && G % SPW == 0, "ring depth and steps per wave must be powers of two");
+  __shared__ __attribute__((aligned(16))) char lds_raw[LDS_BYTES];
+  bf16* lds = (bf16*)lds_raw;
 
   // blockIdx -> (weight panel, m tile): panels are dealt to XCDs, the m tiles of a panel are
   // consecutive slots of that XCD.
@@ -41,13 +106,17 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_kernel(GemmArgs a, int n_ti
   if (m0 >= M) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave % KW, nw = wave / KW;
   const int nblocks = a.N >> 5;
-  const int kb16 = a.K >> 4;
-  const int nb0 = (nt * NW + wave) * WN;
-  const int total_steps = a.K / BK;
-  const int t_begin = sp * steps_per_split;
-  int T = total_steps - t_begin;
-  if (T > steps_per_split) T = steps_per_split;
+  const int kb16 = a.K >> 4;                               // k-steps in the whole K
+  const int nb0 = (nt * NWN + nw) * WN;
+  const int total_chunks = (a.K + KC - 1) / KC;
+  const int c_begin = sp * chunks_per_split;
+  int n_chunks = total_chunks - c_begin;
+  if (n_chunks > chunks_per_split) n_chunks = chunks_per_split;
+  const int s_begin = c_begin * KSTEPS;                    // first global k-step of this workgroup
+  int n_steps = kb16 - s_begin;                            // valid k-steps of this workgroup
+  if (n_steps > n_chunks * KSTEPS) n_steps = n_chunks * KSTEPS;
 
   const bf16* __restrict__ A = (const bf16*)a.A;
   const bf16x8* __restrict__ Wp = (const bf16x8*)a.W;
@@ -60,157 +129,175 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_kernel(GemmArgs a, int n_ti
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 areg[CPT];
-  bf16x8 breg[2][4][WN];
+  bf16x8 zero8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
 
-  auto load_a = [&](int t) {
+  bf16x8 areg[PPT];
+  auto load_a = [&](int chunk) {                           // chunk: index inside this workgroup
+    // unconditional loads from clamped (always valid) addresses keep the loop free of branches, so the
+    // loads stay in flight; rows >= M are never stored, columns past this workgroup's K range are zeroed
+    const int k0 = (c_begin + chunk) * KC;
+    const bool live = chunk < n_chunks;
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int c = tid + i * THREADS;
-      bf16x8 v;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (bf16)0.f;
-      if (c < CHUNKS) {
-        const int row = c >> 3, kc = c & 7;
-        const int gr = m0 + row;
-        if (gr < M) v = *(const bf16x8*)(A + (size_t)gr * a.lda + (size_t)(t_begin + t) * BK + kc * 8);
-      }
-      areg[i] = v;
+    for (int i = 0; i < PPT; ++i) {
+      const int c = tid + i * 256;
+      const int row = c / RPP, kc = c % RPP;
+      const int gr = (m0 + row < M) ? m0 + row : M - 1;
+      const int k = k0 + kc * 8;
+      const bool ok = live && k < a.K;
+      const bf16x8 v = *(const bf16x8*)(A + (size_t)gr * a.lda + (ok ? k : 0));
+      areg[i] = ok ? v : zero8;
     }
   };
-  auto store_a = [&](int buf) {
+  auto store_a = [&]() {
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-      const int c = tid + i * THREADS;
-      if (c < CHUNKS) {
-        const int row = c >> 3, kc = c & 7;
-        *(bf16x8*)(&lds[buf][row * LDS_STRIDE + kc * 8]) = areg[i];
-      }
+    for (int i = 0; i < PPT; ++i) {
+      const int c = tid + i * 256;
+      const int row = c / RPP, kc = c % RPP;
+      *(bf16x8*)(&lds[row * LDS_STRIDE + kc * 8]) = areg[i];
     }
   };
-  auto load_b = [&](int t, bf16x8 (&b)[4][WN]) {
+
+  // B ring: this wave's k-steps, in order q = chunk * SPW + j, live in slot q % P
+  bf16x8 breg[P][WN];
+  const bf16x8* bbase[WN];
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      if (nb0 + j < nblocks) {
-        const bf16x8* p = Wp + ((size_t)(nb0 + j) * kb16 + (size_t)(t_begin + t) * 4) * 64 + lane;
+  for (int j = 0; j < WN; ++j) {
+    const int nb = (nb0 + j < nblocks) ? nb0 + j : 0;      // columns past N: valid reads, never stored
+    bbase[j] = Wp + ((size_t)nb * kb16 + s_begin) * 64 + lane;
+  }
+  auto load_b = [&](int q, int p) {
+    // past the end the last fragment is re-read: it only ever meets zeroed activation columns
+    int s = (q / SPW) * KSTEPS + kw * SPW + (q % SPW);
+    s = s < n_steps ? s : n_steps - 1;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) b[ks][j] = p[ks * 64];
-      }
-    }
-  };
-  auto compute = [&](int buf, const bf16x8 (&b)[4][WN]) {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[WM];
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-        af[i] = *(const bf16x8*)(&lds[buf][(32 * i + (lane & 31)) * LDS_STRIDE + ks * 16 + (lane >> 5) * 8]);
-#pragma unroll
-      for (int j = 0; j < WN; ++j) {
-        if (nb0 + j < nblocks) {
-#pragma unroll
-          for (int i = 0; i < WM; ++i)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], b[ks][j], acc[i][j], 0, 0, 0);
-        }
-      }
-    }
+    for (int j = 0; j < WN; ++j) breg[p][j] = bbase[j][(size_t)s * 64];
   };
 
   load_a(0);
-  load_b(0, breg[0]);
-  store_a(0);
-  __syncthreads();
-  for (int t = 0; t < T; t += 2) {
-    if (t + 1 < T) { load_a(t + 1); load_b(t + 1, breg[1]); }
-    compute(0, breg[0]);
-    if (t + 1 < T) store_a(1);
-    __syncthreads();
-    if (t + 1 < T) {
-      if (t + 2 < T) { load_a(t + 2); load_b(t + 2, breg[0]); }
-      compute(1, breg[1]);
-      if (t + 2 < T) store_a(0);
-      __syncthreads();
+#pragma unroll
+  for (int p = 0; p < P; ++p) load_b(p, p);
+
+  const int q_total = n_chunks * SPW;
+  for (int q0 = 0; q0 < q_total; q0 += G) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int q = q0 + g;
+      if (g % SPW == 0) {                                  // chunk boundary (static position)
+        const int c = q / SPW;
+        if (c > 0) __syncthreads();                        // every wave is done reading the previous chunk
+        store_a();
+        __syncthreads();
+        load_a(c + 1);                                     // prefetch; zeros past the last chunk
+      }
+      const int ks = kw * SPW + (g % SPW);                 // k-step inside the chunk
+      bf16x8 af[WM];
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+        af[i] = *(const bf16x8*)(&lds[(32 * i + (lane & 31)) * LDS_STRIDE + ks * 16 + (lane >> 5) * 8]);
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], breg[g % P][j], acc[i][j], 0, 0, 0);
+      load_b(q + P, g % P);
     }
   }
 
-  // epilogue: register e of a 32x32 accumulator holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
-  const int cl = lane & 31, rhalf = (lane >> 5) * 4;
-  if (a.epi == EPI_SWIGLU) {
-    if constexpr (WN == 2) {
-      if (nb0 + 1 < nblocks) {
-        const int col = (nb0 >> 1) * 32 + cl;
-        bf16* out = (bf16*)a.out;
+  // partial sums of the KW waves that share columns: waves kw > 0 hand theirs over through LDS, one at a time
+  if constexpr (KW > 1) {
+    float* red = (float*)lds_raw + (size_t)nw * WM * WN * 16 * 64;
+    for (int r = 1; r < KW; ++r) {
+      __syncthreads();
+      if (kw == r) {
 #pragma unroll
         for (int i = 0; i < WM; ++i)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int row = m0 + 32 * i + 8 * (e >> 2) + rhalf + (e & 3);
-            if (row < M) out[(size_t)row * a.ldo + col] = (bf16)(silu(acc[i][0][e]) * acc[i][1][e]);
-          }
+          for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[((i * WN + j) * 16 + e) * 64 + lane] = acc[i][j][e];
+      }
+      __syncthreads();
+      if (kw == 0) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+          for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * WN + j) * 16 + e) * 64 + lane];
       }
     }
-    return;
+    if (kw != 0) return;
   }
-#pragma unroll
-  for (int j = 0; j < WN; ++j) {
-    if (nb0 + j >= nblocks) continue;
-    const int col = (nb0 + j) * 32 + cl;
-    const float bv = (a.bias != nullptr && sp == 0) ? a.bias[col] : 0.f;
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + 32 * i + 8 * (e >> 2) + rhalf + (e & 3);
-        if (row >= M) continue;
-        float v = acc[i][j][e] + bv;
-        const size_t o = (size_t)row * a.ldo + col;
-        if (a.epi == EPI_STORE) {
-          ((bf16*)a.out)[o] = (bf16)apply_act(v, a.act);
-        } else if (a.epi == EPI_STORE_F32) {
-          ((float*)a.out)[o] = apply_act(v, a.act);
-        } else {
-          if (a.epi == EPI_GATE_RESID) v *= a.gate[(size_t)row * a.ldg + col];
-          float* dst = (float*)a.out + o;
-          if (splits > 1) atomicAdd(dst, v);     // partial sums of a split K range meet in memory
-          else *dst += v;
-        }
-      }
+
+  // epilogue, specialised on (kind, whole tile inside M) so that the executed path is straight-line
+  const bool full = (m0 + BM <= M);
+  const bool atomic = splits > 1;
+  const int cl = lane & 31, rhalf = (lane >> 5) * 4;
+#define FARD_EPI(KIND)                                                                              \
+  do {                                                                                              \
+    if (full) epilogue<KIND, true, WM, WN>(a, acc, m0, M, nb0, nblocks, cl, rhalf, sp == 0, atomic); \
+    else epilogue<KIND, false, WM, WN>(a, acc, m0, M, nb0, nblocks, cl, rhalf, sp == 0, atomic);     \
+  } while (0)
+  switch (a.epi) {
+    case EPI_STORE: FARD_EPI(EPI_STORE); break;
+    case EPI_STORE_F32: FARD_EPI(EPI_STORE_F32); break;
+    case EPI_RESID: FARD_EPI(EPI_RESID); break;
+    case EPI_GATE_RESID: FARD_EPI(EPI_GATE_RESID); break;
+    case EPI_SWIGLU: FARD_EPI(EPI_SWIGLU); break;
+    default: break;
   }
+#undef FARD_EPI
 }
 
-template <int WM, int WN, int NW>
+template <int WM, int WN, int KW, int P, int KC>
 hipError_t launch_cfg(hipStream_t s, const GemmArgs& a, int splits) {
-  const int BN = 32 * WN * NW, BM = 32 * WM;
+  const int BN = 32 * WN * (4 / KW), BM = 32 * WM;
   const int n_tiles = (a.N + BN - 1) / BN;
   const int m_tiles = (a.M + BM - 1) / BM;
-  const int total_steps = a.K / BK;
-  if (splits > total_steps) splits = total_steps;
+  const int total_chunks = (a.K + KC - 1) / KC;
+  if (splits > total_chunks) splits = total_chunks;
   if (splits < 1) splits = 1;
-  const int sps = (total_steps + splits - 1) / splits;
-  splits = (total_steps + sps - 1) / sps;
+  const int cps = (total_chunks + splits - 1) / splits;
+  splits = (total_chunks + cps - 1) / cps;
   const int panels = n_tiles * splits;
   const int grid = ((panels + 7) / 8) * 8 * m_tiles;
-  gemm_bf16_kernel<WM, WN, NW><<<grid, 64 * NW, 0, s>>>(a, n_tiles, m_tiles, splits, sps);
+  gemm_bf16_kernel<WM, WN, KW, P, KC><<<grid, 256, 0, s>>>(a, n_tiles, m_tiles, splits, cps);
   return hipGetLastError();
 }
 
+// Tile choice.  The chip has 256 CUs; these GEMMs rarely have that many 128-column tiles, so narrow
+// tiles (waves splitting K inside the workgroup) and K splits across workgroups are used until the
+// grid covers it.  EPI_SWIGLU needs both column blocks of a pair in one wave (WN = 2).
+int g_force_wn = 0, g_force_kw = 0, g_force_splits = 0, g_force_kc = 256;   // tuning hook (gemm_force_cfg); 0 = heuristic
+
 template <int WM>
 hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
+  if (g_force_wn) {
+    const int sp = g_force_splits ? g_force_splits : 1;
+    if (g_force_kc == 512) {
+      if (g_force_wn == 2 && g_force_kw == 1) return launch_cfg<WM, 2, 1, 8, 512>(s, a, sp);
+      if (g_force_wn == 1 && g_force_kw == 1) return launch_cfg<WM, 1, 1, 16, 512>(s, a, sp);
+      if (g_force_wn == 2 && g_force_kw == 4) return launch_cfg<WM, 2, 4, 8, 512>(s, a, sp);
+      return launch_cfg<WM, 1, 4, 8, 512>(s, a, sp);
+    }
+    if (g_force_wn == 2 && g_force_kw == 1) return launch_cfg<WM, 2, 1, 8, 256>(s, a, sp);
+    if (g_force_wn == 1 && g_force_kw == 1) return launch_cfg<WM, 1, 1, 16, 256>(s, a, sp);
+    if (g_force_wn == 2 && g_force_kw == 4) return launch_cfg<WM, 2, 4, 8, 256>(s, a, sp);
+    return launch_cfg<WM, 1, 4, 8, 256>(s, a, sp);
+  }
   const int m_tiles = (a.M + 32 * WM - 1) / (32 * WM);
   const bool resid = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
-  // wide wave tiles only when that still leaves enough workgroups to cover the chip
-  const int tiles_wn2 = ((a.N + 255) / 256) * m_tiles;
-  const bool wn2 = (a.epi == EPI_SWIGLU) || tiles_wn2 >= 512;
-  const int BN = wn2 ? 256 : 128;
-  const int tiles = ((a.N + BN - 1) / BN) * m_tiles;
-  int splits = 1;
-  if (resid && tiles < 256) {
-    splits = (256 + tiles - 1) / tiles;
-    const int max_splits = a.K / (2 * BK) > 0 ? a.K / (2 * BK) : 1;   // keep >= 2 pipeline steps per split
-    if (splits > max_splits) splits = max_splits;
-    if (splits > 16) splits = 16;
-  }
-  return wn2 ? launch_cfg<WM, 2, 4>(s, a, splits) : launch_cfg<WM, 1, 4>(s, a, splits);
+  constexpr int KC = 256;
+  const int total_chunks = (a.K + KC - 1) / KC;
+  auto tiles = [&](int bn) { return ((a.N + bn - 1) / bn) * m_tiles; };
+  auto splits_for = [&](int t) { return (resid && t < 256) ? (256 + t - 1) / t : 1; };
+  if (tiles(256) >= 512) return launch_cfg<WM, 2, 1, 8, 256>(s, a, 1);                 // plenty of wide tiles
+  if (a.epi != EPI_SWIGLU && tiles(128) * (resid ? total_chunks : 1) >= 256)
+    return launch_cfg<WM, 1, 1, 16, 256>(s, a, splits_for(tiles(128)));
+  if (a.epi == EPI_SWIGLU || tiles(64) >= 192 || WM > 1) return launch_cfg<WM, 2, 4, 8, 256>(s, a, splits_for(tiles(64)));
+  return launch_cfg<WM, 1, 4, 8, 256>(s, a, splits_for(tiles(32)));
 }
 
 // ---------------------------------------------------------------------------------- fp32 path
@@ -273,9 +360,11 @@ __global__ void pack_weight_kernel(const TS* __restrict__ src, int ld, int K, in
 
 }  // namespace
 
+void gemm_force_cfg(int wn, int kw, int splits, int kc) { g_force_wn = wn; g_force_kw = kw; g_force_splits = splits; g_force_kc = kc; }
+
 hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a) {
   if (a.M <= 0) return hipSuccess;
-  if (a.K % BK != 0 || a.N % 32 != 0 || a.lda % 8 != 0) return hipErrorInvalidValue;
+  if (a.K % 64 != 0 || a.N % 32 != 0 || a.lda % 8 != 0) return hipErrorInvalidValue;
   if (a.epi == EPI_SWIGLU && a.N % 64 != 0) return hipErrorInvalidValue;
   if (a.M <= 32) return launch_wm<1>(s, a);
   if (a.M <= 64) return launch_wm<2>(s, a);

@@ -118,6 +118,23 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+// One workgroup per row.  The row is read once with 16-byte loads and stays in registers for the
+// statistics and the output pass (d <= 256 * 4 * NORM_VPT); everything a thread needs is requested
+// before the first reduction so that the loads overlap.
+constexpr int NORM_VPT = 8;
+template <typename T>
+__device__ __forceinline__ void store4(T* p, float a, float b, float c, float d);
+template <>
+__device__ __forceinline__ void store4<float>(float* p, float a, float b, float c, float d) {
+  *(f32x4*)p = f32x4{a, b, c, d};
+}
+template <>
+__device__ __forceinline__ void store4<bf16>(bf16* p, float a, float b, float c, float d) {
+  bf16x4 v;
+  v[0] = (bf16)a; v[1] = (bf16)b; v[2] = (bf16)c; v[3] = (bf16)d;
+  *(bf16x4*)p = v;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, int d, int M, const int* m_dev,
                                                    int norm_type, float eps, const float* __restrict__ g,
@@ -129,25 +146,44 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
   const int r = blockIdx.x;
   if (r >= Me) return;
   const float* row = h + (size_t)(in_map ? in_map[r] : r) * d;
-  float mean = 0.f;
-  if (norm_type == 0) {
-    float s = 0.f;
-    for (int c = threadIdx.x; c < d; c += blockDim.x) s += row[c];
-    mean = block_sum(s, red) / (float)d;
+  const int n4 = d >> 2;                                   // d % 4 == 0 (checked on the host)
+  f32x4 x[NORM_VPT];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NORM_VPT; ++i) {
+    const int c4 = threadIdx.x + i * 256;
+    x[i] = (c4 < n4) ? ((const f32x4*)row)[c4] : f32x4{0.f, 0.f, 0.f, 0.f};
   }
+#pragma unroll
+  for (int i = 0; i < NORM_VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
+  float mean = 0.f;
+  if (norm_type == 0) mean = block_sum(s, red) / (float)d;
   float q = 0.f;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    const float t = row[c] - mean;
-    q += t * t;
+#pragma unroll
+  for (int i = 0; i < NORM_VPT; ++i) {
+    const int c4 = threadIdx.x + i * 256;
+    if (c4 < n4) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float t = x[i][e] - mean; q += t * t; }
+    }
   }
   const float var = block_sum(q, red) / (float)d;
   const float rstd = 1.0f / sqrtf(var + eps);
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float y = (row[c] - mean) * rstd;
-    if (g) y *= g[c];
-    if (b) y += b[c];
-    if (scale) y = y * (1.0f + scale[(size_t)r * ldm + c]) + shift[(size_t)r * ldm + c];
-    out[(size_t)r * d + c] = from_f32<T>(y);
+#pragma unroll
+  for (int i = 0; i < NORM_VPT; ++i) {
+    const int c4 = threadIdx.x + i * 256;
+    if (c4 >= n4) continue;
+    f32x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (x[i][e] - mean) * rstd;
+    if (g) { const f32x4 v = ((const f32x4*)g)[c4]; y *= v; }
+    if (b) { const f32x4 v = ((const f32x4*)b)[c4]; y += v; }
+    if (scale) {
+      const f32x4 sc = *(const f32x4*)(scale + (size_t)r * ldm + c4 * 4);
+      const f32x4 sh = *(const f32x4*)(shift + (size_t)r * ldm + c4 * 4);
+      y = y * (1.0f + sc) + sh;
+    }
+    store4<T>(out + (size_t)r * d + c4 * 4, y[0], y[1], y[2], y[3]);
   }
 }
 
@@ -423,30 +459,87 @@ __global__ __launch_bounds__(256) void head_prep_kernel(const float* __restrict_
   if (xt_out && blockIdx.x == 0 && threadIdx.x < D) xt_out[(size_t)r * D + threadIdx.x] = xr[threadIdx.x] * xscale;
 }
 
-// One wave per row: final AdaLN, output projection to D <= 16 components, sampler update.
+// One wave per row: final AdaLN, output projection to D <= 16 components, sampler update.  The row,
+// its modulation and (for D == 16) the projection rows are fetched with 16-byte loads issued up
+// front and kept in registers (w <= 64 * 4 * HO_VPT).
+constexpr int HO_VPT = 8;
+template <typename T>
+__device__ __forceinline__ void load_w16(const T* p, float (&o)[16]);
+template <>
+__device__ __forceinline__ void load_w16<float>(const float* p, float (&o)[16]) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const f32x4 v = ((const f32x4*)p)[q];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[q * 4 + e] = v[e];
+  }
+}
+template <>
+__device__ __forceinline__ void load_w16<bf16>(const bf16* p, float (&o)[16]) {
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const bf16x8 v = ((const bf16x8*)p)[q];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[q * 8 + e] = (float)v[e];
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   const int ne = eff_rows(a.n, a.n_dev);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;
   if (r >= ne) return;
-  const int w = a.w, D = a.D;
+  const int w = a.w, D = a.D, n4 = w >> 2;
   const float* row = a.hh + (size_t)r * w;
+  const float* scp = a.scale + (size_t)r * a.ldm;
+  const float* shp = a.shift + (size_t)r * a.ldm;
+  f32x4 x[HO_VPT], sc[HO_VPT], sh[HO_VPT];
+#pragma unroll
+  for (int i = 0; i < HO_VPT; ++i) {
+    const int c4 = lane + i * WAVE;
+    const bool ok = c4 < n4;
+    const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+    x[i] = ok ? ((const f32x4*)row)[c4] : z4;
+    sc[i] = ok ? ((const f32x4*)scp)[c4] : z4;
+    sh[i] = ok ? ((const f32x4*)shp)[c4] : z4;
+  }
   float s = 0.f;
-  for (int c = lane; c < w; c += WAVE) s += row[c];
+#pragma unroll
+  for (int i = 0; i < HO_VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
   const float mean = wave_sum(s) / (float)w;
   float q = 0.f;
-  for (int c = lane; c < w; c += WAVE) { const float t = row[c] - mean; q += t * t; }
+#pragma unroll
+  for (int i = 0; i < HO_VPT; ++i) {
+    if (lane + i * WAVE < n4) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float t = x[i][e] - mean; q += t * t; }
+    }
+  }
   const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)w + 1e-6f);
   float acc[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
   const T* W = (const T*)a.w_out;
-  for (int c = lane; c < w; c += WAVE) {
-    const float y = (row[c] - mean) * rstd * (1.0f + a.scale[(size_t)r * a.ldm + c]) + a.shift[(size_t)r * a.ldm + c];
 #pragma unroll
-    for (int k = 0; k < 16; ++k)
-      if (k < D) acc[k] += y * to_f32(W[(size_t)c * D + k]);
+  for (int i = 0; i < HO_VPT; ++i) {
+    const int c4 = lane + i * WAVE;
+    if (c4 >= n4) continue;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float y = (x[i][e] - mean) * rstd * (1.0f + sc[i][e]) + sh[i][e];
+      const int c = c4 * 4 + e;
+      if (D == 16) {
+        float wr[16];
+        load_w16<T>(W + (size_t)c * 16, wr);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[k] += y * wr[k];
+      } else {
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+          if (k < D) acc[k] += y * to_f32(W[(size_t)c * D + k]);
+      }
+    }
   }
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = wave_sum(acc[k]);
@@ -569,6 +662,7 @@ hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M,
                        float eps, const float* g, const float* b, const float* shift, const float* scale, int ldm,
                        const int* in_map, void* out) {
   if (M <= 0) return hipSuccess;
+  if (d % 4 != 0 || d > 256 * 4 * NORM_VPT || ldm % 4 != 0) return hipErrorInvalidValue;
   if (is_bf16)
     norm_kernel<bf16><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out);
   else
@@ -644,7 +738,7 @@ hipError_t launch_head_prep(hipStream_t s, int is_bf16, const float* xsrc, const
 
 hipError_t launch_head_out(hipStream_t s, int is_bf16, const HeadStepArgs& a) {
   if (a.n <= 0) return hipSuccess;
-  if (a.D > 16) return hipErrorInvalidValue;
+  if (a.D > 16 || a.w % 4 != 0 || a.w > 64 * 4 * HO_VPT || a.ldm % 4 != 0) return hipErrorInvalidValue;
   if (is_bf16)
     head_out_kernel<bf16><<<(a.n + 3) / 4, 256, 0, s>>>(a);
   else

@@ -138,9 +138,17 @@ def _draw_weights(shapes, seed, prefix, dtype, w_std, affine, layers=None, std_o
 
 
 def tf_weights(c: TfCfg, seed: int, prefix: str, dtype: int, w_std=0.02, affine=False,
-               std_overrides=None) -> dict:
-    return _draw_weights(tf_weight_shapes(c), seed, prefix, dtype, w_std, affine,
-                         std_overrides=std_overrides)
+               std_overrides=None, deep_from=None, deep_gain=1.0) -> dict:
+    """deep_from / deep_gain: the output projections (wo, w2 / wd) of layers >= deep_from are drawn
+    with std w_std * deep_gain.  With deep_from = L_draft this makes the deep layers refinements of
+    the shallow ones, so that a draft made of the first L_draft layers predicts the target's feature
+    about as well as a trained draft would (acceptance well inside (0, 1))."""
+    ov = dict(std_overrides or {})
+    if deep_from is not None and deep_gain != 1.0:
+        for l in range(deep_from, c.n_layers):
+            for nm in ("wo", "w2", "wd"):
+                ov[f"L{l}.{nm}"] = w_std * deep_gain
+    return _draw_weights(tf_weight_shapes(c), seed, prefix, dtype, w_std, affine, std_overrides=ov)
 
 
 def head_weights(h: HeadCfg, seed: int, dtype: int, w_std=0.02, affine=False,

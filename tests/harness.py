@@ -30,7 +30,7 @@ class Case:
 
 
 def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_draft=False, cache_layers_shared=False,
-               std_overrides=None, peaky=False) -> Case:
+               std_overrides=None, peaky=False, deep_gain=1.0) -> Case:
     rc = kind if isinstance(kind, RoundCfg) else (config(kind) if isinstance(kind, int) else reduced(kind))
     rc = clone(rc)
     if same_draft:
@@ -44,7 +44,8 @@ def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_d
         std_overrides["wqkv"] = 1.4 / np.sqrt(min(rc.target.d_model, rc.draft.d_model))
     if w_std is None:
         w_std = 0.02                                       # the workload recipe: N(0, 0.02)
-    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides)
+    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
+                       deep_from=rc.draft.n_layers, deep_gain=deep_gain)
     same_shape = (rc.draft.d_model, rc.draft.n_heads, rc.draft.n_kv_heads, rc.draft.d_ff) == \
                  (rc.target.d_model, rc.target.n_heads, rc.target.n_kv_heads, rc.target.d_ff)
     if same_shape:
