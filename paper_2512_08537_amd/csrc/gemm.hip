@@ -267,6 +267,339 @@ hipError_t launch_cfg(hipStream_t s, const GemmArgs& a, int splits) {
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------ skinny variants (M <= a few hundred)
+// For the skinny GEMMs of a round (2-50 MB of weights each) a launch is one memory round trip long
+// if, and only if, every load it needs is in flight from the first cycle.  Two kernels do that:
+//  * gemm_bf16_res_kernel (64 < M): the whole activation panel of the workgroup (64 rows x its K range,
+//    in passes of up to ~1100 k) goes HBM/L2 -> LDS by the direct-to-LDS loads of gfx950
+//    (global_load_lds_dwordx4: no registers, 1 KiB per wave instruction) while the first P k-steps of every
+//    wave's weight stream are requested; one wait, one barrier, then an MFMA loop without barriers whose
+//    LDS fragment reads run two steps ahead of the MFMAs.
+//  * gemm_bf16_direct_kernel (M <= 64): the 4 waves split K; each wave needs only its own k-slices of the
+//    activations, so it loads them straight into registers as MFMA A fragments: no LDS before the MFMAs.
+// Both finish through lds_epilogue: partial tiles meet in LDS, then all 256 threads read them back
+// row-contiguous and write 8-16 bytes per lane (full cache lines) instead of 2-byte scattered stores.
+constexpr int RU = 1056;              // bytes between activation units in LDS (1 KiB unit + 32 B: conflict-free reads)
+
+// Tile of the workgroup: BM x BN, partial sums of KW wave groups.  lds holds KW * BM * (BN + 4) floats.
+template <int WM, int WN, int KW, int NWN>
+__device__ __forceinline__ void lds_epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN], float* lds, int m0, int M,
+                                             int n0, int kw, int nw, bool add_bias, bool atomic) {
+  constexpr int BM = 32 * WM, BNW = 32 * WN, BN = BNW * NWN, LDT = BN + 4;
+  const int lane = threadIdx.x & 63;
+  __syncthreads();                                         // the staging area is free
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        lds[(kw * BM + row) * LDT + nw * BNW + 32 * j + (lane & 31)] = acc[i][j][e];
+      }
+  __syncthreads();
+  const int N = a.N;
+  if (a.epi == EPI_SWIGLU) {
+    // packed column blocks alternate gate / up (32 columns each): output column = packed / 2
+    constexpr int GPR = BN / 8;                            // groups of 4 output columns per row
+    bf16* out = (bf16*)a.out;
+    for (int idx = threadIdx.x; idx < BM * GPR; idx += 256) {
+      const int row = idx / GPR, og = idx - row * GPR;
+      const int oc = og * 4;                               // output column inside the tile's output half
+      const int pc = (oc >> 5) * 64 + (oc & 31);           // packed column of the gate value
+      const int gr = m0 + row;
+      if (gr >= M || n0 + pc + 32 >= N) continue;         // gate and up blocks both inside N
+      f32x4 g = {0.f, 0.f, 0.f, 0.f}, u = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < KW; ++k) {
+        g += *(const f32x4*)(&lds[(k * BM + row) * LDT + pc]);
+        u += *(const f32x4*)(&lds[(k * BM + row) * LDT + pc + 32]);
+      }
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)(silu(g[e]) * u[e]);
+      *(bf16x4*)(out + (size_t)gr * a.ldo + (n0 >> 1) + oc) = o;
+    }
+    return;
+  }
+  constexpr int GPR = BN / 4;                              // groups of 4 columns per row
+  for (int idx = threadIdx.x; idx < BM * GPR; idx += 256) {
+    const int row = idx / GPR, cg = idx - row * GPR;
+    const int col = cg * 4;
+    const int gr = m0 + row, gc = n0 + col;
+    if (gr >= M || gc >= N) continue;                      // N % 32 == 0: a group is all in or all out
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < KW; ++k) v += *(const f32x4*)(&lds[(k * BM + row) * LDT + col]);
+    if (a.bias != nullptr && add_bias) v += *(const f32x4*)(a.bias + gc);
+    const size_t o = (size_t)gr * a.ldo + gc;
+    if (a.epi == EPI_STORE) {
+      bf16x4 t;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) t[e] = (bf16)apply_act(v[e], a.act);
+      *(bf16x4*)((bf16*)a.out + o) = t;
+    } else if (a.epi == EPI_STORE_F32) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], a.act);
+      *(f32x4*)((float*)a.out + o) = v;
+    } else {
+      if (a.epi == EPI_GATE_RESID) v *= *(const f32x4*)(a.gate + (size_t)gr * a.ldg + gc);
+      float* dst = (float*)a.out + o;
+      if (atomic) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) atomicAdd(dst + e, v[e]);   // partial sums of a split K range meet in memory
+      } else {
+        *(f32x4*)dst = *(const f32x4*)dst + v;
+      }
+    }
+  }
+}
+
+template <int WM, int WN, int KW, int P>
+__global__ __launch_bounds__(256) void gemm_bf16_res_kernel(GemmArgs a, int n_tiles, int m_tiles, int splits,
+                                                            int chunks_per_split, int chunks_per_pass) {
+  constexpr int NWN = 4 / KW;
+  constexpr int SPW = 16 / KW;                             // k-steps per wave per 256-k chunk
+  constexpr int BM = 32 * WM;
+  constexpr int UPC = BM / 2;                              // units per chunk
+  constexpr int AD = 3;                                    // LDS fragment reads run AD steps ahead (ring of AD+1 divides P)
+  static_assert(P % (AD + 1) == 0, "fragment ring must divide the weight ring");
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+
+  const int id = blockIdx.x;
+  const int xcd = id & 7, slot = id >> 3;
+  const int pq = slot / m_tiles, mt = slot - pq * m_tiles;
+  const int panel = pq * 8 + xcd;
+  if (panel >= n_tiles * splits) return;
+  const int nt = panel % n_tiles, sp = panel / n_tiles;
+  const int M = eff_rows(a.M, a.m_dev);
+  const int m0 = mt * BM;
+  if (m0 >= M) return;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave % KW, nw = wave / KW;
+  const int nblocks = a.N >> 5;
+  const int kb16 = a.K >> 4;
+  const int nb0 = (nt * NWN + nw) * WN;
+  const int total_chunks = a.K >> 8;                       // K % 256 == 0 (host check)
+  const int c_begin = sp * chunks_per_split;
+  int n_chunks = total_chunks - c_begin;
+  if (n_chunks > chunks_per_split) n_chunks = chunks_per_split;
+  const int n_steps = n_chunks * 16;                       // k-steps of this workgroup
+  const int s_begin = c_begin * 16;
+
+  const bf16* __restrict__ A = (const bf16*)a.A;
+  const bf16x8* __restrict__ Wp = (const bf16x8*)a.W;
+
+  f32x16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  bf16x8 zero8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
+
+  // weight ring: this wave's k-steps in order q = chunk * SPW + j live in slot q % P
+  bf16x8 breg[P][WN];
+  const bf16x8* bbase[WN];
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int nb = (nb0 + j < nblocks) ? nb0 + j : 0;      // columns past N: valid reads, never stored
+    bbase[j] = Wp + ((size_t)nb * kb16 + s_begin) * 64 + lane;
+  }
+  auto load_b = [&](int q, int p) {
+    int s = (q / SPW) * 16 + kw * SPW + (q % SPW);
+    s = s < n_steps ? s : n_steps - 1;                     // past the end: a re-read that only meets zeros
+#pragma unroll
+    for (int j = 0; j < WN; ++j) breg[p][j] = bbase[j][(size_t)s * 64];
+  };
+#pragma unroll
+  for (int p = 0; p < P; ++p) load_b(p, p);
+
+  const int urow = lane & 1, ukp = lane >> 1;              // lane -> (row parity, k-piece) inside a unit
+  const int q_total = n_chunks * SPW;
+  const int wave_steps_per_pass = chunks_per_pass * SPW;
+  // byte offset of this lane's fragment inside a unit pair, for row block i: rows 32 i + lane % 32
+  int frag_off[WM];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    const int r = 32 * i + (lane & 31);
+    frag_off[i] = (r >> 1) * RU + ((((lane >> 5) * 2) + (r & 1)) << 4);
+  }
+
+  for (int pass0 = 0; pass0 < n_chunks; pass0 += chunks_per_pass) {
+    int pc = n_chunks - pass0;
+    if (pc > chunks_per_pass) pc = chunks_per_pass;
+    if (pass0 > 0) __syncthreads();                        // previous panel fully consumed
+    for (int u = wave; u < pc * UPC; u += 4) {             // activation panel: units dealt to the waves
+      const int c = u / UPC, pr = u - c * UPC;
+      int row = m0 + 2 * pr + urow;
+      row = row < M ? row : M - 1;                         // rows past M: valid reads, never stored
+      const bf16* g = A + (size_t)row * a.lda + (size_t)(c_begin + pass0 + c) * 256 + ukp * 8;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                       (__attribute__((address_space(3))) void*)(lds_raw + (size_t)u * RU), 16, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0);                         // every outstanding load of this wave, LDS writes included
+    __syncthreads();
+
+    const int q_begin = pass0 * SPW;
+    int q_end = q_begin + wave_steps_per_pass;
+    if (q_end > q_total) q_end = q_total;
+    // fragment of step q (clamped to the panel; steps past its end are zeroed at use)
+    auto frag = [&](int q, bf16x8 (&f)[WM]) {
+      const int qc = q < q_end ? q : q_end - 1;
+      const int c = qc / SPW - pass0;
+      const int ks = kw * SPW + (qc % SPW);
+      const int base = c * UPC * RU + ks * 64;             // a k-step is 2 pieces x 2 rows x 16 B = 64 B further
+#pragma unroll
+      for (int i = 0; i < WM; ++i) f[i] = *(const bf16x8*)(lds_raw + base + frag_off[i]);
+    };
+    bf16x8 af[AD + 1][WM];
+#pragma unroll
+    for (int d = 0; d < AD; ++d) frag(q_begin + d, af[d]);
+    for (int q0 = q_begin; q0 < q_end; q0 += P) {
+#pragma unroll
+      for (int g = 0; g < P; ++g) {
+        const int q = q0 + g;
+        frag(q + AD, af[(g + AD) % (AD + 1)]);
+        const bool live = q < q_end;                       // select, not a branch: branches would drain the ring
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+          for (int i = 0; i < WM; ++i)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(live ? af[g % (AD + 1)][i] : zero8, breg[g][j],
+                                                                acc[i][j], 0, 0, 0);
+        load_b(q + P, g);
+        __builtin_amdgcn_sched_barrier(0);                 // the refill stays P steps ahead of its use
+      }
+    }
+  }
+  lds_epilogue<WM, WN, KW, NWN>(a, acc, (float*)lds_raw, m0, M, nt * NWN * WN * 32, kw, nw, sp == 0, splits > 1);
+}
+
+// M <= 64: 4 waves split K (interleaved k-steps), activations as A fragments straight from global memory.
+template <int WM, int WN, int P>
+__global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(GemmArgs a, int n_tiles, int splits, int steps_per_split) {
+  constexpr int KW = 4;
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+  const int id = blockIdx.x;
+  if (id >= n_tiles * splits) return;
+  const int nt = id % n_tiles, sp = id / n_tiles;
+  const int M = eff_rows(a.M, a.m_dev);
+  if (M <= 0) return;
+  const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
+  const int nblocks = a.N >> 5;
+  const int kb16 = a.K >> 4;
+  const int nb0 = nt * WN;
+  const int s_begin = sp * steps_per_split;
+  int n_steps = kb16 - s_begin;
+  if (n_steps > steps_per_split) n_steps = steps_per_split;
+  // this wave takes k-steps kw, kw + 4, kw + 8, ... of the workgroup's range
+  const int my_steps = (n_steps - kw + KW - 1) / KW;
+
+  const bf16* __restrict__ A = (const bf16*)a.A;
+  const bf16x8* __restrict__ Wp = (const bf16x8*)a.W;
+  f32x16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  bf16x8 zero8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
+
+  const bf16x8* bbase[WN];
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int nb = (nb0 + j < nblocks) ? nb0 + j : 0;
+    bbase[j] = Wp + ((size_t)nb * kb16 + s_begin) * 64 + lane;
+  }
+  const bf16* abase[WM];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    int row = 32 * i + (lane & 31);
+    row = row < M ? row : M - 1;
+    abase[i] = A + (size_t)row * a.lda + (size_t)s_begin * 16 + (lane >> 5) * 8;
+  }
+  bf16x8 breg[P][WN], areg[P][WM];
+  auto load_ab = [&](int t, int p) {                       // t-th step of this wave
+    int s = kw + t * KW;
+    s = s < n_steps ? s : n_steps - 1;                     // past the end: re-read, zeroed at use
+#pragma unroll
+    for (int j = 0; j < WN; ++j) breg[p][j] = bbase[j][(size_t)s * 64];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 16);
+  };
+#pragma unroll
+  for (int p = 0; p < P; ++p) load_ab(p, p);
+  __builtin_amdgcn_sched_barrier(0);                       // keep all P steps of loads ahead of the first MFMA
+  for (int t0 = 0; t0 < my_steps; t0 += P) {
+#pragma unroll
+    for (int g = 0; g < P; ++g) {
+      const bool live = (t0 + g) < my_steps;
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(live ? areg[g][i] : zero8, breg[g][j], acc[i][j], 0, 0, 0);
+      load_ab(t0 + g + P, g);
+      __builtin_amdgcn_sched_barrier(0);                   // the refill stays P steps ahead of its use
+    }
+  }
+  lds_epilogue<WM, WN, KW, 1>(a, acc, (float*)lds_raw, 0, M, nt * WN * 32, kw, 0, sp == 0, splits > 1);
+}
+
+constexpr int RES_LDS_BUDGET = 150 * 1024;
+
+template <int WM, int WN, int KW, int P>
+hipError_t launch_res(hipStream_t s, const GemmArgs& a, int splits) {
+  const int BN = 32 * WN * (4 / KW), BM = 32 * WM;
+  const int n_tiles = (a.N + BN - 1) / BN;
+  const int m_tiles = (a.M + BM - 1) / BM;
+  const int total_chunks = a.K / 256;
+  if (splits > total_chunks) splits = total_chunks;
+  if (splits < 1) splits = 1;
+  const int cps = (total_chunks + splits - 1) / splits;
+  splits = (total_chunks + cps - 1) / cps;
+  const int chunk_bytes = (BM / 2) * RU;
+  int cpp = RES_LDS_BUDGET / chunk_bytes;                  // chunks resident per pass
+  if (cpp > cps) cpp = cps;
+  size_t lds = (size_t)cpp * chunk_bytes;
+  const size_t epi = (size_t)KW * BM * (BN + 4) * 4;
+  if (lds < epi) lds = epi;
+  static bool attr_set = false;                            // per template instance
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_res_kernel<WM, WN, KW, P>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, RES_LDS_BUDGET + 8192);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int panels = n_tiles * splits;
+  const int grid = ((panels + 7) / 8) * 8 * m_tiles;
+  gemm_bf16_res_kernel<WM, WN, KW, P><<<grid, 256, lds, s>>>(a, n_tiles, m_tiles, splits, cps, cpp);
+  return hipGetLastError();
+}
+
+template <int WM, int WN, int P>
+hipError_t launch_direct(hipStream_t s, const GemmArgs& a, int splits) {
+  const int BN = 32 * WN;
+  const int n_tiles = (a.N + BN - 1) / BN;
+  const int total_steps = a.K / 16;
+  if (splits < 1) splits = 1;
+  int sps = (total_steps + splits - 1) / splits;
+  sps = ((sps + 3) / 4) * 4;                               // whole groups of 4 k-steps (one per wave)
+  splits = (total_steps + sps - 1) / sps;
+  const size_t lds = (size_t)4 * 32 * WM * (BN + 4) * 4;
+  gemm_bf16_direct_kernel<WM, WN, P><<<n_tiles * splits, 256, lds, s>>>(a, n_tiles, splits, sps);
+  return hipGetLastError();
+}
+
 // Tile choice.  The chip has 256 CUs; these GEMMs rarely have that many 128-column tiles, so narrow
 // tiles (waves splitting K inside the workgroup) and K splits across workgroups are used until the
 // grid covers it.  EPI_SWIGLU needs both column blocks of a pair in one wave (WN = 2).
@@ -276,6 +609,20 @@ template <int WM>
 hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
   if (g_force_wn) {
     const int sp = g_force_splits ? g_force_splits : 1;
+    if (g_force_kc == 0) {
+      if constexpr (WM == 2) {
+        if (g_force_wn == 1 && g_force_kw == 2) return launch_res<2, 1, 2, 16>(s, a, sp);
+        if (g_force_wn == 2 && g_force_kw == 2) return launch_res<2, 2, 2, 16>(s, a, sp);
+        if (g_force_wn == 2 && g_force_kw == 1) return launch_res<2, 2, 1, 16>(s, a, sp);
+        return launch_res<2, 1, 1, 16>(s, a, sp);
+      }
+    }
+    if (g_force_kc == 1) {
+      if constexpr (WM <= 2) {
+        if (g_force_wn == 2) return launch_direct<WM, 2, 16>(s, a, sp);
+        return launch_direct<WM, 1, 16>(s, a, sp);
+      }
+    }
     if (g_force_kc == 512) {
       if (g_force_wn == 2 && g_force_kw == 1) return launch_cfg<WM, 2, 1, 8, 512>(s, a, sp);
       if (g_force_wn == 1 && g_force_kw == 1) return launch_cfg<WM, 1, 1, 16, 512>(s, a, sp);
@@ -287,8 +634,20 @@ hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
     if (g_force_wn == 2 && g_force_kw == 4) return launch_cfg<WM, 2, 4, 8, 256>(s, a, sp);
     return launch_cfg<WM, 1, 4, 8, 256>(s, a, sp);
   }
-  const int m_tiles = (a.M + 32 * WM - 1) / (32 * WM);
   const bool resid = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
+  if constexpr (WM == 3) {
+    // a few hundred rows, full-K epilogue: the resident-activation kernel on 64-row tiles, sized so that the
+    // grid stays within one workgroup per CU
+    if (!resid && a.M <= 640 && a.K % 256 == 0) {
+      const int mt64 = (a.M + 63) / 64;
+      if (a.epi == EPI_SWIGLU || ((a.N + 63) / 64) * mt64 > 256) {
+        if (((a.N + 127) / 128) * mt64 <= 288) return launch_res<2, 2, 2, 16>(s, a, 1);
+      } else {
+        return launch_res<2, 1, 2, 16>(s, a, 1);
+      }
+    }
+  }
+  const int m_tiles = (a.M + 32 * WM - 1) / (32 * WM);
   constexpr int KC = 256;
   const int total_chunks = (a.K + KC - 1) / KC;
   auto tiles = [&](int bn) { return ((a.N + bn - 1) / bn) * m_tiles; };
@@ -296,7 +655,8 @@ hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
   if (tiles(256) >= 512) return launch_cfg<WM, 2, 1, 8, 256>(s, a, 1);                 // plenty of wide tiles
   if (a.epi != EPI_SWIGLU && tiles(128) * (resid ? total_chunks : 1) >= 256)
     return launch_cfg<WM, 1, 1, 16, 256>(s, a, splits_for(tiles(128)));
-  if (a.epi == EPI_SWIGLU || tiles(64) >= 192 || WM > 1) return launch_cfg<WM, 2, 4, 8, 256>(s, a, splits_for(tiles(64)));
+  if (WM > 1 && a.epi != EPI_SWIGLU) return launch_cfg<WM, 1, 1, 16, 256>(s, a, splits_for(tiles(128)));
+  if (a.epi == EPI_SWIGLU || tiles(64) >= 192) return launch_cfg<WM, 2, 4, 8, 256>(s, a, splits_for(tiles(64)));
   return launch_cfg<WM, 1, 4, 8, 256>(s, a, splits_for(tiles(32)));
 }
 
@@ -367,7 +727,7 @@ hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a) {
   if (a.K % 64 != 0 || a.N % 32 != 0 || a.lda % 8 != 0) return hipErrorInvalidValue;
   if (a.epi == EPI_SWIGLU && a.N % 64 != 0) return hipErrorInvalidValue;
   if (a.M <= 32) return launch_wm<1>(s, a);
-  if (a.M <= 64) return launch_wm<2>(s, a);
+  if (a.M <= 64 || (g_force_wn && g_force_kc == 0)) return launch_wm<2>(s, a);
   return launch_wm<3>(s, a);
 }
 
