@@ -61,11 +61,14 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
                             const int* cache_len, const int* row_start, int B, int nq_max,
                             void* out, int ldo, float* ent_heads);
 
-// Shallow-feature entropy + threshold + prefix rule + compaction (one launch).
-// feat: [B, K, L] storage type; prior_alive (optional, [B]) masks samples that already stopped.
+// Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
+// One launch (wave per row, last workgroup compacts; needs the zeroed `ticket`) up to ENT_SAMPLE_MODE_MIN_B
+// samples, two launches (wave per sample, parallel compaction through blk_cnt[ENT_MAX_BLOCKS]) above.
+constexpr int ENT_SAMPLE_MODE_MIN_B = 1024;
+constexpr int ENT_MAX_BLOCKS = 2048;
 hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L,
                                     float tau, float* H, uint8_t* keep, int* n_keep, int* surv_idx,
-                                    int* n_surv, unsigned* ticket);
+                                    int* n_surv, unsigned* ticket, int* blk_cnt);
 
 // H[r] = softmax entropy of the fp32 row feat[r*ld .. r*ld+L) (one wave per row).
 hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H);

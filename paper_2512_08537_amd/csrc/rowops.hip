@@ -2,6 +2,7 @@
 // pre-filter, head sampler pieces, accept test.  Memory-bound or tiny; one wave or one
 // workgroup per row, fp32 arithmetic, vector loads where rows are long.
 #include "kernels.h"
+#include <type_traits>
 
 namespace fard {
 
@@ -263,41 +264,29 @@ __device__ __forceinline__ Mla mla_merge(Mla p, Mla q) {
   Mla r;
   r.m = m;
   float l = 0.f, a = 0.f;
-  if (p.l > 0.f) { const float dl = p.m - m, e = expf(dl); l += e * p.l; a += e * (p.a + dl * p.l); }
-  if (q.l > 0.f) { const float dl = q.m - m, e = expf(dl); l += e * q.l; a += e * (q.a + dl * q.l); }
+  if (p.l > 0.f) { const float dl = p.m - m, e = __expf(dl); l += e * p.l; a += e * (p.a + dl * p.l); }
+  if (q.l > 0.f) { const float dl = q.m - m, e = __expf(dl); l += e * q.l; a += e * (q.a + dl * q.l); }
   r.l = l;
   r.a = a;
   return r;
 }
-__device__ __forceinline__ void mla_push(Mla& s, float x) {
-  if (x > s.m) {
-    if (s.l > 0.f) { const float dl = s.m - x, e = expf(dl); s.a = e * (s.a + dl * s.l); s.l = e * s.l; }
-    s.m = x;
+// Move the running maximum of s up to mx (no-op when mx <= s.m).
+__device__ __forceinline__ void mla_raise(Mla& s, float mx) {
+  if (mx > s.m) {
+    if (s.l > 0.f) { const float dl = s.m - mx, e = __expf(dl); s.a = e * (s.a + dl * s.l); s.l = e * s.l; }
+    s.m = mx;
   }
-  const float t = x - s.m, e = expf(t);
+}
+__device__ __forceinline__ void mla_add(Mla& s, float x) {   // requires x <= s.m
+  const float t = x - s.m, e = __expf(t);
   s.l += e;
   s.a += e * t;
 }
-template <typename T>
-__device__ __forceinline__ float row_entropy_wave(const T* __restrict__ row, int L, int lane) {
-  Mla s{-INFINITY, 0.f, 0.f};
-  if constexpr (sizeof(T) == 2) {
-    const int nvec = L >> 3;                      // 16-byte chunks of 8 bf16
-    const bf16x8* rv = (const bf16x8*)row;
-    const bool aligned = (((uintptr_t)row) & 15) == 0;
-    if (aligned) {
-      for (int c = lane; c < nvec; c += WAVE) {
-        const bf16x8 v = rv[c];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) mla_push(s, (float)v[i]);
-      }
-      for (int c = (nvec << 3) + lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
-    } else {
-      for (int c = lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
-    }
-  } else {
-    for (int c = lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
-  }
+__device__ __forceinline__ void mla_push(Mla& s, float x) {
+  mla_raise(s, x);
+  mla_add(s, x);
+}
+__device__ __forceinline__ float mla_finish(Mla s) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     Mla q;
@@ -306,15 +295,70 @@ __device__ __forceinline__ float row_entropy_wave(const T* __restrict__ row, int
     q.a = __shfl_xor(s.a, o, WAVE);
     s = mla_merge(s, q);
   }
-  return logf(s.l) - s.a / s.l;
+  return __logf(s.l) - s.a / s.l;
+}
+// A lane takes its 16-byte pieces of the row NCH at a time: all loads of a group are issued first, then one
+// maximum over the group, one rescale of the running sums, and independent exponentials.
+template <typename T>
+__device__ __forceinline__ float row_entropy_wave(const T* __restrict__ row, int L, int lane) {
+  Mla s{-INFINITY, 0.f, 0.f};
+  constexpr int VE = 16 / sizeof(T);              // elements per 16-byte piece
+  constexpr int NCH = 4;
+  using Vec = typename std::conditional<sizeof(T) == 2, bf16x8, f32x4>::type;
+  const bool aligned = (((uintptr_t)row) & 15) == 0;
+  const int nvec = aligned ? L / VE : 0;
+  const Vec* rv = (const Vec*)row;
+  for (int c0 = 0; c0 < nvec; c0 += NCH * WAVE) {
+    Vec v[NCH];
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = c0 + j * WAVE + lane;
+      v[j] = rv[c < nvec ? c : nvec - 1];
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (c0 + j * WAVE + lane < nvec) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) mx = fmaxf(mx, (float)v[j][i]);
+      }
+    }
+    mla_raise(s, mx);
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (c0 + j * WAVE + lane < nvec) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) mla_add(s, (float)v[j][i]);
+      }
+    }
+  }
+  for (int c = nvec * VE + lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
+  return mla_finish(s);
+}
+
+// Exclusive scan of one int per thread over a 256-thread workgroup; returns the workgroup total in *total.
+__device__ __forceinline__ int block_excl_scan(int v, int* s_scan, int* total) {
+  const int tid = threadIdx.x;
+  s_scan[tid] = v;
+  __syncthreads();
+#pragma unroll
+  for (int o = 1; o < 256; o <<= 1) {
+    const int u = (tid >= o) ? s_scan[tid - o] : 0;
+    __syncthreads();
+    s_scan[tid] += u;
+    __syncthreads();
+  }
+  const int incl = s_scan[tid];
+  *total = s_scan[255];
+  __syncthreads();
+  return incl - v;
 }
 
 // Threshold, prefix rule and compaction over [B, K] entropies, by one workgroup.
 __device__ void prefilter_tail(const float* H, int B, int K, float tau, uint8_t* keep, int* n_keep,
-                               int* surv_idx, int* n_surv, int* s_scan, int* s_carry) {
+                               int* surv_idx, int* n_surv, int* s_scan) {
   const int tid = threadIdx.x, nt = blockDim.x;
-  if (tid == 0) *s_carry = 0;
-  __syncthreads();
+  int carry = 0;
   for (int base = 0; base < B; base += nt) {
     const int b = base + tid;
     int cnt = 0;
@@ -328,33 +372,21 @@ __device__ void prefilter_tail(const float* H, int B, int K, float tau, uint8_t*
       }
       n_keep[b] = cnt;
     }
-    s_scan[tid] = cnt;
-    __syncthreads();
-    for (int o = 1; o < nt; o <<= 1) {
-      int v = (tid >= o) ? s_scan[tid - o] : 0;
-      __syncthreads();
-      s_scan[tid] += v;
-      __syncthreads();
-    }
-    const int carry = *s_carry;
-    if (b < B) {
-      const int start = carry + s_scan[tid] - cnt;
-      for (int i = 0; i < cnt; ++i) surv_idx[start + i] = b * K + i;   // kept drafts are a prefix
-    }
-    __syncthreads();
-    if (tid == nt - 1) *s_carry = carry + s_scan[nt - 1];
-    __syncthreads();
+    int total;
+    const int start = carry + block_excl_scan(cnt, s_scan, &total);
+    for (int i = 0; i < cnt; ++i) surv_idx[start + i] = b * K + i;   // kept drafts are a prefix
+    carry += total;
   }
-  if (tid == 0) *n_surv = *s_carry;
+  if (tid == 0) *n_surv = carry;
 }
 
+// One wave per draft row; the workgroup that finishes last applies the threshold and compacts.
 template <typename T>
 __global__ __launch_bounds__(256) void entropy_prefilter_kernel(const T* __restrict__ feat, int B, int K, int L,
                                                                 float tau, float* __restrict__ H, uint8_t* keep,
                                                                 int* n_keep, int* surv_idx, int* n_surv,
                                                                 unsigned* ticket) {
   __shared__ int s_scan[256];
-  __shared__ int s_carry;
   __shared__ int s_last;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const long rows = (long)B * K;
@@ -373,7 +405,62 @@ __global__ __launch_bounds__(256) void entropy_prefilter_kernel(const T* __restr
   if (!s_last) return;
   __threadfence();
   if (threadIdx.x == 0) *ticket = 0;             // ready for the next launch
-  prefilter_tail(H, B, K, tau, keep, n_keep, surv_idx, n_surv, s_scan, &s_carry);
+  prefilter_tail(H, B, K, tau, keep, n_keep, surv_idx, n_surv, s_scan);
+}
+
+// Large batches: one wave per sample walks its K rows and applies the prefix rule itself; workgroup
+// `blockIdx.x` owns the samples [blockIdx.x * spb, (blockIdx.x + 1) * spb) and records how many drafts they kept.
+template <typename T>
+__global__ __launch_bounds__(256) void entropy_samples_kernel(const T* __restrict__ feat, int B, int K, int L,
+                                                              float tau, int spb, float* __restrict__ H,
+                                                              uint8_t* __restrict__ keep, int* __restrict__ n_keep,
+                                                              int* __restrict__ blk_cnt) {
+  __shared__ int s_cnt[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b0 = blockIdx.x * spb, b1 = min(B, b0 + spb);
+  int total = 0;
+  for (int b = b0 + wave; b < b1; b += 4) {
+    bool alive = true;
+    int cnt = 0;
+    for (int i = 0; i < K; ++i) {
+      const size_t r = (size_t)b * K + i;
+      const float h = row_entropy_wave(feat + r * L, L, lane);
+      alive = alive && !(h < tau);
+      cnt += alive ? 1 : 0;
+      if (lane == 0) {
+        H[r] = h;
+        keep[r] = alive ? 1 : 0;
+      }
+    }
+    if (lane == 0) n_keep[b] = cnt;
+    total += cnt;
+  }
+  if (lane == 0) s_cnt[wave] = total;
+  __syncthreads();
+  if (threadIdx.x == 0) blk_cnt[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+}
+
+// Second pass of the large-batch path: workgroup i sums the counts of the workgroups before it, then lists
+// the kept drafts of its own samples.
+__global__ __launch_bounds__(256) void entropy_compact_kernel(const int* __restrict__ n_keep,
+                                                              const int* __restrict__ blk_cnt, int B, int K, int spb,
+                                                              int* __restrict__ surv_idx, int* __restrict__ n_surv) {
+  __shared__ int s_scan[256];
+  const int tid = threadIdx.x;
+  int part = 0;
+  for (int j = tid; j < (int)blockIdx.x; j += 256) part += blk_cnt[j];
+  int carry;
+  block_excl_scan(part, s_scan, &carry);
+  const int b0 = blockIdx.x * spb, b1 = min(B, b0 + spb);
+  for (int base = b0; base < b1; base += 256) {
+    const int b = base + tid;
+    const int cnt = (b < b1) ? n_keep[b] : 0;
+    int total;
+    const int start = carry + block_excl_scan(cnt, s_scan, &total);
+    for (int i = 0; i < cnt; ++i) surv_idx[start + i] = b * K + i;
+    carry += total;
+  }
+  if (blockIdx.x == gridDim.x - 1 && tid == 0) *n_surv = carry;
 }
 
 template <typename T>
@@ -694,11 +781,22 @@ hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v
 
 hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L, float tau,
                                     float* H, uint8_t* keep, int* n_keep, int* surv_idx, int* n_surv,
-                                    unsigned* ticket) {
+                                    unsigned* ticket, int* blk_cnt) {
+  if (B > ENT_SAMPLE_MODE_MIN_B) {
+    // two launches: per-sample waves, then a parallel compaction
+    int spb = (B + ENT_MAX_BLOCKS - 1) / ENT_MAX_BLOCKS;
+    spb = (spb + 3) & ~3;
+    const unsigned blocks = (unsigned)((B + spb - 1) / spb);
+    if (is_bf16)
+      entropy_samples_kernel<bf16><<<blocks, 256, 0, s>>>((const bf16*)feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
+    else
+      entropy_samples_kernel<float><<<blocks, 256, 0, s>>>((const float*)feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
+    entropy_compact_kernel<<<blocks, 256, 0, s>>>(n_keep, blk_cnt, B, K, spb, surv_idx, n_surv);
+    return hipGetLastError();
+  }
   const long rows = (long)B * K;
   long blocks = (rows + 3) / 4;
   if (blocks < 1) blocks = 1;
-  if (blocks > 8192) blocks = 8192;              // grid-stride beyond this: 32 workgroups per CU
   if (is_bf16)
     entropy_prefilter_kernel<bf16><<<(unsigned)blocks, 256, 0, s>>>((const bf16*)feat, B, K, L, tau, H, keep, n_keep,
                                                                     surv_idx, n_surv, ticket);

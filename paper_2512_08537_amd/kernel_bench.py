@@ -1,0 +1,54 @@
+#!/usr/bin/env python3
+"""Per-kernel roofline measurements that the round benchmark cannot isolate.
+
+  python -m paper_2512_08537_amd.kernel_bench entropy     # entropy pre-filter: config shapes + 2^20-row shape
+
+Prints one JSON line per measurement: algorithmic bytes / HIP-event time on the library's stream.
+"""
+from __future__ import annotations
+
+import json
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+
+
+def entropy():
+    import torch
+    from tests.harness import build_case, make_ctx
+    case = build_case("ln-gelu-bf16", seed=0)
+    ctx = make_ctx(case)
+    # (B, K, L): configs[0..4] feature shapes, then the scaled shape that shows the asymptotic bandwidth
+    shapes = [(1, 4, 256), (32, 8, 1024), (64, 8, 1280), (8, 8, 2048), (256, 8, 1280), (1 << 17, 8, 1280)]
+    for (B, K, L) in shapes:
+        g = torch.Generator(device="cuda").manual_seed(0)
+        feat = (torch.randn((B, K, L), generator=g, device="cuda", dtype=torch.float32) * 0.25).to(torch.bfloat16)
+        for _ in range(3):
+            out = ctx.entropy_prefilter(feat, 2.14)
+        ctx.sync()
+        iters = 20 if B * K * L < (1 << 28) else 5
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            out = ctx.entropy_prefilter(feat, 2.14)
+        e1.record()
+        ctx.sync()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        nbytes = B * K * L * 2 + B * K * 9
+        gbs = nbytes / us / 1e3
+        print(json.dumps({"kernel": "entropy_prefilter_kernel<bf16>", "rows": B * K, "len": L, "us_per_launch": round(us, 2),
+                          "algorithmic_bytes": nbytes, "achieved_GBs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4),
+                          "n_surv": int(out[4].cpu()[0])}), flush=True)
+    ctx.close()
+
+
+if __name__ == "__main__":
+    what = sys.argv[1] if len(sys.argv) > 1 else "entropy"
+    {"entropy": entropy}[what]()

@@ -88,7 +88,7 @@ def _check_prefilter(ctx, feat, tau, dtype_tol=1e-3):
 
 
 @pytest.mark.parametrize("B,K,L", [(1, 4, 256), (32, 8, 1024), (64, 8, 1280), (8, 8, 2048), (3, 5, 130), (2, 1, 1),
-                                   (7, 3, 9)])
+                                   (7, 3, 9), (1024, 2, 72), (1025, 3, 136), (9001, 2, 40), (2500, 4, 257)])
 def test_prefilter_shapes(ctx_bf16, B, K, L):
     ctx, _ = ctx_bf16
     feat = gen.normal(5, f"feat{B}{K}{L}", (B, K, L), 2.0, DT_BF16)
@@ -175,6 +175,8 @@ def test_prefilter_f32(ctx_f32):
     ctx, _ = ctx_f32
     feat = gen.normal(6, "featf32", (4, 4, 256), 3.0, DT_F32)
     _check_prefilter(ctx, feat, 3.0, dtype_tol=1e-4)
+    feat = gen.normal(6, "featf32big", (1300, 3, 100), 3.0, DT_F32)     # wave-per-sample path, ragged pieces
+    _check_prefilter(ctx, feat, 2.5, dtype_tol=1e-4)
 
 
 # ----------------------------------------------------------------------------- head
