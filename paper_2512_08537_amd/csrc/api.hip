@@ -129,7 +129,6 @@ struct fard_ctx {
   float *cz = nullptr, *hh = nullptr, *mod = nullptr, *xt = nullptr;
   void *sc = nullptr, *a1 = nullptr, *a2 = nullptr;
   int *alive = nullptr, *act_idx = nullptr, *n_act = nullptr, *emap = nullptr, *omap = nullptr;
-  unsigned* ticket = nullptr;
   int* ent_blk = nullptr;
   void* gemm_tmp = nullptr;
   size_t gemm_tmp_bytes = 0;
@@ -503,9 +502,7 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<int>(c, &c->n_act, 4))) return rc;
   if ((rc = dalloc<int>(c, &c->emap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->omap, g.max_batch))) return rc;
-  if ((rc = dalloc<unsigned>(c, &c->ticket, 4))) return rc;
   if ((rc = dalloc<int>(c, &c->ent_blk, ENT_MAX_BLOCKS))) return rc;
-  HIPCHK(c, hipMemsetAsync(c->ticket, 0, 16, c->stream));
   return FARD_OK;
 }
 
@@ -807,8 +804,7 @@ int entropy_prefilter(fard_ctx* c, const void* feat, int32_t B, int32_t K, int32
   }
   if (!feat || !H || !keep || !n_keep || !surv_idx) return fail(c, FARD_EINVAL, "null argument");
   Bracket br(c, CLS_ENT, 0, (double)B * K * L * c->esz);
-  HIPCHK(c, launch_entropy_prefilter(c->stream, c->bf16, feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, c->ticket,
-                                        c->ent_blk));
+  HIPCHK(c, launch_entropy_prefilter(c->stream, c->bf16, feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, c->ent_blk));
   return FARD_OK;
 }
 

@@ -62,13 +62,14 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
                             void* out, int ldo, float* ent_heads);
 
 // Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
-// One launch (wave per row, last workgroup compacts; needs the zeroed `ticket`) up to ENT_SAMPLE_MODE_MIN_B
-// samples, two launches (wave per sample, parallel compaction through blk_cnt[ENT_MAX_BLOCKS]) above.
+// Up to ENT_SAMPLE_MODE_MIN_B samples: a wave per row, then one workgroup thresholds and compacts.  Above: a
+// wave per sample applies the prefix rule itself and a second launch compacts in parallel through
+// blk_cnt[ENT_MAX_BLOCKS].
 constexpr int ENT_SAMPLE_MODE_MIN_B = 1024;
 constexpr int ENT_MAX_BLOCKS = 2048;
 hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L,
                                     float tau, float* H, uint8_t* keep, int* n_keep, int* surv_idx,
-                                    int* n_surv, unsigned* ticket, int* blk_cnt);
+                                    int* n_surv, int* blk_cnt);
 
 // H[r] = softmax entropy of the fp32 row feat[r*ld .. r*ld+L) (one wave per row).
 hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H);

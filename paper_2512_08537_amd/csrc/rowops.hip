@@ -256,87 +256,133 @@ __global__ __launch_bounds__(256) void kv_load_kernel(KvGeom kv, const T* __rest
 }
 
 // ================================================================== entropy pre-filter
-// Online softmax-entropy of one row held by one wave: every lane folds its elements into a
-// running (m, l, a) with a = sum e^{x-m} (x-m); lanes are merged with a butterfly; H = ln l - a/l.
+// Online softmax-entropy of one row held by one wave.  Every lane folds its elements into a running
+// (m, l, a) kept in base-2 units: m = log2(e) * (reference value), l = sum 2^t, a = sum 2^t * t with
+// t = log2(e) * x - m.  The reference cancels in H = ln l - ln(2) * a / l, so any m that avoids overflow is
+// valid; lanes are merged through a wave maximum and two wave sums.
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
 struct Mla { float m, l, a; };
-__device__ __forceinline__ Mla mla_merge(Mla p, Mla q) {
-  const float m = fmaxf(p.m, q.m);
-  Mla r;
-  r.m = m;
-  float l = 0.f, a = 0.f;
-  if (p.l > 0.f) { const float dl = p.m - m, e = __expf(dl); l += e * p.l; a += e * (p.a + dl * p.l); }
-  if (q.l > 0.f) { const float dl = q.m - m, e = __expf(dl); l += e * q.l; a += e * (q.a + dl * q.l); }
-  r.l = l;
-  r.a = a;
-  return r;
-}
-// Move the running maximum of s up to mx (no-op when mx <= s.m).
+// Move the reference of s up to the element value mx (no-op when it is not larger).
 __device__ __forceinline__ void mla_raise(Mla& s, float mx) {
-  if (mx > s.m) {
-    if (s.l > 0.f) { const float dl = s.m - mx, e = __expf(dl); s.a = e * (s.a + dl * s.l); s.l = e * s.l; }
-    s.m = mx;
+  const float m2 = mx * LOG2E;
+  if (m2 > s.m) {
+    if (s.l > 0.f) {
+      const float dl = s.m - m2, e = __builtin_amdgcn_exp2f(dl);
+      s.a = e * (s.a + dl * s.l);
+      s.l = e * s.l;
+    }
+    s.m = m2;
   }
 }
-__device__ __forceinline__ void mla_add(Mla& s, float x) {   // requires x <= s.m
-  const float t = x - s.m, e = __expf(t);
+__device__ __forceinline__ void mla_add(Mla& s, float x) {   // requires x * LOG2E <= s.m (up to rounding)
+  const float t = fmaf(x, LOG2E, -s.m), e = __builtin_amdgcn_exp2f(t);
   s.l += e;
-  s.a += e * t;
+  s.a = fmaf(e, t, s.a);
 }
 __device__ __forceinline__ void mla_push(Mla& s, float x) {
   mla_raise(s, x);
   mla_add(s, x);
 }
+// Merge the lanes: common reference by a wave maximum, one rescale per lane, two wave sums.
 __device__ __forceinline__ float mla_finish(Mla s) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    Mla q;
-    q.m = __shfl_xor(s.m, o, WAVE);
-    q.l = __shfl_xor(s.l, o, WAVE);
-    q.a = __shfl_xor(s.a, o, WAVE);
-    s = mla_merge(s, q);
+  const float M = wave_max(s.m);
+  float l = 0.f, a = 0.f;
+  if (s.l > 0.f) {
+    const float dl = s.m - M, e = __builtin_amdgcn_exp2f(dl);
+    l = e * s.l;
+    a = e * (s.a + dl * s.l);
   }
-  return __logf(s.l) - s.a / s.l;
+  l = wave_sum(l);
+  a = wave_sum(a);
+  return __logf(l) - LN2 * a / l;
 }
-// A lane takes its 16-byte pieces of the row NCH at a time: all loads of a group are issued first, then one
-// maximum over the group, one rescale of the running sums, and independent exponentials.
+
+constexpr int ENT_NCH = 4;                        // 16-byte pieces a lane holds in flight
+template <typename T> struct EntVec { using type = f32x4; };
+template <> struct EntVec<bf16> { using type = bf16x8; };
+
+// Issue the loads of up to ENT_NCH pieces per lane starting at piece c0 (addresses clamped, nvec >= 1).
+template <typename T>
+__device__ __forceinline__ void ent_fetch(const T* __restrict__ row, int c0, int nvec, int lane,
+                                          typename EntVec<T>::type (&v)[ENT_NCH]) {
+  using Vec = typename EntVec<T>::type;
+  const Vec* rv = (const Vec*)row;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH; ++j) {
+    const int c = c0 + j * WAVE + lane;
+    v[j] = rv[c < nvec ? c : nvec - 1];
+  }
+}
+// Fold the fetched pieces: one maximum over the group, one rescale, then independent exponentials.
+template <typename T>
+__device__ __forceinline__ void ent_fold(Mla& s, const typename EntVec<T>::type (&v)[ENT_NCH], int c0, int nvec,
+                                         int lane) {
+  constexpr int VE = 16 / sizeof(T);
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH; ++j) {
+    if (c0 + j * WAVE + lane < nvec) {
+#pragma unroll
+      for (int i = 0; i < VE; ++i) mx = fmaxf(mx, (float)v[j][i]);
+    }
+  }
+  mla_raise(s, mx);
+#pragma unroll
+  for (int j = 0; j < ENT_NCH; ++j) {
+    if (c0 + j * WAVE + lane < nvec) {
+#pragma unroll
+      for (int i = 0; i < VE; ++i) mla_add(s, (float)v[j][i]);
+    }
+  }
+}
+
+// Entropy of a row that is entirely in the fetched registers (two passes: wave maximum, then sums).
+template <typename T>
+__device__ __forceinline__ float ent_row_regs(const typename EntVec<T>::type (&v)[ENT_NCH], int nvec, int lane) {
+  constexpr int VE = 16 / sizeof(T);
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH; ++j) {
+    if (j * WAVE + lane < nvec) {
+#pragma unroll
+      for (int i = 0; i < VE; ++i) mx = fmaxf(mx, (float)v[j][i]);
+    }
+  }
+  const float m2 = wave_max(mx) * LOG2E;
+  float l = 0.f, a = 0.f;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH; ++j) {
+    if (j * WAVE + lane < nvec) {
+#pragma unroll
+      for (int i = 0; i < VE; ++i) {
+        const float t = fmaf((float)v[j][i], LOG2E, -m2), e = __builtin_amdgcn_exp2f(t);
+        l += e;
+        a = fmaf(e, t, a);
+      }
+    }
+  }
+  l = wave_sum(l);
+  a = wave_sum(a);
+  return __logf(l) - LN2 * a / l;
+}
+
 template <typename T>
 __device__ __forceinline__ float row_entropy_wave(const T* __restrict__ row, int L, int lane) {
   Mla s{-INFINITY, 0.f, 0.f};
   constexpr int VE = 16 / sizeof(T);              // elements per 16-byte piece
-  constexpr int NCH = 4;
-  using Vec = typename std::conditional<sizeof(T) == 2, bf16x8, f32x4>::type;
   const bool aligned = (((uintptr_t)row) & 15) == 0;
   const int nvec = aligned ? L / VE : 0;
-  const Vec* rv = (const Vec*)row;
-  for (int c0 = 0; c0 < nvec; c0 += NCH * WAVE) {
-    Vec v[NCH];
-#pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      const int c = c0 + j * WAVE + lane;
-      v[j] = rv[c < nvec ? c : nvec - 1];
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      if (c0 + j * WAVE + lane < nvec) {
-#pragma unroll
-        for (int i = 0; i < VE; ++i) mx = fmaxf(mx, (float)v[j][i]);
-      }
-    }
-    mla_raise(s, mx);
-#pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      if (c0 + j * WAVE + lane < nvec) {
-#pragma unroll
-        for (int i = 0; i < VE; ++i) mla_add(s, (float)v[j][i]);
-      }
-    }
+  for (int c0 = 0; c0 < nvec; c0 += ENT_NCH * WAVE) {
+    typename EntVec<T>::type v[ENT_NCH];
+    ent_fetch<T>(row, c0, nvec, lane, v);
+    ent_fold<T>(s, v, c0, nvec, lane);
   }
   for (int c = nvec * VE + lane; c < L; c += WAVE) mla_push(s, to_f32(row[c]));
   return mla_finish(s);
 }
 
-// Exclusive scan of one int per thread over a 256-thread workgroup; returns the workgroup total in *total.
+// Exclusive scan of one int per thread over a 256-thread workgroup; the workgroup total goes to *total.
 __device__ __forceinline__ int block_excl_scan(int v, int* s_scan, int* total) {
   const int tid = threadIdx.x;
   s_scan[tid] = v;
@@ -354,19 +400,40 @@ __device__ __forceinline__ int block_excl_scan(int v, int* s_scan, int* total) {
   return incl - v;
 }
 
-// Threshold, prefix rule and compaction over [B, K] entropies, by one workgroup.
-__device__ void prefilter_tail(const float* H, int B, int K, float tau, uint8_t* keep, int* n_keep,
-                               int* surv_idx, int* n_surv, int* s_scan) {
-  const int tid = threadIdx.x, nt = blockDim.x;
+// H[r] = entropy of row r (one wave per row, rows `ld` elements apart).
+template <typename T>
+__global__ __launch_bounds__(256) void entropy_rows_kernel(const T* __restrict__ feat, int ld, int rows, int L,
+                                                           float* __restrict__ H) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * 4 + wave;
+  if (r >= rows) return;
+  const T* row = feat + (size_t)r * ld;
+  constexpr int VE = 16 / sizeof(T);
+  float h;
+  if ((((uintptr_t)row) & 15) == 0 && L % VE == 0 && L >= VE && L / VE <= ENT_NCH * WAVE) {
+    typename EntVec<T>::type v[ENT_NCH];
+    ent_fetch<T>(row, 0, L / VE, lane, v);
+    h = ent_row_regs<T>(v, L / VE, lane);
+  } else {
+    h = row_entropy_wave(row, L, lane);
+  }
+  if (lane == 0) H[r] = h;
+}
+
+// Threshold, prefix rule and compaction over [B, K] entropies, by one workgroup (small batches).
+__global__ __launch_bounds__(256) void prefilter_tail_kernel(const float* __restrict__ H, int B, int K, float tau,
+                                                             uint8_t* __restrict__ keep, int* __restrict__ n_keep,
+                                                             int* __restrict__ surv_idx, int* __restrict__ n_surv) {
+  __shared__ int s_scan[256];
+  const int tid = threadIdx.x;
   int carry = 0;
-  for (int base = 0; base < B; base += nt) {
+  for (int base = 0; base < B; base += 256) {
     const int b = base + tid;
     int cnt = 0;
     if (b < B) {
       bool alive = true;
       for (int i = 0; i < K; ++i) {
-        const float hv = __hip_atomic_load(&H[(size_t)b * K + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        alive = alive && !(hv < tau);
+        alive = alive && !(H[(size_t)b * K + i] < tau);
         keep[(size_t)b * K + i] = alive ? 1 : 0;
         cnt += alive ? 1 : 0;
       }
@@ -380,37 +447,11 @@ __device__ void prefilter_tail(const float* H, int B, int K, float tau, uint8_t*
   if (tid == 0) *n_surv = carry;
 }
 
-// One wave per draft row; the workgroup that finishes last applies the threshold and compacts.
-template <typename T>
-__global__ __launch_bounds__(256) void entropy_prefilter_kernel(const T* __restrict__ feat, int B, int K, int L,
-                                                                float tau, float* __restrict__ H, uint8_t* keep,
-                                                                int* n_keep, int* surv_idx, int* n_surv,
-                                                                unsigned* ticket) {
-  __shared__ int s_scan[256];
-  __shared__ int s_last;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const long rows = (long)B * K;
-  for (long r = (long)blockIdx.x * 4 + wave; r < rows; r += (long)gridDim.x * 4) {
-    const float h = row_entropy_wave(feat + (size_t)r * L, L, lane);
-    if (lane == 0) H[r] = h;
-  }
-  // the workgroup that finishes last sees every H and runs the scan
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const unsigned t = atomicAdd(ticket, 1u);
-    s_last = (t == gridDim.x - 1) ? 1 : 0;
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  if (threadIdx.x == 0) *ticket = 0;             // ready for the next launch
-  prefilter_tail(H, B, K, tau, keep, n_keep, surv_idx, n_surv, s_scan);
-}
-
 // Large batches: one wave per sample walks its K rows and applies the prefix rule itself; workgroup
-// `blockIdx.x` owns the samples [blockIdx.x * spb, (blockIdx.x + 1) * spb) and records how many drafts they kept.
-template <typename T>
+// `blockIdx.x` owns the samples [blockIdx.x * spb, (blockIdx.x + 1) * spb) and records how many drafts they
+// kept.  PIPE: every row is at most ENT_NCH * 64 aligned 16-byte pieces, and the loads of the wave's next row
+// are issued before the current row is folded.
+template <typename T, bool PIPE>
 __global__ __launch_bounds__(256) void entropy_samples_kernel(const T* __restrict__ feat, int B, int K, int L,
                                                               float tau, int spb, float* __restrict__ H,
                                                               uint8_t* __restrict__ keep, int* __restrict__ n_keep,
@@ -419,21 +460,56 @@ __global__ __launch_bounds__(256) void entropy_samples_kernel(const T* __restric
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b0 = blockIdx.x * spb, b1 = min(B, b0 + spb);
   int total = 0;
-  for (int b = b0 + wave; b < b1; b += 4) {
+  if constexpr (PIPE) {
+    constexpr int VE = 16 / sizeof(T);
+    using Vec = typename EntVec<T>::type;
+    const int nvec = L / VE;
+    const int nb = (b1 - b0 - wave + 3) / 4;       // samples of this wave: b0 + wave + 4 j
+    const int nq = nb > 0 ? nb * K : 0;
+    Vec cur[ENT_NCH], nxt[ENT_NCH];
+    if (nq > 0) ent_fetch<T>(feat + (size_t)(b0 + wave) * K * L, 0, nvec, lane, cur);
     bool alive = true;
-    int cnt = 0;
-    for (int i = 0; i < K; ++i) {
+    int cnt = 0, i = 0, b = b0 + wave;
+    for (int q = 0; q < nq; ++q) {
       const size_t r = (size_t)b * K + i;
-      const float h = row_entropy_wave(feat + r * L, L, lane);
+      const int in = (i + 1 == K) ? 0 : i + 1, bn = (i + 1 == K) ? b + 4 : b;
+      if (q + 1 < nq) ent_fetch<T>(feat + ((size_t)bn * K + in) * L, 0, nvec, lane, nxt);
+      __builtin_amdgcn_sched_barrier(0);
+      const float h = ent_row_regs<T>(cur, nvec, lane);
       alive = alive && !(h < tau);
       cnt += alive ? 1 : 0;
       if (lane == 0) {
         H[r] = h;
         keep[r] = alive ? 1 : 0;
       }
+      if (in == 0) {
+        if (lane == 0) n_keep[b] = cnt;
+        total += cnt;
+        cnt = 0;
+        alive = true;
+      }
+#pragma unroll
+      for (int j = 0; j < ENT_NCH; ++j) cur[j] = nxt[j];
+      i = in;
+      b = bn;
     }
-    if (lane == 0) n_keep[b] = cnt;
-    total += cnt;
+  } else {
+    for (int b = b0 + wave; b < b1; b += 4) {
+      bool alive = true;
+      int cnt = 0;
+      for (int i = 0; i < K; ++i) {
+        const size_t r = (size_t)b * K + i;
+        const float h = row_entropy_wave(feat + r * L, L, lane);
+        alive = alive && !(h < tau);
+        cnt += alive ? 1 : 0;
+        if (lane == 0) {
+          H[r] = h;
+          keep[r] = alive ? 1 : 0;
+        }
+      }
+      if (lane == 0) n_keep[b] = cnt;
+      total += cnt;
+    }
   }
   if (lane == 0) s_cnt[wave] = total;
   __syncthreads();
@@ -461,16 +537,6 @@ __global__ __launch_bounds__(256) void entropy_compact_kernel(const int* __restr
     carry += total;
   }
   if (blockIdx.x == gridDim.x - 1 && tid == 0) *n_surv = carry;
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void entropy_rows_kernel(const T* __restrict__ feat, int ld, int rows, int L,
-                                                           float* __restrict__ H) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = blockIdx.x * 4 + wave;
-  if (r >= rows) return;
-  const float h = row_entropy_wave(feat + (size_t)r * ld, L, lane);
-  if (lane == 0) H[r] = h;
 }
 
 __global__ __launch_bounds__(256) void entropy_step_kernel(const float* __restrict__ ent_heads, int n_heads,
@@ -779,30 +845,33 @@ hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v
   return hipGetLastError();
 }
 
-hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L, float tau,
-                                    float* H, uint8_t* keep, int* n_keep, int* surv_idx, int* n_surv,
-                                    unsigned* ticket, int* blk_cnt) {
-  if (B > ENT_SAMPLE_MODE_MIN_B) {
-    // two launches: per-sample waves, then a parallel compaction
-    int spb = (B + ENT_MAX_BLOCKS - 1) / ENT_MAX_BLOCKS;
-    spb = (spb + 3) & ~3;
-    const unsigned blocks = (unsigned)((B + spb - 1) / spb);
-    if (is_bf16)
-      entropy_samples_kernel<bf16><<<blocks, 256, 0, s>>>((const bf16*)feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
-    else
-      entropy_samples_kernel<float><<<blocks, 256, 0, s>>>((const float*)feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
-    entropy_compact_kernel<<<blocks, 256, 0, s>>>(n_keep, blk_cnt, B, K, spb, surv_idx, n_surv);
-    return hipGetLastError();
+template <typename T>
+static void launch_entropy_prefilter_t(hipStream_t s, const T* feat, int B, int K, int L, float tau, float* H,
+                                       uint8_t* keep, int* n_keep, int* surv_idx, int* n_surv, int* blk_cnt) {
+  if (B <= ENT_SAMPLE_MODE_MIN_B) {
+    const int rows = B * K;
+    if (rows > 0) entropy_rows_kernel<T><<<(rows + 3) / 4, 256, 0, s>>>(feat, L, rows, L, H);
+    prefilter_tail_kernel<<<1, 256, 0, s>>>(H, B, K, tau, keep, n_keep, surv_idx, n_surv);
+    return;
   }
-  const long rows = (long)B * K;
-  long blocks = (rows + 3) / 4;
-  if (blocks < 1) blocks = 1;
-  if (is_bf16)
-    entropy_prefilter_kernel<bf16><<<(unsigned)blocks, 256, 0, s>>>((const bf16*)feat, B, K, L, tau, H, keep, n_keep,
-                                                                    surv_idx, n_surv, ticket);
+  int spb = (B + ENT_MAX_BLOCKS - 1) / ENT_MAX_BLOCKS;
+  spb = (spb + 3) & ~3;
+  const unsigned blocks = (unsigned)((B + spb - 1) / spb);
+  constexpr int VE = 16 / (int)sizeof(T);
+  const bool pipe = (((uintptr_t)feat) & 15) == 0 && L % VE == 0 && L >= VE && L / VE <= ENT_NCH * WAVE;
+  if (pipe)
+    entropy_samples_kernel<T, true><<<blocks, 256, 0, s>>>(feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
   else
-    entropy_prefilter_kernel<float><<<(unsigned)blocks, 256, 0, s>>>((const float*)feat, B, K, L, tau, H, keep, n_keep,
-                                                                     surv_idx, n_surv, ticket);
+    entropy_samples_kernel<T, false><<<blocks, 256, 0, s>>>(feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
+  entropy_compact_kernel<<<blocks, 256, 0, s>>>(n_keep, blk_cnt, B, K, spb, surv_idx, n_surv);
+}
+
+hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat, int B, int K, int L, float tau,
+                                    float* H, uint8_t* keep, int* n_keep, int* surv_idx, int* n_surv, int* blk_cnt) {
+  if (is_bf16)
+    launch_entropy_prefilter_t<bf16>(s, (const bf16*)feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, blk_cnt);
+  else
+    launch_entropy_prefilter_t<float>(s, (const float*)feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, blk_cnt);
   return hipGetLastError();
 }
 
