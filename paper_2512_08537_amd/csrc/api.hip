@@ -394,7 +394,11 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
   Bracket br(c, CLS_GEMM, fl, by);
-  return c->bf16 ? launch_gemm_bf16(c->stream, a) : launch_gemm_f32(c->stream, a);
+  if (!c->bf16) return launch_gemm_f32(c->stream, a);
+  // a few dozen rows against a weight matrix that 16-column tiles spread over enough workgroups: the
+  // narrow-tile kernel finishes in one memory round trip, without atomics
+  if (M <= 64 && K <= 2048 && N <= 8192 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
+  return launch_gemm_bf16(c->stream, a);
 }
 
 int load_head(fard_ctx* c, Loader& ld) {
@@ -968,7 +972,8 @@ int spec_gemm_fused(fard_ctx* c, const fard_fused_gemm* d) {
   if (d->M == 0) return FARD_OK;
   if (!d->A || !d->W || !d->out) return fail(c, FARD_EINVAL, "null argument");
   if (d->act < 0 || d->act > 2 || d->a_act < 0 || d->a_act > 2) return fail(c, FARD_EINVAL, "act");
-  if (d->a_mode < 0 || d->a_mode > 2 || d->epi < 0 || d->epi > 3 || d->norm_kind < 0 || d->norm_kind > 1 || d->splits < 0)
+  if (d->a_mode < 0 || d->a_mode > 2 || d->epi < 0 || d->epi > 3 || d->norm_kind < 0 || d->norm_kind > 1 || d->splits < -1 ||
+      (d->splits == -1 && d->a_mode != 0))
     return fail(c, FARD_EINVAL, "selector");
   if (d->epi == 3 && !d->gate) return fail(c, FARD_EINVAL, "epi 3 needs gate");
   if ((d->scale == nullptr) != (d->shift == nullptr)) return fail(c, FARD_EINVAL, "scale and shift go together");
@@ -981,7 +986,8 @@ int spec_gemm_fused(fard_ctx* c, const fard_fused_gemm* d) {
   x.ln_eps = d->norm_eps; x.norm_kind = d->norm_kind;
   x.force_splits = d->splits;
   x.g.W = nullptr;
-  if (!skinny_fits(x)) return fail(c, FARD_ESHAPE, "fused GEMM: M <= 64, K % 64 == 0, N % 32 == 0; a_mode 2: K % 256 == 0, K <= 2048; epi 0/1: K <= 2240 (M <= 32) or 1088");
+  const bool narrow = d->splits == -1;
+  if (narrow ? !narrow_supported(x.g) : !skinny_fits(x)) return fail(c, FARD_ESHAPE, "fused GEMM: M <= 64, K % 64 == 0, N % 32 == 0; a_mode 2: K % 256 == 0, K <= 2048; epi 0/1: K <= 2240 (M <= 32) or 1088");
   const size_t bytes = (size_t)d->K * d->N * 2;
   if (bytes > c->gemm_tmp_bytes) {
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -994,7 +1000,7 @@ int spec_gemm_fused(fard_ctx* c, const fard_fused_gemm* d) {
   HIPCHK(c, launch_pack_weight(c->stream, d->W, 1, d->N, d->K, d->N, c->gemm_tmp, 0, 1));
   x.g.W = c->gemm_tmp;
   { Bracket br(c, CLS_GEMM, 2.0 * d->M * (double)d->N * d->K, (double)d->K * d->N * 2);
-    HIPCHK(c, launch_gemm_skinny(c->stream, x)); }
+    HIPCHK(c, narrow ? launch_gemm_narrow(c->stream, x.g) : launch_gemm_skinny(c->stream, x)); }
   return FARD_OK;
 }
 

@@ -65,6 +65,11 @@ bool skinny_supported(const SkinnyArgs& x);
 bool skinny_fits(const SkinnyArgs& x);
 hipError_t launch_gemm_skinny(hipStream_t s, const SkinnyArgs& x);
 
+// Narrow-tile GEMM for M <= 64: one workgroup per 16 columns, no K split (no atomics; EPI_RESID and
+// EPI_GATE_RESID read-modify-write their tile), bf16 A.
+bool narrow_supported(const GemmArgs& a);
+hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a);
+
 // Tuning hook: force the wave tile (wn in {1,2}), the K-split inside the workgroup (kw in {1,4}) and the
 // K split across workgroups of every following bf16 launch; wn = 0 restores the built-in choice.
 void gemm_force_cfg(int wn, int kw, int splits, int kc = 256);

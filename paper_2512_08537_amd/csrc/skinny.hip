@@ -311,6 +311,126 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs x, int n_ti
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Narrow-tile variant: no K split, so any epilogue works without atomics and the result is
+// deterministic.  One workgroup per 16 weight columns (v_mfma_f32_16x16x32_bf16: lane l holds row /
+// column l % 16 and k = 8 (l / 16) .. + 8 of a 32-k step; accumulator register e is row 4 (l / 16) + e);
+// the 4 waves interleave the 32-k steps.  Weight and activation fragments go straight from memory into
+// MFMA operand registers -- the 16-column B fragment is two 256-byte halves of the packed 32-column
+// fragments -- so a wave's first SK_P steps are one memory round trip with no LDS staging and no
+// barrier before the MFMAs.  MT: 16-row tiles (rows <= 16 MT).
+constexpr int NR_LDT = 20;              // floats per row of a partial tile in LDS
+
+template <int MT, bool ONESHOT>
+__global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
+  __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * NR_LDT];
+  const int M = eff_rows(a.M, a.m_dev);
+  if (M <= 0) return;
+  const int c16 = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
+  const int kb16 = a.K >> 4, kb32 = a.K >> 5;
+  const int my_steps = (kb32 - kw + 3) >> 2;               // steps kw, kw + 4, ... (may be 0)
+  const int n0 = c16 * 16;
+
+  // packed B: fragment (nb, kb16 index) holds lane L = 32 * (k / 8 % 2) + n % 32
+  const int kg = lane >> 4;                                // k group of this lane inside a 32-k step
+  const bf16x8* __restrict__ bbase = (const bf16x8*)a.W + (size_t)(c16 >> 1) * kb16 * 64 + (kg >> 1) * 64 +
+                                     (kg & 1) * 32 + (c16 & 1) * 16 + (lane & 15);
+  const bf16* __restrict__ abase[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int r = 16 * i + (lane & 15);
+    r = r < M ? r : M - 1;
+    abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
+  }
+  bf16x8 breg[SK_P], areg[SK_P][MT];
+  auto load_ab = [&](int t, int p) {
+    int s = kw + 4 * t;
+    s = s < kb32 ? s : kb32 - 1;                           // past the end: a re-read, zeroed at use
+    breg[p] = bbase[(size_t)s * 128];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 32);
+  };
+#pragma unroll
+  for (int p = 0; p < SK_P; ++p) load_ab(p, p);
+
+  // epilogue operands that do not depend on the product: thread -> (row, 2 columns)
+  const int er = tid >> 3, ec = (tid & 7) * 2;
+  constexpr int EP = (16 * MT + 31) / 32;                  // passes of 32 rows
+  float2 gate[EP], old[EP], bias2 = {0.f, 0.f};
+  const bool rmw = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
+#pragma unroll
+  for (int i = 0; i < EP; ++i) {
+    int r = er + 32 * i;
+    r = r < M ? r : M - 1;
+    gate[i] = float2{1.f, 1.f};
+    old[i] = float2{0.f, 0.f};
+    if (a.epi == EPI_GATE_RESID) gate[i] = *(const float2*)(a.gate + (size_t)r * a.ldg + n0 + ec);
+    if (rmw) old[i] = *(const float2*)((const float*)a.out + (size_t)r * a.ldo + n0 + ec);
+  }
+  if (a.bias != nullptr) bias2 = *(const float2*)(a.bias + n0 + ec);
+  __builtin_amdgcn_sched_barrier(0);
+
+  f32x4 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 zero8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
+  if constexpr (ONESHOT) {
+#pragma unroll
+    for (int g = 0; g < SK_P; ++g) {
+      const bf16x8 b = (g < my_steps) ? breg[g] : zero8;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
+    }
+  } else {
+    for (int t0 = 0; t0 < my_steps; t0 += SK_P) {
+#pragma unroll
+      for (int g = 0; g < SK_P; ++g) {
+        const bf16x8 b = (t0 + g < my_steps) ? breg[g] : zero8;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
+        load_ab(t0 + g + SK_P, g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
+  // partial tiles of the 4 waves meet in LDS
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      red[(kw * 16 * MT + 16 * i + 4 * (lane >> 4) + e) * NR_LDT + (lane & 15)] = acc[i][e];
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < EP; ++i) {
+    const int row = er + 32 * i;
+    if (row >= M || row >= 16 * MT) continue;
+    float2 v = bias2;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float2 pv = *(const float2*)(red + (k * 16 * MT + row) * NR_LDT + ec);
+      v.x += pv.x;
+      v.y += pv.y;
+    }
+    const size_t o = (size_t)row * a.ldo + n0 + ec;
+    if (a.epi == EPI_STORE) {
+      bf16* dst = (bf16*)a.out + o;
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      bf16x2 t;
+      t[0] = (bf16)apply_act(v.x, a.act);
+      t[1] = (bf16)apply_act(v.y, a.act);
+      *(bf16x2*)dst = t;
+    } else if (a.epi == EPI_STORE_F32) {
+      *(float2*)((float*)a.out + o) = float2{apply_act(v.x, a.act), apply_act(v.y, a.act)};
+    } else {
+      *(float2*)((float*)a.out + o) = float2{old[i].x + gate[i].x * v.x, old[i].y + gate[i].y * v.y};
+    }
+  }
+}
+
 template <int WM, int AMODE>
 hipError_t launch_skinny_t(hipStream_t s, const SkinnyArgs& x, int n_tiles, int splits, int sps) {
   const int BM = 32 * WM;
@@ -372,6 +492,26 @@ hipError_t launch_gemm_skinny(hipStream_t s, const SkinnyArgs& x) {
   if (WM == 1) { FARD_SK(1) }
   FARD_SK(2)
 #undef FARD_SK
+}
+
+bool narrow_supported(const GemmArgs& a) {
+  return a.M >= 1 && a.M <= 64 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
+}
+
+hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
+  if (!narrow_supported(a)) return hipErrorInvalidValue;
+  const int grid = a.N / 16;
+  const bool oneshot = (a.K / 32 + 3) / 4 <= SK_P;
+#define FARD_NR(MTV)                                                          \
+  do {                                                                        \
+    if (oneshot) gemm_narrow_kernel<MTV, true><<<grid, 256, 0, s>>>(a);       \
+    else gemm_narrow_kernel<MTV, false><<<grid, 256, 0, s>>>(a);              \
+  } while (0)
+  if (a.M <= 16) FARD_NR(1);
+  else if (a.M <= 32) FARD_NR(2);
+  else FARD_NR(4);
+#undef FARD_NR
+  return hipGetLastError();
 }
 
 bool skinny_fits(const SkinnyArgs& x) {

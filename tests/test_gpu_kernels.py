@@ -56,6 +56,9 @@ _FUSED_CASES = [
     (32, 1024, 1024, 1, 3, 0), (7, 4096, 1024, 1, 2, 0), (64, 1088, 32, 1, 0, 0), (50, 512, 160, 1, 1, 0),
     (32, 1024, 1024, 2, 2, 0), (32, 1024, 4096, 2, 2, 2), (9, 256, 64, 2, 0, 0), (64, 1280, 640, 2, 2, 5),
     (33, 2048, 96, 2, 2, 0), (30, 2048, 96, 2, 1, 0), (3, 1536, 256, 2, 3, 0),
+    # splits -1: narrow tiles, K never split
+    (32, 1024, 1024, 0, 0, -1), (32, 1024, 1024, 0, 3, -1), (13, 64, 32, 0, 1, -1), (16, 1280, 96, 0, 2, -1),
+    (17, 4096, 1024, 0, 2, -1), (64, 1024, 160, 0, 3, -1), (49, 1536, 64, 0, 0, -1), (1, 192, 32, 0, 1, -1),
 ]
 
 
