@@ -213,7 +213,8 @@ int spec_gemm(fard_ctx* ctx, const void* A, const void* W, const float* bias, in
  *   epi 0     out storage type [M,N] = act(A W + bias);   1: the same, out fp32
  *   epi 2     out fp32 [M,N] += A W + bias;   3: out fp32 [M,N] += gate[m,n] * (A W + bias)
  *   splits    K slices combined with fp32 atomics (epi 2, 3 only; other epilogues use 1); 0 = library's choice;
- *             -1 (a_mode 0 only) = the 16-column-tile kernel that never splits K (no atomics, any epi)
+ *             -1 (a_mode 0 only) = the 16-column-tile kernel that never splits K (no atomics, any epi,
+ *             M <= 1024)
  *             epi 0, 1 keep a workgroup's whole K in LDS: K <= 2240 (M <= 32) or K <= 1088 (M <= 64)
  * Errors: FARD_ESHAPE for sizes outside the limits above, FARD_EINVAL for bad selectors or NULLs. */
 typedef struct fard_fused_gemm {

@@ -398,6 +398,8 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
   // a few dozen rows against a weight matrix that 16-column tiles spread over enough workgroups: the
   // narrow-tile kernel finishes in one memory round trip, without atomics
   if (M <= 64 && K <= 2048 && N <= 8192 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
+  // a few hundred rows against a small square-ish matrix: still ahead of the split-K kernels (measured)
+  if (M <= 640 && K <= 1536 && N <= 1536 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
   return launch_gemm_bf16(c->stream, a);
 }
 
@@ -987,7 +989,7 @@ int spec_gemm_fused(fard_ctx* c, const fard_fused_gemm* d) {
   x.force_splits = d->splits;
   x.g.W = nullptr;
   const bool narrow = d->splits == -1;
-  if (narrow ? !narrow_supported(x.g) : !skinny_fits(x)) return fail(c, FARD_ESHAPE, "fused GEMM: M <= 64, K % 64 == 0, N % 32 == 0; a_mode 2: K % 256 == 0, K <= 2048; epi 0/1: K <= 2240 (M <= 32) or 1088");
+  if (narrow ? !(narrow_supported(x.g) && d->M <= 1024) : !skinny_fits(x)) return fail(c, FARD_ESHAPE, "fused GEMM: M <= 64, K % 64 == 0, N % 32 == 0; a_mode 2: K % 256 == 0, K <= 2048; epi 0/1: K <= 2240 (M <= 32) or 1088");
   const size_t bytes = (size_t)d->K * d->N * 2;
   if (bytes > c->gemm_tmp_bytes) {
     HIPCHK(c, hipStreamSynchronize(c->stream));

@@ -65,8 +65,9 @@ bool skinny_supported(const SkinnyArgs& x);
 bool skinny_fits(const SkinnyArgs& x);
 hipError_t launch_gemm_skinny(hipStream_t s, const SkinnyArgs& x);
 
-// Narrow-tile GEMM for M <= 64: one workgroup per 16 columns, no K split (no atomics; EPI_RESID and
-// EPI_GATE_RESID read-modify-write their tile), bf16 A.
+// Narrow-tile GEMM: one workgroup per 16 columns and 16-64 rows, no K split (no atomics; EPI_RESID and
+// EPI_GATE_RESID read-modify-write their tile), bf16 A.  Meant for M <= 64, or a few hundred rows when K
+// and N are about 1024.
 bool narrow_supported(const GemmArgs& a);
 hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a);
 

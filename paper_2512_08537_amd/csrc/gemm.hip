@@ -287,6 +287,13 @@ __device__ __forceinline__ void lds_epilogue(const GemmArgs& a, f32x16 (&acc)[WM
                                              int n0, int kw, int nw, bool add_bias, bool atomic) {
   constexpr int BM = 32 * WM, BNW = 32 * WN, BN = BNW * NWN, LDT = BN + 4;
   const int lane = threadIdx.x & 63;
+  // a thread keeps its 4 columns over all rows of the tile: its bias is requested before the barriers
+  constexpr int GPR = BN / 4;                              // groups of 4 columns per row
+  static_assert(256 % GPR == 0, "a thread keeps its column group over all rows");
+  const int col = (threadIdx.x % GPR) * 4;
+  const int gc = n0 + col;
+  f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
+  if (a.epi != EPI_SWIGLU && a.bias != nullptr && add_bias && gc < a.N) bias4 = *(const f32x4*)(a.bias + gc);
   __syncthreads();                                         // the staging area is free
 #pragma unroll
   for (int i = 0; i < WM; ++i)
@@ -301,10 +308,10 @@ __device__ __forceinline__ void lds_epilogue(const GemmArgs& a, f32x16 (&acc)[WM
   const int N = a.N;
   if (a.epi == EPI_SWIGLU) {
     // packed column blocks alternate gate / up (32 columns each): output column = packed / 2
-    constexpr int GPR = BN / 8;                            // groups of 4 output columns per row
+    constexpr int OGPR = BN / 8;                           // groups of 4 output columns per row
     bf16* out = (bf16*)a.out;
-    for (int idx = threadIdx.x; idx < BM * GPR; idx += 256) {
-      const int row = idx / GPR, og = idx - row * GPR;
+    for (int idx = threadIdx.x; idx < BM * OGPR; idx += 256) {
+      const int row = idx / OGPR, og = idx - row * OGPR;
       const int oc = og * 4;                               // output column inside the tile's output half
       const int pc = (oc >> 5) * 64 + (oc & 31);           // packed column of the gate value
       const int gr = m0 + row;
@@ -322,16 +329,13 @@ __device__ __forceinline__ void lds_epilogue(const GemmArgs& a, f32x16 (&acc)[WM
     }
     return;
   }
-  constexpr int GPR = BN / 4;                              // groups of 4 columns per row
-  for (int idx = threadIdx.x; idx < BM * GPR; idx += 256) {
-    const int row = idx / GPR, cg = idx - row * GPR;
-    const int col = cg * 4;
-    const int gr = m0 + row, gc = n0 + col;
-    if (gr >= M || gc >= N) continue;                      // N % 32 == 0: a group is all in or all out
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (gc >= N) return;                                     // N % 32 == 0: a group is all in or all out
+  for (int row = threadIdx.x / GPR; row < BM; row += 256 / GPR) {
+    const int gr = m0 + row;
+    if (gr >= M) break;
+    f32x4 v = bias4;
 #pragma unroll
     for (int k = 0; k < KW; ++k) v += *(const f32x4*)(&lds[(k * BM + row) * LDT + col]);
-    if (a.bias != nullptr && add_bias) v += *(const f32x4*)(a.bias + gc);
     const size_t o = (size_t)gr * a.ldo + gc;
     if (a.epi == EPI_STORE) {
       bf16x4 t;

@@ -318,14 +318,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs x, int n_ti
 // the 4 waves interleave the 32-k steps.  Weight and activation fragments go straight from memory into
 // MFMA operand registers -- the 16-column B fragment is two 256-byte halves of the packed 32-column
 // fragments -- so a wave's first SK_P steps are one memory round trip with no LDS staging and no
-// barrier before the MFMAs.  MT: 16-row tiles (rows <= 16 MT).
+// barrier before the MFMAs.  MT: 16-row tiles per workgroup; blockIdx.y walks the row slabs.
 constexpr int NR_LDT = 20;              // floats per row of a partial tile in LDS
 
 template <int MT, bool ONESHOT>
 __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * NR_LDT];
   const int M = eff_rows(a.M, a.m_dev);
-  if (M <= 0) return;
+  const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
+  if (m0 >= M) return;
   const int c16 = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
   const int kb16 = a.K >> 4, kb32 = a.K >> 5;
@@ -339,7 +340,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   const bf16* __restrict__ abase[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
-    int r = 16 * i + (lane & 15);
+    int r = m0 + 16 * i + (lane & 15);
     r = r < M ? r : M - 1;
     abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
   }
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   const bool rmw = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
 #pragma unroll
   for (int i = 0; i < EP; ++i) {
-    int r = er + 32 * i;
+    int r = m0 + er + 32 * i;
     r = r < M ? r : M - 1;
     gate[i] = float2{1.f, 1.f};
     old[i] = float2{0.f, 0.f};
@@ -407,7 +408,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < EP; ++i) {
     const int row = er + 32 * i;
-    if (row >= M || row >= 16 * MT) continue;
+    if (m0 + row >= M || row >= 16 * MT) continue;
     float2 v = bias2;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -415,7 +416,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
       v.x += pv.x;
       v.y += pv.y;
     }
-    const size_t o = (size_t)row * a.ldo + n0 + ec;
+    const size_t o = (size_t)(m0 + row) * a.ldo + n0 + ec;
     if (a.epi == EPI_STORE) {
       bf16* dst = (bf16*)a.out + o;
       typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -495,20 +496,22 @@ hipError_t launch_gemm_skinny(hipStream_t s, const SkinnyArgs& x) {
 }
 
 bool narrow_supported(const GemmArgs& a) {
-  return a.M >= 1 && a.M <= 64 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
+  return a.M >= 1 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
 }
 
 hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   if (!narrow_supported(a)) return hipErrorInvalidValue;
-  const int grid = a.N / 16;
   const bool oneshot = (a.K / 32 + 3) / 4 <= SK_P;
-#define FARD_NR(MTV)                                                          \
-  do {                                                                        \
-    if (oneshot) gemm_narrow_kernel<MTV, true><<<grid, 256, 0, s>>>(a);       \
-    else gemm_narrow_kernel<MTV, false><<<grid, 256, 0, s>>>(a);              \
+  // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
+  // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
+#define FARD_NR(MTV)                                                                  \
+  do {                                                                                \
+    const dim3 grid(a.N / 16, (a.M + 16 * MTV - 1) / (16 * MTV));                     \
+    if (oneshot) gemm_narrow_kernel<MTV, true><<<grid, 256, 0, s>>>(a);               \
+    else gemm_narrow_kernel<MTV, false><<<grid, 256, 0, s>>>(a);                      \
   } while (0)
   if (a.M <= 16) FARD_NR(1);
-  else if (a.M <= 32) FARD_NR(2);
+  else if (a.M <= 32 || a.M > 64) FARD_NR(2);
   else FARD_NR(4);
 #undef FARD_NR
   return hipGetLastError();

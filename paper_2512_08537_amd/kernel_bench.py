@@ -58,7 +58,7 @@ def fused():
     ctx = make_ctx(case)
     dev = ctx.dev
     cases = []
-    for M in (32, 64):
+    for M in (32, 64, 288):
         for (K, N, a_mode, epi, splits) in [(1024, 1024, 0, 2, 0), (1024, 1024, 0, 2, 4), (1024, 1024, 0, 2, 16),
                                             (1024, 1024, 0, 3, 0), (1024, 1024, 1, 3, 0), (1024, 1024, 2, 2, 0),
                                             (1024, 1024, 2, 2, 4), (1024, 1024, 0, 0, 0),
@@ -67,7 +67,8 @@ def fused():
                                             (1024, 4096, 2, 2, 4), (1024, 3072, 2, 2, 0), (1024, 3072, 2, 2, 4),
                                             (1024, 1024, 0, 0, -1), (1024, 1024, 0, 2, -1), (1024, 1024, 0, 3, -1),
                                             (4096, 1024, 0, 2, -1), (1024, 4096, 0, 0, -1), (1024, 3072, 0, 0, -1)]:
-            cases.append((M, K, N, a_mode, epi, splits))
+            if M <= 64 or splits == -1:
+                cases.append((M, K, N, a_mode, epi, splits))
     for (M, K, N, a_mode, epi, splits) in cases:
         W = (torch.randn((K, N), device=dev) * 0.02).to(torch.bfloat16)
         A = torch.randn((M, K), device=dev)

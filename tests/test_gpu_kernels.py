@@ -59,6 +59,7 @@ _FUSED_CASES = [
     # splits -1: narrow tiles, K never split
     (32, 1024, 1024, 0, 0, -1), (32, 1024, 1024, 0, 3, -1), (13, 64, 32, 0, 1, -1), (16, 1280, 96, 0, 2, -1),
     (17, 4096, 1024, 0, 2, -1), (64, 1024, 160, 0, 3, -1), (49, 1536, 64, 0, 0, -1), (1, 192, 32, 0, 1, -1),
+    (288, 1024, 1024, 0, 2, -1), (130, 512, 96, 0, 3, -1), (97, 256, 64, 0, 0, -1),
 ]
 
 
