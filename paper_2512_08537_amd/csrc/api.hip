@@ -498,9 +498,9 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<uint8_t>(c, &c->acc_tmp, (size_t)g.max_batch * g.K))) return rc;
   if ((rc = dalloc<float>(c, &c->cz, (size_t)M * w))) return rc;
   if ((rc = dalloc<float>(c, &c->hh, (size_t)M * w))) return rc;
-  if ((rc = dalloc<float>(c, &c->mod, (size_t)M * c->head.mod_n))) return rc;
+  if ((rc = dalloc<float>(c, &c->mod, (size_t)g.head.n_steps * M * c->head.mod_n))) return rc;
   if ((rc = dalloc<float>(c, &c->xt, (size_t)M * D))) return rc;
-  if ((rc = dalloc_bytes(c, &c->sc, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->sc, (size_t)g.head.n_steps * M * w * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->a1, (size_t)M * w * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->a2, (size_t)M * w * c->esz))) return rc;
   if ((rc = dalloc<int>(c, &c->alive, g.max_batch))) return rc;
@@ -579,19 +579,17 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
   hipStream_t s = c->stream;
   const int w = hc.width, D = hc.d_latent, Nb = hc.n_blocks, S = hc.n_steps;
   HIPCHK(c, gemm(c, z, hc.d_cond, hw.c_w, hw.c_b, c->cz, w, n, w, hc.d_cond, n_dev, EPI_STORE_F32, ACT_NONE));
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_head_prep(s, c->bf16, eps, emap, hc.temperature, D, hw.in_w, hw.in_b, c->cz, hw.temb, S, c->hh, c->sc,
+                               c->xt, w, n, n_dev)); }
+  // the modulations of all S steps in one GEMM over S n rows (rows past the device-side count are unused)
+  HIPCHK(c, gemm(c, c->sc, w, hw.mod_all, hw.mod_b_all, c->mod, hw.mod_n, S * n, hw.mod_n, w, nullptr, EPI_STORE_F32, ACT_NONE));
   for (int k = 0; k < S; ++k) {
     const float t = 1.0f - (float)k / (float)S;
     const float t_next = 1.0f - (float)(k + 1) / (float)S;
-    { Bracket br(c, CLS_OTHER);
-      if (k == 0)
-        HIPCHK(c, launch_head_prep(s, c->bf16, eps, emap, hc.temperature, D, hw.in_w, hw.in_b, c->cz, hw.temb, c->hh, c->sc,
-                                   c->xt, w, n, n_dev));
-      else
-        HIPCHK(c, launch_head_prep(s, c->bf16, c->xt, nullptr, 1.0f, D, hw.in_w, hw.in_b, c->cz, hw.temb + (size_t)k * w,
-                                   c->hh, c->sc, nullptr, w, n, n_dev)); }
-    HIPCHK(c, gemm(c, c->sc, w, hw.mod_all, hw.mod_b_all, c->mod, hw.mod_n, n, hw.mod_n, w, n_dev, EPI_STORE_F32, ACT_NONE));
+    const float* modk = c->mod + (size_t)k * n * hw.mod_n;
     for (int j = 0; j < Nb; ++j) {
-      const float* mj = c->mod + (size_t)3 * w * j;
+      const float* mj = modk + (size_t)3 * w * j;
       { Bracket br(c, CLS_OTHER);
         HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1)); }
       HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
@@ -599,7 +597,7 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
     }
     HeadStepArgs a;
     a.hh = c->hh; a.w = w;
-    a.shift = c->mod + (size_t)3 * w * Nb; a.scale = a.shift + w; a.ldm = hw.mod_n;
+    a.shift = modk + (size_t)3 * w * Nb; a.scale = a.shift + w; a.ldm = hw.mod_n;
     a.w_out = hw.out_w; a.b_out = hw.out_b; a.D = D;
     a.xt = c->xt;
     a.eps_next = eps + (size_t)(k + 1) * eps_step_stride;
@@ -609,6 +607,7 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
     a.renoise = hc.renoise;
     a.sigma = hc.sigma_last * hc.temperature;
     a.mu = mu; a.x = x;
+    a.w_in = hw.in_w; a.b_in = hw.in_b; a.hh_next = c->hh;
     a.n = n; a.n_dev = n_dev;
     { Bracket br(c, CLS_OTHER);
       HIPCHK(c, launch_head_out(s, c->bf16, a)); }

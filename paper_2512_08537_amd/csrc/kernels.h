@@ -83,11 +83,11 @@ hipError_t launch_entropy_step(hipStream_t s, const float* ent_heads, int n_head
                                int* alive, int* n_keep, int* act_idx, int* n_act, int* emap, int* omap);
 
 // Head pieces.
-// hh[r, :] = x_t[r, :] W_in + b_in ; sc[r, :] = T(silu(cz[r, :] + temb[:])).  x_t comes from
-// xsrc[xmap ? xmap[r] : r] * xscale.
+// hh[r, :] = x_t[r, :] W_in + b_in ; sc[k n + r, :] = T(silu(cz[r, :] + temb[k, :])) for the S sampler
+// times k.  x_t comes from xsrc[xmap ? xmap[r] : r] * xscale.
 hipError_t launch_head_prep(hipStream_t s, int is_bf16, const float* xsrc, const int* xmap, float xscale,
                             int D, const void* w_in, const float* b_in, const float* cz,
-                            const float* temb, float* hh, void* sc, float* xt_out, int w, int n,
+                            const float* temb, int S, float* hh, void* sc, float* xt_out, int w, int n,
                             const int* n_dev);
 
 struct HeadStepArgs {
@@ -103,6 +103,8 @@ struct HeadStepArgs {
   int renoise;
   float sigma;                        // sigma_last * temperature (last step)
   float* mu; float* x;                // outputs of the last step, row-mapped
+  const void* w_in; const float* b_in;   // input projection [D, w] of the next step (not last)
+  float* hh_next;                     // [n, w] residual stream of the next step (may alias hh)
   int n; const int* n_dev;
 };
 hipError_t launch_head_out(hipStream_t s, int is_bf16, const HeadStepArgs& a);

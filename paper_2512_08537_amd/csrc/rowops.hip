@@ -591,11 +591,13 @@ __global__ __launch_bounds__(256) void entropy_step_kernel(const float* __restri
 }
 
 // ================================================================== head pieces
+// First sampler step: hh = x_t W_in + b_in, x_t kept, and the conditioning silu(cz + temb_k) of all S steps
+// (step k in rows [k n, (k + 1) n) of sc), so that one GEMM produces the modulations of every step.
 template <typename T>
 __global__ __launch_bounds__(256) void head_prep_kernel(const float* __restrict__ xsrc, const int* __restrict__ xmap,
                                                         float xscale, int D, const T* __restrict__ w_in,
                                                         const float* __restrict__ b_in, const float* __restrict__ cz,
-                                                        const float* __restrict__ temb, float* __restrict__ hh,
+                                                        const float* __restrict__ temb, int S, float* __restrict__ hh,
                                                         T* __restrict__ sc, float* __restrict__ xt_out, int w, int n,
                                                         const int* n_dev) {
   const int ne = eff_rows(n, n_dev);
@@ -604,18 +606,19 @@ __global__ __launch_bounds__(256) void head_prep_kernel(const float* __restrict_
   const int c = blockIdx.x * 256 + threadIdx.x;
   const float* xr = xsrc + (size_t)(xmap ? xmap[r] : r) * D;
   if (c < w) {
+    const float czv = cz[(size_t)r * w + c];
     float v = b_in[c];
     for (int k = 0; k < D; ++k) v += (xr[k] * xscale) * to_f32(w_in[(size_t)k * w + c]);
     hh[(size_t)r * w + c] = v;
-    sc[(size_t)r * w + c] = from_f32<T>(silu(cz[(size_t)r * w + c] + temb[c]));
+    for (int k = 0; k < S; ++k) sc[((size_t)k * n + r) * w + c] = from_f32<T>(silu(czv + temb[(size_t)k * w + c]));
   }
   if (xt_out && blockIdx.x == 0 && threadIdx.x < D) xt_out[(size_t)r * D + threadIdx.x] = xr[threadIdx.x] * xscale;
 }
 
-// One wave per row: final AdaLN, output projection to D <= 16 components, sampler update.  The row,
-// its modulation and (for D == 16) the projection rows are fetched with 16-byte loads issued up
-// front and kept in registers (w <= 64 * 4 * HO_VPT).
-constexpr int HO_VPT = 8;
+// One workgroup per row: final AdaLN, output projection to D <= 16 components, sampler update, and (when
+// another step follows) the input projection of the new x_t into hh.  The row, its modulation and the
+// projection rows are fetched with 16-byte loads issued up front (w <= 256 * 4 * HO_VPT).
+constexpr int HO_VPT = 2;
 template <typename T>
 __device__ __forceinline__ void load_w16(const T* p, float (&o)[16]);
 template <>
@@ -639,9 +642,12 @@ __device__ __forceinline__ void load_w16<bf16>(const bf16* p, float (&o)[16]) {
 
 template <typename T>
 __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
+  __shared__ float red[8];
+  __shared__ float part[4][16];
+  __shared__ float xs[16];
   const int ne = eff_rows(a.n, a.n_dev);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int r = blockIdx.x * 4 + wave;
+  const int r = blockIdx.x;
   if (r >= ne) return;
   const int w = a.w, D = a.D, n4 = w >> 2;
   const float* row = a.hh + (size_t)r * w;
@@ -650,7 +656,7 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   f32x4 x[HO_VPT], sc[HO_VPT], sh[HO_VPT];
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) {
-    const int c4 = lane + i * WAVE;
+    const int c4 = threadIdx.x + i * 256;
     const bool ok = c4 < n4;
     const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
     x[i] = ok ? ((const f32x4*)row)[c4] : z4;
@@ -660,23 +666,23 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
-  const float mean = wave_sum(s) / (float)w;
+  const float mean = block_sum(s, red) / (float)w;
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) {
-    if (lane + i * WAVE < n4) {
+    if (threadIdx.x + i * 256 < n4) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) { const float t = x[i][e] - mean; q += t * t; }
     }
   }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)w + 1e-6f);
+  const float rstd = 1.0f / sqrtf(block_sum(q, red) / (float)w + 1e-6f);
   float acc[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
   const T* W = (const T*)a.w_out;
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) {
-    const int c4 = lane + i * WAVE;
+    const int c4 = threadIdx.x + i * 256;
     if (c4 >= n4) continue;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -696,14 +702,17 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   }
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = wave_sum(acc[k]);
-  if (lane < D) {
-    float v = 0.f;
+  if (lane == 0) {
 #pragma unroll
-    for (int k = 0; k < 16; ++k) v = (lane == k) ? acc[k] : v;
-    v += a.b_out[lane];
-    const size_t xi = (size_t)r * D + lane;
-    const size_t ei = (size_t)(a.emap ? a.emap[r] : r) * D + lane;
-    const size_t oi = (size_t)(a.omap ? a.omap[r] : r) * D + lane;
+    for (int k = 0; k < 16; ++k) part[wave][k] = acc[k];
+  }
+  __syncthreads();
+  if (threadIdx.x < D) {
+    const int k = threadIdx.x;
+    const float v = part[0][k] + part[1][k] + part[2][k] + part[3][k] + a.b_out[k];
+    const size_t xi = (size_t)r * D + k;
+    const size_t ei = (size_t)(a.emap ? a.emap[r] : r) * D + k;
+    const size_t oi = (size_t)(a.omap ? a.omap[r] : r) * D + k;
     const float xt = a.xt[xi];
     const float x0 = xt - a.t * v;
     if (a.last) {
@@ -711,8 +720,19 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
       a.x[oi] = x0 + a.sigma * a.eps_next[ei];
     } else {
       const float e = a.renoise ? a.eps_next[ei] : xt + (1.0f - a.t) * v;
-      a.xt[xi] = (1.0f - a.t_next) * x0 + a.t_next * e;
+      const float xn = (1.0f - a.t_next) * x0 + a.t_next * e;
+      a.xt[xi] = xn;
+      xs[k] = xn;
     }
+  }
+  if (a.last) return;
+  __syncthreads();
+  // input projection of the next step
+  const T* w_in = (const T*)a.w_in;
+  for (int c = threadIdx.x; c < w; c += 256) {
+    float v = a.b_in[c];
+    for (int k = 0; k < D; ++k) v += xs[k] * to_f32(w_in[(size_t)k * w + c]);
+    a.hh_next[(size_t)r * w + c] = v;
   }
 }
 
@@ -890,26 +910,26 @@ hipError_t launch_entropy_step(hipStream_t s, const float* ent_heads, int n_head
 }
 
 hipError_t launch_head_prep(hipStream_t s, int is_bf16, const float* xsrc, const int* xmap, float xscale, int D,
-                            const void* w_in, const float* b_in, const float* cz, const float* temb, float* hh,
+                            const void* w_in, const float* b_in, const float* cz, const float* temb, int S, float* hh,
                             void* sc, float* xt_out, int w, int n, const int* n_dev) {
   if (n <= 0) return hipSuccess;
   dim3 grid((w + 255) / 256, n);
   if (is_bf16)
-    head_prep_kernel<bf16><<<grid, 256, 0, s>>>(xsrc, xmap, xscale, D, (const bf16*)w_in, b_in, cz, temb, hh,
+    head_prep_kernel<bf16><<<grid, 256, 0, s>>>(xsrc, xmap, xscale, D, (const bf16*)w_in, b_in, cz, temb, S, hh,
                                                 (bf16*)sc, xt_out, w, n, n_dev);
   else
-    head_prep_kernel<float><<<grid, 256, 0, s>>>(xsrc, xmap, xscale, D, (const float*)w_in, b_in, cz, temb, hh,
+    head_prep_kernel<float><<<grid, 256, 0, s>>>(xsrc, xmap, xscale, D, (const float*)w_in, b_in, cz, temb, S, hh,
                                                  (float*)sc, xt_out, w, n, n_dev);
   return hipGetLastError();
 }
 
 hipError_t launch_head_out(hipStream_t s, int is_bf16, const HeadStepArgs& a) {
   if (a.n <= 0) return hipSuccess;
-  if (a.D > 16 || a.w % 4 != 0 || a.w > 64 * 4 * HO_VPT || a.ldm % 4 != 0) return hipErrorInvalidValue;
+  if (a.D > 16 || a.w % 4 != 0 || a.w > 256 * 4 * HO_VPT || a.ldm % 4 != 0) return hipErrorInvalidValue;
   if (is_bf16)
-    head_out_kernel<bf16><<<(a.n + 3) / 4, 256, 0, s>>>(a);
+    head_out_kernel<bf16><<<a.n, 256, 0, s>>>(a);
   else
-    head_out_kernel<float><<<(a.n + 3) / 4, 256, 0, s>>>(a);
+    head_out_kernel<float><<<a.n, 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
