@@ -201,39 +201,16 @@ int spec_round(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id,
 int spec_gemm(fard_ctx* ctx, const void* A, const void* W, const float* bias, int32_t M, int32_t K,
               int32_t N, int32_t act, void* out);
 
-/* One fused small-batch GEMM (M <= 64 rows, bf16 contexts), for tests and kernel timing: the draft
- * steps and head decodes of a round (Alg. 1 Steps 1-2) run their GEMMs through this kernel with the
- * row-wise work between two GEMMs folded into the operand load.  All pointers are device memory.
- *   W         storage type [K,N] row-major (re-laid on every call); K % 64 == 0, N % 32 == 0
- *   a_mode 0  A storage type [M,K]
- *   a_mode 1  A fp32 [M,K] raw sums; the operand is a_act(A + a_bias[k])   (a_bias fp32 [K] or NULL)
- *   a_mode 2  A fp32 [M,K] stream; the operand is norm(A) * gain[k] + beta[k], then * (1 + scale[m,k])
- *             + shift[m,k]; norm_kind 0 layer norm, 1 RMS norm; gain, beta fp32 [K] or NULL; scale and
- *             shift fp32 [M,K], both or neither; K % 256 == 0 and K <= 2048
- *   epi 0     out storage type [M,N] = act(A W + bias);   1: the same, out fp32
- *   epi 2     out fp32 [M,N] += A W + bias;   3: out fp32 [M,N] += gate[m,n] * (A W + bias)
- *   splits    K slices combined with fp32 atomics (epi 2, 3 only; other epilogues use 1); 0 = library's choice;
- *             -1 (a_mode 0 only) = the 16-column-tile kernel that never splits K (no atomics, any epi,
- *             M <= 1024)
- *             epi 0, 1 keep a workgroup's whole K in LDS: K <= 2240 (M <= 32) or K <= 1088 (M <= 64)
+/* One small-batch GEMM through the narrow-tile kernel (bf16 contexts), for tests and kernel timing: the
+ * draft steps and head decodes of a round (Alg. 1 Steps 1-2) run their GEMMs through it.  All pointers
+ * are device memory.  A storage type [M,K]; W storage type [K,N] row-major (re-laid on every call);
+ * bias fp32 [N] or NULL; M <= 1024, K % 64 == 0, N % 32 == 0.
+ *   epi 0  out storage type [M,N] = act(A W + bias);   1: the same, out fp32
+ *   epi 2  out fp32 [M,N] += A W + bias;   3: out fp32 [M,N] += gate[m,n] * (A W + bias), gate fp32 [M,N]
+ * K is never split: no atomics, results are deterministic.
  * Errors: FARD_ESHAPE for sizes outside the limits above, FARD_EINVAL for bad selectors or NULLs. */
-typedef struct fard_fused_gemm {
-  const void* A;
-  const void* W;
-  const float* bias;   /* fp32 [N] or NULL */
-  void* out;
-  const float* gate;   /* fp32 [M,N], epi 3 */
-  const float* a_bias;
-  const float* gain;
-  const float* beta;
-  const float* scale;
-  const float* shift;
-  int32_t M, K, N;
-  int32_t a_mode, a_act, norm_kind;
-  float norm_eps;
-  int32_t epi, act, splits;
-} fard_fused_gemm;
-int spec_gemm_fused(fard_ctx* ctx, const fard_fused_gemm* desc);
+int spec_gemm_narrow(fard_ctx* ctx, const void* A, const void* W, const float* bias, const float* gate,
+                     int32_t M, int32_t K, int32_t N, int32_t epi, int32_t act, void* out);
 
 /* Per-kernel timing with HIP events on the context's stream.  enable = 1 brackets every launch of
  * the named kernel class between two events; spec_profile_read synchronises and returns the

@@ -49,12 +49,6 @@ class Tensor(C.Structure):
                 ("on_device", C.c_int32)]
 
 
-class FusedGemm(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("A", "W", "bias", "out", "gate", "a_bias", "gain", "beta", "scale", "shift")] + \
-               [(n, C.c_int32) for n in ("M", "K", "N", "a_mode", "a_act", "norm_kind")] + [("norm_eps", C.c_float)] + \
-               [(n, C.c_int32) for n in ("epi", "act", "splits")]
-
-
 _vp, _i32, _f32 = C.c_void_p, C.c_int32, C.c_float
 _SIGS = {
     "spec_round_init": [C.POINTER(RoundCfg), C.POINTER(Tensor), _i32, _vp, C.POINTER(_vp)],
@@ -71,7 +65,7 @@ _SIGS = {
     "spec_accept": [_vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _vp, _vp, _vp],
     "spec_round": [_vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "spec_gemm": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
-    "spec_gemm_fused": [_vp, C.POINTER(FusedGemm)],
+    "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp],
     "spec_profile_enable": [_vp, _i32],
     "spec_profile_read": [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                           C.POINTER(C.c_double)],
@@ -314,15 +308,11 @@ class Context:
         self._chk(lib.spec_gemm(self.h, _ptr(A), _ptr(W), _ptr(bias), M, K, N, act, _ptr(out)))
         return out
 
-    def spec_gemm_fused(self, A, W, out, M=None, bias=None, gate=None, a_mode=0, a_bias=None, a_act=0, gain=None,
-                        beta=None, scale=None, shift=None, norm_kind=0, norm_eps=1e-5, epi=0, act=0, splits=0):
+    def spec_gemm_narrow(self, A, W, out, bias=None, gate=None, epi=0, act=0):
         """`out` is written (epi 0, 1) or accumulated into (epi 2, 3) in place and returned."""
-        K, N = W.shape
-        d = FusedGemm(A=_ptr(A), W=_ptr(W), bias=_ptr(bias), out=_ptr(out), gate=_ptr(gate), a_bias=_ptr(a_bias),
-                      gain=_ptr(gain), beta=_ptr(beta), scale=_ptr(scale), shift=_ptr(shift),
-                      M=A.shape[0] if M is None else M, K=K, N=N, a_mode=a_mode, a_act=a_act, norm_kind=norm_kind,
-                      norm_eps=norm_eps, epi=epi, act=act, splits=splits)
-        self._chk(lib.spec_gemm_fused(self.h, C.byref(d)))
+        M, K = A.shape
+        N = W.shape[1]
+        self._chk(lib.spec_gemm_narrow(self.h, _ptr(A), _ptr(W), _ptr(bias), _ptr(gate), M, K, N, epi, act, _ptr(out)))
         return out
 
     def spec_profile_enable(self, on: bool):

@@ -965,31 +965,20 @@ int spec_gemm(fard_ctx* c, const void* A, const void* W, const float* bias, int3
   return FARD_OK;
 }
 
-int spec_gemm_fused(fard_ctx* c, const fard_fused_gemm* d) {
+int spec_gemm_narrow(fard_ctx* c, const void* A, const void* W, const float* bias, const float* gate, int32_t M,
+                     int32_t K, int32_t N, int32_t epi, int32_t act, void* out) {
   if (check_ctx(c)) return FARD_EINVAL;
-  if (!d) return fail(c, FARD_EINVAL, "null descriptor");
-  if (!c->bf16) return fail(c, FARD_EINVAL, "spec_gemm_fused needs a bf16 context");
-  if (d->M < 0 || d->K < 1 || d->N < 1) return fail(c, FARD_ESHAPE, "M >= 0, K, N >= 1 required");
-  if (d->M == 0) return FARD_OK;
-  if (!d->A || !d->W || !d->out) return fail(c, FARD_EINVAL, "null argument");
-  if (d->act < 0 || d->act > 2 || d->a_act < 0 || d->a_act > 2) return fail(c, FARD_EINVAL, "act");
-  if (d->a_mode < 0 || d->a_mode > 2 || d->epi < 0 || d->epi > 3 || d->norm_kind < 0 || d->norm_kind > 1 || d->splits < -1 ||
-      (d->splits == -1 && d->a_mode != 0))
-    return fail(c, FARD_EINVAL, "selector");
-  if (d->epi == 3 && !d->gate) return fail(c, FARD_EINVAL, "epi 3 needs gate");
-  if ((d->scale == nullptr) != (d->shift == nullptr)) return fail(c, FARD_EINVAL, "scale and shift go together");
-  SkinnyArgs x;
-  x.g.A = d->A; x.g.lda = d->K; x.g.bias = d->bias; x.g.out = d->out; x.g.ldo = d->N;
-  x.g.gate = d->gate; x.g.ldg = d->N; x.g.M = d->M; x.g.N = d->N; x.g.K = d->K; x.g.m_dev = nullptr;
-  x.g.act = d->act; x.g.epi = d->epi;
-  x.a_mode = d->a_mode; x.a_bias = d->a_bias; x.a_act = d->a_act;
-  x.ln_gain = d->gain; x.ln_beta = d->beta; x.ln_scale = d->scale; x.ln_shift = d->shift; x.ld_mod = d->K;
-  x.ln_eps = d->norm_eps; x.norm_kind = d->norm_kind;
-  x.force_splits = d->splits;
-  x.g.W = nullptr;
-  const bool narrow = d->splits == -1;
-  if (narrow ? !(narrow_supported(x.g) && d->M <= 1024) : !skinny_fits(x)) return fail(c, FARD_ESHAPE, "fused GEMM: M <= 64, K % 64 == 0, N % 32 == 0; a_mode 2: K % 256 == 0, K <= 2048; epi 0/1: K <= 2240 (M <= 32) or 1088");
-  const size_t bytes = (size_t)d->K * d->N * 2;
+  if (!c->bf16) return fail(c, FARD_EINVAL, "spec_gemm_narrow needs a bf16 context");
+  if (M < 0 || K < 1 || N < 1) return fail(c, FARD_ESHAPE, "M >= 0, K, N >= 1 required");
+  if (M == 0) return FARD_OK;
+  if (!A || !W || !out) return fail(c, FARD_EINVAL, "null argument");
+  if (act < 0 || act > 2 || epi < 0 || epi > 3) return fail(c, FARD_EINVAL, "selector");
+  if (epi == 3 && !gate) return fail(c, FARD_EINVAL, "epi 3 needs gate");
+  GemmArgs a;
+  a.A = A; a.lda = K; a.W = nullptr; a.bias = bias; a.out = out; a.ldo = N; a.gate = gate; a.ldg = N;
+  a.M = M; a.N = N; a.K = K; a.m_dev = nullptr; a.act = act; a.epi = epi;
+  if (!narrow_supported(a) || M > 1024) return fail(c, FARD_ESHAPE, "narrow GEMM needs M <= 1024, K % 64 == 0, N % 32 == 0");
+  const size_t bytes = (size_t)K * N * 2;
   if (bytes > c->gemm_tmp_bytes) {
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
@@ -998,10 +987,10 @@ int spec_gemm_fused(fard_ctx* c, const fard_fused_gemm* d) {
     HIPCHK(c, hipMalloc(&c->gemm_tmp, bytes));
     c->gemm_tmp_bytes = bytes;
   }
-  HIPCHK(c, launch_pack_weight(c->stream, d->W, 1, d->N, d->K, d->N, c->gemm_tmp, 0, 1));
-  x.g.W = c->gemm_tmp;
-  { Bracket br(c, CLS_GEMM, 2.0 * d->M * (double)d->N * d->K, (double)d->K * d->N * 2);
-    HIPCHK(c, narrow ? launch_gemm_narrow(c->stream, x.g) : launch_gemm_skinny(c->stream, x)); }
+  HIPCHK(c, launch_pack_weight(c->stream, W, 1, N, K, N, c->gemm_tmp, 0, 1));
+  a.W = c->gemm_tmp;
+  { Bracket br(c, CLS_GEMM, 2.0 * M * (double)N * K, (double)K * N * 2);
+    HIPCHK(c, launch_gemm_narrow(c->stream, a)); }
   return FARD_OK;
 }
 

@@ -35,36 +35,6 @@ inline size_t packed_elems(int K, int N) { return (size_t)K * (size_t)N; }
 hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a);
 hipError_t launch_gemm_f32(hipStream_t s, const GemmArgs& a);
 
-// ---- skinny GEMM (M <= 64) with fused activation-side work
-enum SkinnyAMode {
-  SK_A_BF16 = 0,       // A bf16 [M, K]
-  SK_A_ACT = 1,        // A fp32 [M, K] raw sums; operand = a_act(A + a_bias[k])
-  SK_A_NORM = 2,       // A fp32 [M, K] stream; operand = norm(A) * gain[k] + beta[k], then * (1 + scale[m,k]) + shift[m,k]
-};
-constexpr int SK_LDS_MAX = 144 * 1024;
-
-struct SkinnyArgs {
-  GemmArgs g;              // A / lda follow a_mode; K is the full row width for SK_A_NORM
-  int a_mode = SK_A_BF16;
-  const float* a_bias = nullptr;
-  int a_act = 0;
-  const float* ln_gain = nullptr;   // [K] or nullptr
-  const float* ln_beta = nullptr;   // [K] or nullptr
-  const float* ln_scale = nullptr;  // [M, ld_mod] or nullptr (with ln_shift)
-  const float* ln_shift = nullptr;
-  int ld_mod = 0;
-  float ln_eps = 1e-5f;
-  int norm_kind = 0;                // 0 layer norm, 1 RMS norm
-  float* zero_ptr = nullptr;        // optional side job: clear zero_n floats (zero_n % 4 == 0, 16-byte aligned)
-  int zero_n = 0;
-  int force_splits = 0;             // tuning hook; 0 = built-in choice
-};
-
-// Shape limits of the kernel; skinny_fits also checks that an unsplittable epilogue's K fits in LDS.
-bool skinny_supported(const SkinnyArgs& x);
-bool skinny_fits(const SkinnyArgs& x);
-hipError_t launch_gemm_skinny(hipStream_t s, const SkinnyArgs& x);
-
 // Narrow-tile GEMM: one workgroup per 16 columns and 16-64 rows, no K split (no atomics; EPI_RESID and
 // EPI_GATE_RESID read-modify-write their tile), bf16 A.  Meant for M <= 64, or a few hundred rows when K
 // and N are about 1024.

@@ -1,0 +1,177 @@
+// Narrow-tile GEMM for the small-batch GEMMs of a round.
+//
+// The draft steps and their diffusion-head decodes multiply a few dozen rows by 2-8 MB weight matrices,
+// hundreds of times per round, in one dependent chain: a launch costs one memory round trip whatever it
+// computes, so the kernel is built to need exactly one.  No K split, so any epilogue works without
+// atomics and the result is deterministic.  One workgroup per 16 weight columns
+// (v_mfma_f32_16x16x32_bf16: lane l holds row / column l % 16 and k = 8 (l / 16) .. + 8 of a 32-k step;
+// accumulator register e is row 4 (l / 16) + e); the 4 waves interleave the 32-k steps.  Weight and
+// activation fragments go straight from memory into MFMA operand registers -- the 16-column B fragment is
+// two 256-byte halves of the packed 32-column fragments -- so a wave's first SK_P steps are one memory
+// round trip with no LDS staging and no barrier before the MFMAs.  MT: 16-row tiles per workgroup;
+// blockIdx.y walks the row slabs.
+//
+// Measured alternatives that lost and are not kept: 32-column tiles with K split over workgroups and fp32
+// atomics (the atomics cost 1-2 us per launch and grow with the split count); folding the preceding
+// norm into the operand load (fp32 rows read in MFMA fragment order touch 4x the cache lines of the bf16
+// operand, and recomputing row statistics in every workgroup hot-spots the L2 lines of those rows).
+#include "gemm.h"
+
+namespace fard {
+
+namespace {
+
+constexpr int SK_P = 8;                 // fragments per operand a wave keeps in flight
+constexpr int NR_LDT = 20;              // floats per row of a partial tile in LDS
+
+// Epilogue of the narrow-tile kernels: thread -> (row, 2 columns) of the [16 MT, 16] tile.  The operands
+// that do not depend on the product (gate, old value of a read-modify-write target, bias) are requested by
+// prefetch() at kernel start; finish() adds the 4 waves' partial tiles through LDS and writes the result.
+template <int MT>
+struct NarrowEpi {
+  static constexpr int EP = (16 * MT + 31) / 32;           // passes of 32 rows
+  float2 gate[EP], old[EP], bias2;
+  int er, ec;
+  __device__ __forceinline__ void prefetch(const GemmArgs& a, int M, int m0, int n0) {
+    er = threadIdx.x >> 3;
+    ec = (threadIdx.x & 7) * 2;
+    bias2 = float2{0.f, 0.f};
+    const bool rmw = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
+#pragma unroll
+    for (int i = 0; i < EP; ++i) {
+      int r = m0 + er + 32 * i;
+      r = r < M ? r : M - 1;
+      gate[i] = float2{1.f, 1.f};
+      old[i] = float2{0.f, 0.f};
+      if (a.epi == EPI_GATE_RESID) gate[i] = *(const float2*)(a.gate + (size_t)r * a.ldg + n0 + ec);
+      if (rmw) old[i] = *(const float2*)((const float*)a.out + (size_t)r * a.ldo + n0 + ec);
+    }
+    if (a.bias != nullptr) bias2 = *(const float2*)(a.bias + n0 + ec);
+  }
+  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT], float* red, int M, int m0, int n0) {
+    const int lane = threadIdx.x & 63, kw = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        red[(kw * 16 * MT + 16 * i + 4 * (lane >> 4) + e) * NR_LDT + (lane & 15)] = acc[i][e];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < EP; ++i) {
+      const int row = er + 32 * i;
+      if (m0 + row >= M || row >= 16 * MT) continue;
+      float2 v = bias2;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float2 pv = *(const float2*)(red + (k * 16 * MT + row) * NR_LDT + ec);
+        v.x += pv.x;
+        v.y += pv.y;
+      }
+      const size_t o = (size_t)(m0 + row) * a.ldo + n0 + ec;
+      if (a.epi == EPI_STORE) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 t;
+        t[0] = (bf16)apply_act(v.x, a.act);
+        t[1] = (bf16)apply_act(v.y, a.act);
+        *(bf16x2*)((bf16*)a.out + o) = t;
+      } else if (a.epi == EPI_STORE_F32) {
+        *(float2*)((float*)a.out + o) = float2{apply_act(v.x, a.act), apply_act(v.y, a.act)};
+      } else {
+        *(float2*)((float*)a.out + o) = float2{old[i].x + gate[i].x * v.x, old[i].y + gate[i].y * v.y};
+      }
+    }
+  }
+};
+
+template <int MT, bool ONESHOT>
+__global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
+  __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * NR_LDT];
+  const int M = eff_rows(a.M, a.m_dev);
+  const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
+  if (m0 >= M) return;
+  const int c16 = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
+  const int kb16 = a.K >> 4, kb32 = a.K >> 5;
+  const int my_steps = (kb32 - kw + 3) >> 2;               // steps kw, kw + 4, ... (may be 0)
+  const int n0 = c16 * 16;
+
+  // packed B: fragment (nb, kb16 index) holds lane L = 32 * (k / 8 % 2) + n % 32
+  const int kg = lane >> 4;                                // k group of this lane inside a 32-k step
+  const bf16x8* __restrict__ bbase = (const bf16x8*)a.W + (size_t)(c16 >> 1) * kb16 * 64 + (kg >> 1) * 64 +
+                                     (kg & 1) * 32 + (c16 & 1) * 16 + (lane & 15);
+  const bf16* __restrict__ abase[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    int r = m0 + 16 * i + (lane & 15);
+    r = r < M ? r : M - 1;
+    abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
+  }
+  bf16x8 breg[SK_P], areg[SK_P][MT];
+  auto load_ab = [&](int t, int p) {
+    int s = kw + 4 * t;
+    s = s < kb32 ? s : kb32 - 1;                           // past the end: a re-read, zeroed at use
+    breg[p] = bbase[(size_t)s * 128];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 32);
+  };
+#pragma unroll
+  for (int p = 0; p < SK_P; ++p) load_ab(p, p);
+
+  NarrowEpi<MT> epi;
+  epi.prefetch(a, M, m0, n0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  f32x4 acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 zero8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
+  if constexpr (ONESHOT) {
+#pragma unroll
+    for (int g = 0; g < SK_P; ++g) {
+      const bf16x8 b = (g < my_steps) ? breg[g] : zero8;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
+    }
+  } else {
+    for (int t0 = 0; t0 < my_steps; t0 += SK_P) {
+#pragma unroll
+      for (int g = 0; g < SK_P; ++g) {
+        const bf16x8 b = (t0 + g < my_steps) ? breg[g] : zero8;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
+        load_ab(t0 + g + SK_P, g);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+
+  epi.finish(a, acc, red, M, m0, n0);
+}
+
+}  // namespace
+
+bool narrow_supported(const GemmArgs& a) {
+  return a.M >= 1 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
+}
+
+hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
+  if (!narrow_supported(a)) return hipErrorInvalidValue;
+  const bool oneshot = (a.K / 32 + 3) / 4 <= SK_P;
+  // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
+  // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
+#define FARD_NR(MTV)                                                                  \
+  do {                                                                                \
+    const dim3 grid(a.N / 16, (a.M + 16 * MTV - 1) / (16 * MTV));                     \
+    if (oneshot) gemm_narrow_kernel<MTV, true><<<grid, 256, 0, s>>>(a);               \
+    else gemm_narrow_kernel<MTV, false><<<grid, 256, 0, s>>>(a);                      \
+  } while (0)
+  if (a.M <= 16) FARD_NR(1);
+  else if (a.M <= 32 || a.M > 64) FARD_NR(2);
+  else FARD_NR(4);
+#undef FARD_NR
+  return hipGetLastError();
+}
+
+}  // namespace fard

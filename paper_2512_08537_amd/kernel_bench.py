@@ -2,6 +2,7 @@
 """Per-kernel roofline measurements that the round benchmark cannot isolate.
 
   python -m paper_2512_08537_amd.kernel_bench entropy     # entropy pre-filter: config shapes + 2^20-row shape
+  python -m paper_2512_08537_amd.kernel_bench narrow      # narrow-tile GEMM launches (time them with rocprofv3 --kernel-trace)
 
 Prints one JSON line per measurement: algorithmic bytes / HIP-event time on the library's stream.
 """
@@ -49,47 +50,29 @@ def entropy():
     ctx.close()
 
 
-def fused():
-    """Launches the small-batch fused GEMM at the shapes of a configs[1] draft step; kernel durations are read
-    from a rocprofv3 kernel trace of this run (the host loop here is slower than the kernels)."""
+def narrow():
+    """Launches the narrow-tile GEMM at the shapes of a configs[1] round; kernel durations are read from a
+    rocprofv3 kernel trace of this run (the host loop here is slower than the kernels)."""
     import torch
     from tests.harness import build_case, make_ctx
     case = build_case("ln-gelu-bf16", seed=0)
     ctx = make_ctx(case)
     dev = ctx.dev
-    cases = []
-    for M in (32, 64, 288):
-        for (K, N, a_mode, epi, splits) in [(1024, 1024, 0, 2, 0), (1024, 1024, 0, 2, 4), (1024, 1024, 0, 2, 16),
-                                            (1024, 1024, 0, 3, 0), (1024, 1024, 1, 3, 0), (1024, 1024, 2, 2, 0),
-                                            (1024, 1024, 2, 2, 4), (1024, 1024, 0, 0, 0),
-                                            (1024, 20480, 0, 1, 0), (1024, 20480, 1, 1, 0),
-                                            (4096, 1024, 1, 2, 0), (4096, 1024, 1, 2, 16), (1024, 4096, 2, 2, 0),
-                                            (1024, 4096, 2, 2, 4), (1024, 3072, 2, 2, 0), (1024, 3072, 2, 2, 4),
-                                            (1024, 1024, 0, 0, -1), (1024, 1024, 0, 2, -1), (1024, 1024, 0, 3, -1),
-                                            (4096, 1024, 0, 2, -1), (1024, 4096, 0, 0, -1), (1024, 3072, 0, 0, -1)]:
-            if M <= 64 or splits == -1:
-                cases.append((M, K, N, a_mode, epi, splits))
-    for (M, K, N, a_mode, epi, splits) in cases:
-        W = (torch.randn((K, N), device=dev) * 0.02).to(torch.bfloat16)
-        A = torch.randn((M, K), device=dev)
-        if a_mode == 0:
-            A = A.to(torch.bfloat16)
-        kw = {}
-        if a_mode == 1:
-            kw = dict(a_bias=torch.zeros(K, device=dev), a_act=2)
-        if a_mode == 2:
-            kw = dict(scale=torch.zeros((M, K), device=dev), shift=torch.zeros((M, K), device=dev))
-        out = torch.zeros((M, N), device=dev, dtype=torch.bfloat16 if epi == 0 else torch.float32)
-        if epi == 3:
-            kw["gate"] = torch.ones((M, N), device=dev)
-        bias = torch.zeros(N, device=dev)
-        for _ in range(12):
-            ctx.spec_gemm_fused(A, W, out, bias=bias, a_mode=a_mode, epi=epi, act=0, splits=splits, **kw)
-        ctx.sync()
-        print(json.dumps({"case": [M, K, N, a_mode, epi, splits]}), flush=True)
+    for M in (16, 32, 64, 288):
+        for (K, N, epi) in [(1024, 1024, 0), (1024, 1024, 2), (1024, 1024, 3), (4096, 1024, 2), (1024, 4096, 0),
+                            (1024, 3072, 0), (1280, 1280, 3), (2048, 2048, 0)]:
+            W = (torch.randn((K, N), device=dev) * 0.02).to(torch.bfloat16)
+            A = torch.randn((M, K), device=dev).to(torch.bfloat16)
+            out = torch.zeros((M, N), device=dev, dtype=torch.bfloat16 if epi == 0 else torch.float32)
+            gate = torch.ones((M, N), device=dev) if epi == 3 else None
+            bias = torch.zeros(N, device=dev)
+            for _ in range(12):
+                ctx.spec_gemm_narrow(A, W, out, bias=bias, gate=gate, epi=epi)
+            ctx.sync()
+            print(json.dumps({"case": [M, K, N, epi]}), flush=True)
     ctx.close()
 
 
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "entropy"
-    {"entropy": entropy, "fused": fused}[what]()
+    {"entropy": entropy, "narrow": narrow}[what]()

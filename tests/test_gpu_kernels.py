@@ -49,58 +49,26 @@ def test_gemm_bf16_matches_fp64(ctx_bf16, M, K, N, act):
     assert rel_inf(got, ref) < 1e-2
 
 
-_FUSED_CASES = [
-    # M, K, N, a_mode, epi, splits
-    (32, 1024, 1024, 0, 0, 0), (32, 1024, 1024, 0, 2, 0), (32, 1024, 1024, 0, 3, 0), (5, 256, 64, 0, 1, 0),
-    (33, 512, 96, 0, 2, 3), (64, 1280, 1280, 0, 3, 0), (40, 4096, 128, 0, 2, 0), (17, 2240, 64, 0, 0, 0),
-    (32, 1024, 1024, 1, 3, 0), (7, 4096, 1024, 1, 2, 0), (64, 1088, 32, 1, 0, 0), (50, 512, 160, 1, 1, 0),
-    (32, 1024, 1024, 2, 2, 0), (32, 1024, 4096, 2, 2, 2), (9, 256, 64, 2, 0, 0), (64, 1280, 640, 2, 2, 5),
-    (33, 2048, 96, 2, 2, 0), (30, 2048, 96, 2, 1, 0), (3, 1536, 256, 2, 3, 0),
-    # splits -1: narrow tiles, K never split
-    (32, 1024, 1024, 0, 0, -1), (32, 1024, 1024, 0, 3, -1), (13, 64, 32, 0, 1, -1), (16, 1280, 96, 0, 2, -1),
-    (17, 4096, 1024, 0, 2, -1), (64, 1024, 160, 0, 3, -1), (49, 1536, 64, 0, 0, -1), (1, 192, 32, 0, 1, -1),
-    (288, 1024, 1024, 0, 2, -1), (130, 512, 96, 0, 3, -1), (97, 256, 64, 0, 0, -1),
+_NARROW_CASES = [
+    # M, K, N, epi
+    (32, 1024, 1024, 0), (32, 1024, 1024, 3), (13, 64, 32, 1), (16, 1280, 96, 2), (17, 4096, 1024, 2),
+    (64, 1024, 160, 3), (49, 1536, 64, 0), (1, 192, 32, 1), (288, 1024, 1024, 2), (130, 512, 96, 3),
+    (97, 256, 64, 0), (32, 1024, 4096, 0), (5, 2048, 64, 2),
 ]
 
 
-@pytest.mark.parametrize("M,K,N,a_mode,epi,splits", _FUSED_CASES)
-def test_gemm_fused_matches_fp64(ctx_bf16, M, K, N, a_mode, epi, splits):
-    """Small-batch GEMM with the operand-side work folded in: bf16 operand, act(sums + bias), norm(+AdaLN)."""
+@pytest.mark.parametrize("M,K,N,epi", _NARROW_CASES)
+def test_gemm_narrow_matches_fp64(ctx_bf16, M, K, N, epi):
+    """Narrow-tile GEMM (no K split): every epilogue, one-shot and ring loops, ragged row slabs."""
     import torch
     from oracle import transformer as otf
     ctx, _ = ctx_bf16
-    tag = f"{M}.{K}.{N}.{a_mode}.{epi}"
+    tag = f"{M}.{K}.{N}.{epi}"
+    A = gen.normal(13, "A" + tag, (M, K), 1.0, DT_BF16)
     W = gen.normal(13, "W" + tag, (K, N), 0.05, DT_BF16)
     b = gen.normal(13, "b" + tag, (N,), 0.1, DT_F32)
-    kw = {}
-    if a_mode == 0:
-        A = gen.normal(13, "A" + tag, (M, K), 1.0, DT_BF16)
-        op = A.astype(np.float64)
-        A_dev = ctx.dev_store(A)
-    elif a_mode == 1:
-        A = gen.normal(13, "A" + tag, (M, K), 1.5, DT_F32)
-        ab = gen.normal(13, "ab" + tag, (K,), 0.3, DT_F32)
-        a_act = 1 + (M % 2)
-        op = {1: otf.gelu_erf, 2: otf.silu}[a_act](A.astype(np.float64) + ab)
-        A_dev = ctx.dev_f32(A)
-        kw = dict(a_bias=ctx.dev_f32(ab), a_act=a_act)
-    else:
-        A = gen.normal(13, "A" + tag, (M, K), 2.0, DT_F32) + 0.7
-        g = 1.0 + gen.normal(13, "g" + tag, (K,), 0.1, DT_F32)
-        be = gen.normal(13, "be" + tag, (K,), 0.1, DT_F32)
-        kind = M % 2
-        eps = 1e-5 if kind == 0 else 1e-6
-        x64 = A.astype(np.float64)
-        op = otf.layer_norm(x64, g, be, eps) if kind == 0 else otf.rms_norm(x64, g, eps) + be
-        kw = dict(gain=ctx.dev_f32(g), beta=ctx.dev_f32(be), norm_kind=kind, norm_eps=eps)
-        if N % 64 == 0:                                      # AdaLN modulation on top
-            sc = gen.normal(13, "sc" + tag, (M, K), 0.2, DT_F32)
-            sh = gen.normal(13, "sh" + tag, (M, K), 0.2, DT_F32)
-            op = op * (1.0 + sc) + sh
-            kw.update(scale=ctx.dev_f32(sc), shift=ctx.dev_f32(sh))
-        A_dev = ctx.dev_f32(A)
-    ref = op @ W.astype(np.float64) + b
-    act = 0
+    ref = A.astype(np.float64) @ W.astype(np.float64) + b
+    act, kw = 0, {}
     if epi in (0, 1):
         act = 2 if epi == 0 else 1
         ref = {1: otf.gelu_erf, 2: otf.silu}[act](ref)
@@ -113,25 +81,30 @@ def test_gemm_fused_matches_fp64(ctx_bf16, M, K, N, a_mode, epi, splits):
             kw["gate"] = ctx.dev_f32(gate)
         ref = base + ref
         out = ctx.dev_f32(base)
-    ctx.spec_gemm_fused(A_dev, ctx.dev_store(W), out, bias=ctx.dev_f32(b), a_mode=a_mode, epi=epi, act=act,
-                        splits=splits, **kw)
+    ctx.spec_gemm_narrow(ctx.dev_store(A), ctx.dev_store(W), out, bias=ctx.dev_f32(b), epi=epi, act=act, **kw)
     ctx.sync()
-    got = out.float().cpu().numpy()
-    err = rel_inf(got, ref)
+    err = rel_inf(out.float().cpu().numpy(), ref)
     assert err < 1e-2, err
 
 
-def test_gemm_fused_rejects_bad_shapes(ctx_bf16):
+def test_gemm_narrow_is_deterministic_and_rejects_bad_shapes(ctx_bf16):
     import torch
     ctx, _ = ctx_bf16
-    A = torch.zeros((65, 64), dtype=ctx.tdtype, device=ctx.dev)
-    W = torch.zeros((64, 32), dtype=ctx.tdtype, device=ctx.dev)
+    A = ctx.dev_store(gen.normal(14, "A", (32, 1024), 1.0, DT_BF16))
+    W = ctx.dev_store(gen.normal(14, "W", (1024, 256), 0.05, DT_BF16))
+    base = gen.normal(14, "o", (32, 256), 1.0, DT_F32)
+    outs = []
+    for _ in range(3):
+        o = ctx.dev_f32(base)
+        ctx.spec_gemm_narrow(A, W, o, epi=2)
+        ctx.sync()
+        outs.append(o.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    Wbad = torch.zeros((96, 32), dtype=ctx.tdtype, device=ctx.dev)          # K % 64 != 0
     with pytest.raises(Exception):
-        ctx.spec_gemm_fused(A, W, ctx.empty((65, 32), ctx.tdtype))
-    Af = torch.zeros((4, 2304), dtype=torch.float32, device=ctx.dev)
-    W2 = torch.zeros((2304, 32), dtype=ctx.tdtype, device=ctx.dev)
-    with pytest.raises(Exception):
-        ctx.spec_gemm_fused(Af, W2, ctx.empty((4, 32), ctx.tdtype), a_mode=2)
+        ctx.spec_gemm_narrow(torch.zeros((4, 96), dtype=ctx.tdtype, device=ctx.dev), Wbad, ctx.empty((4, 32), ctx.tdtype))
+    with pytest.raises(Exception):                                            # epi 3 without gate
+        ctx.spec_gemm_narrow(A, W, ctx.dev_f32(base), epi=3)
 
 
 def test_gemm_f32_matches_fp64(ctx_f32):
