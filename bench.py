@@ -26,6 +26,20 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 
+def hbm_traffic_per_launch(config):
+    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary of this benchmark (FETCH_SIZE and
+    WRITE_SIZE, scaled by a plain copy kernel); None when no summary covers the configuration."""
+    path = os.path.join(ROOT, "profiles", f"gemm_cfg{config}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,11 +111,14 @@ def main():
     g_avg_us = g["ms"] / max(g["launches"], 1) * 1e3
     g_tflops = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
     peak = PEAK_BF16_TFLOPS if rc.dtype == 1 else PEAK_FP32_TFLOPS
-    roofline = {"bound": "mfma" if rc.dtype == 1 else "alu", "kernel": "gemm_bf16_kernel (all verify/draft/head GEMMs)",
+    roofline = {"bound": "mfma" if rc.dtype == 1 else "alu",
+                "kernel": "GEMM kernels of the round (gemm_narrow_kernel, gemm_bf16_res_kernel, gemm_bf16_kernel)",
                 "achieved": round(g_tflops, 3), "peak": peak, "unit": "TFLOP/s", "frac": round(g_tflops / peak, 5),
-                "traffic": None, "launches_per_step": g["launches"] / args.steps,
+                "traffic": hbm_traffic_per_launch(args.config), "launches_per_step": g["launches"] / args.steps,
                 "avg_launch_us": round(g_avg_us, 3),
-                "flops_per_launch": g["flops"] / max(g["launches"], 1)}
+                "flops_per_launch": g["flops"] / max(g["launches"], 1),
+                "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
+                "achieved_GBs": round(g["bytes"] / (g["ms"] * 1e-3) / 1e9, 1) if g["ms"] > 0 else 0.0}
     # attention: algorithmic K/V bytes of the verify forward + the K draft steps
     t, d = rc.target, rc.draft
     esz = 2 if rc.dtype == 1 else 4

@@ -3,6 +3,7 @@
 
   python -m paper_2512_08537_amd.kernel_bench entropy     # entropy pre-filter: config shapes + 2^20-row shape
   python -m paper_2512_08537_amd.kernel_bench narrow      # narrow-tile GEMM launches (time them with rocprofv3 --kernel-trace)
+  python -m paper_2512_08537_amd.kernel_bench copy        # 256 MiB copy: calibration of the HBM traffic counters
 
 Prints one JSON line per measurement: algorithmic bytes / HIP-event time on the library's stream.
 """
@@ -73,6 +74,19 @@ def narrow():
     ctx.close()
 
 
+def copy():
+    """A plain device copy of known size (256 MiB read + 256 MiB written per launch): the yardstick that the
+    FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run are scaled by."""
+    import torch
+    n = 64 << 20
+    a = torch.zeros(n, device="cuda", dtype=torch.float32)
+    b = torch.ones(n, device="cuda", dtype=torch.float32)
+    for _ in range(5):
+        a.copy_(b)
+    torch.cuda.synchronize()
+    print(json.dumps({"kernel": "torch copy_", "bytes_read": n * 4, "bytes_written": n * 4, "launches": 5}), flush=True)
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "entropy"
-    {"entropy": entropy, "narrow": narrow}[what]()
+    {"entropy": entropy, "narrow": narrow, "copy": copy}[what]()
