@@ -535,12 +535,16 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
       HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, nullptr, nullptr, 0, nullptr, c->u)); }
     HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
     KvGeom kg = kv_geom(c, m, l);
-    { Bracket br(c, CLS_OTHER);
+    // learned positions, bf16: the attention kernel stores the new K / V rows itself
+    const bool fused_append = c->bf16 && t.pos != FARD_POS_ROPE;
+    if (!fused_append) {
+      Bracket br(c, CLS_OTHER);
       HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE, t.rope_theta, c->maps.row_sample,
-                                   c->maps.row_pos, M, m_dev)); }
+                                   c->maps.row_pos, M, m_dev));
+    }
     { Bracket br(c, CLS_ATTN);
       HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, m.len, c->maps.row_start, B, nq_max, c->ao, HD,
-                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr)); }
+                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0)); }
     HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
     { Bracket br(c, CLS_OTHER);
       HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u)); }

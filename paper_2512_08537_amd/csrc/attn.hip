@@ -13,6 +13,9 @@
 // entropy ln l - a/l of the attention distribution (Eq. 1 / S2.1 indicator) falls out for free.
 // With grouped KV heads the G query heads of a KV head are packed into the columns (G*n_q <= 64).
 //
+// With learned positions (no RoPE) the kernel also appends the new rows' K and V to the cache, so a layer
+// needs no separate append launch.
+//
 // fp32 path: one wave per (row, head), scores staged in LDS; for the small fp32 configuration.
 #include "kernels.h"
 
@@ -24,7 +27,7 @@ template <int DH, int NQB>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
                                                         const int* __restrict__ cache_len,
                                                         const int* __restrict__ row_start, bf16* __restrict__ out,
-                                                        int ldo, float* __restrict__ ent_heads) {
+                                                        int ldo, float* __restrict__ ent_heads, int append) {
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
@@ -65,8 +68,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   }
 
   const size_t head_elems = (size_t)kv.ctx_pad * DH;
-  const bf16* Kb = (const bf16*)kv.k + ((size_t)b * Hk + hk) * head_elems;
-  const bf16* Vb = (const bf16*)kv.v + ((size_t)b * Hk + hk) * head_elems;
+  bf16* Kb = (bf16*)kv.k + ((size_t)b * Hk + hk) * head_elems;
+  bf16* Vb = (bf16*)kv.v + ((size_t)b * Hk + hk) * head_elems;
 
   float m_run[NQB], l_run[NQB], a_run[NQB];
   f32x16 o[DB][NQB];
@@ -83,7 +86,28 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 
   const int n_keys = p0 + nq;
   const int n_blocks = (n_keys + 31) >> 5;
-  for (int kb = wave; kb < n_blocks; kb += 4) {
+  // Blocks that hold only cached positions come first; with `append` the workgroup then stores the new rows'
+  // K and V into the cache (it owns this sample's kv head) and reads the blocks that contain them afterwards.
+  const int tail0 = append ? (p0 >> 5) : n_blocks;
+  for (int phase = 0; phase < 2; ++phase) {
+    if (phase == 1) {
+      if (!append) break;
+      const bf16* ksrc = qkv + (size_t)r0 * ld + (size_t)(n_heads + hk) * DH;
+      const bf16* vsrc = ksrc + (size_t)Hk * DH;
+      constexpr int D8 = DH / 8;
+      for (int idx = tid; idx < nq * D8; idx += 256) {       // K: 8 dims of a key are contiguous in the cache
+        const int j = idx / D8, d8 = idx - j * D8;
+        *(bf16x8*)(Kb + k_offset_bf16(p0 + j, d8 * 8, DH)) = *(const bf16x8*)(ksrc + (size_t)j * ld + d8 * 8);
+      }
+      for (int idx = tid; idx < nq * DH; idx += 256) {       // V: keys are contiguous, dims are not
+        const int j = idx / DH, d = idx - j * DH;
+        Vb[v_offset_bf16(p0 + j, d, DH)] = vsrc[(size_t)j * ld + d];
+      }
+      __threadfence_block();
+      __syncthreads();
+    }
+    const int kb_lo = (phase == 0) ? 0 : tail0, kb_hi = (phase == 0) ? tail0 : n_blocks;
+  for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
     const bf16x8* kblk = (const bf16x8*)(Kb + (size_t)kb * 32 * DH);
     const bf16x8* vblk = (const bf16x8*)(Vb + (size_t)kb * 32 * DH);
     bf16x8 kf[DC];
@@ -154,6 +178,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
         for (int hf = 0; hf < 2; ++hf)
           o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[db][hf], pf[hf], o[db][qb], 0, 0, 0);
     }
+  }
   }
 
   // ---- merge the four waves
@@ -264,9 +289,10 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 }  // namespace
 
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv, const int* cache_len,
-                            const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads) {
+                            const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads, int append) {
   if (B <= 0 || nq_max <= 0) return hipSuccess;
   if (!kv.is_bf16) {
+    if (append) return hipErrorInvalidValue;
     dim3 grid(n_heads, nq_max, B);
     const size_t smem = (size_t)kv.ctx_pad * sizeof(float);
     if (smem > 64 * 1024) return hipErrorInvalidValue;
@@ -281,14 +307,14 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
   const bf16* q = (const bf16*)qkv;
   bf16* o = (bf16*)out;
   if (kv.d_head == 64) {
-    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
-    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
+    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
   } else if (kv.d_head == 128) {
-    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
-    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
+    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
   } else if (kv.d_head == 32) {
-    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
-    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads);
+    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
+    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
   } else {
     return hipErrorInvalidValue;
   }

@@ -46,6 +46,24 @@ hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M,
                        int norm_type, float eps, const float* g, const float* b, const float* shift,
                        const float* scale, int ldm, const int* in_map, void* out);
 
+// ---- KV cache addressing (device side)
+// bf16 cache, blocks of 32 positions.  K block: [d/16][lane][8] with lane = (pos%32) + 32*((d%16)/8):
+// the A operand of v_mfma_f32_32x32x16_bf16 with keys as rows.  V block: [d/32][half][lane][8] with
+// lane = d%32 + 32*g, holding the 8 keys {16*half + 8*(i/4) + 4*g + i%4}: the A operand of the
+// P*V product with dims as rows, keys ordered the way the score accumulators hold them.
+__device__ __forceinline__ size_t k_offset_bf16(int pos, int d, int dh) {
+  const int kb = pos >> 5, lr = pos & 31;
+  const int dc = d >> 4, g = (d >> 3) & 1, i = d & 7;
+  return (size_t)kb * 32 * dh + ((size_t)(dc * 64 + lr + 32 * g) << 3) + i;
+}
+__device__ __forceinline__ size_t v_offset_bf16(int pos, int d, int dh) {
+  const int kb = pos >> 5, pk = pos & 31;
+  const int hf = pk >> 4, rem = pk & 15;
+  const int g = (rem >> 2) & 1, i = ((rem >> 3) << 2) | (rem & 3);
+  const int db = d >> 5, lane = (d & 31) + 32 * g;
+  return (size_t)kb * 32 * dh + ((size_t)((db * 2 + hf) * 64 + lane) << 3) + i;
+}
+
 // Splits qkv[M, (H+2Hkv) dh] rows: optional RoPE on q (in place) and k, then stores k, v at
 // position row_pos[r] of sample row_sample[r] in the cache.
 hipError_t launch_rope_append(hipStream_t s, void* qkv, int ld, int n_heads, KvGeom kv, int rope,
@@ -57,9 +75,11 @@ hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v
 
 // Cached causal attention.  q rows come from qkv (row r, head g at column g*dh); output
 // out_T[r, g*dh + :].  ent_heads[r, g] (optional) receives the entropy of the attention row.
+// append != 0 (bf16 caches, no RoPE): the kernel itself stores the new rows' K and V at positions
+// cache_len[b] .. + n_q - 1 before it reads them, replacing a separate launch_rope_append.
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv,
                             const int* cache_len, const int* row_start, int B, int nq_max,
-                            void* out, int ldo, float* ent_heads);
+                            void* out, int ldo, float* ent_heads, int append);
 
 // Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
 // Up to ENT_SAMPLE_MODE_MIN_B samples: a wave per row, then one workgroup thresholds and compacts.  Above: a

@@ -8,24 +8,6 @@ namespace fard {
 
 namespace {
 
-// ================================================================== KV cache addressing
-// bf16 cache, blocks of 32 positions.  K block: [d/16][lane][8] with lane = (pos%32) + 32*((d%16)/8):
-// the A operand of v_mfma_f32_32x32x16_bf16 with keys as rows.  V block: [d/32][half][lane][8] with
-// lane = d%32 + 32*g, holding the 8 keys {16*half + 8*(i/4) + 4*g + i%4}: the A operand of the
-// P*V product with dims as rows, keys ordered the way the score accumulators hold them.
-__device__ __forceinline__ size_t k_offset_bf16(int pos, int d, int dh) {
-  const int kb = pos >> 5, lr = pos & 31;
-  const int dc = d >> 4, g = (d >> 3) & 1, i = d & 7;
-  return (size_t)kb * 32 * dh + ((size_t)(dc * 64 + lr + 32 * g) << 3) + i;
-}
-__device__ __forceinline__ size_t v_offset_bf16(int pos, int d, int dh) {
-  const int kb = pos >> 5, pk = pos & 31;
-  const int hf = pk >> 4, rem = pk & 15;
-  const int g = (rem >> 2) & 1, i = ((rem >> 3) << 2) | (rem & 3);
-  const int db = d >> 5, lane = (d & 31) + 32 * g;
-  return (size_t)kb * 32 * dh + ((size_t)((db * 2 + hf) * 64 + lane) << 3) + i;
-}
-
 // ================================================================== row maps
 __global__ __launch_bounds__(256) void build_rows_kernel(const int* n_base, int add, int B, int K, int D,
                                                          const int* cache_len, RowMaps maps,
