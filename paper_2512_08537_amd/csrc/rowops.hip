@@ -65,6 +65,26 @@ __global__ __launch_bounds__(256) void build_rows_kernel(const int* n_base, int 
 }
 
 // ================================================================== embedding
+// v + sum_k xv[k] * W[k, c] for a projection from D latent components (W [D, ld] row-major).  For D <= 16 every
+// weight and input load is issued before the first use: the sum is one memory round trip, not D.
+template <typename T, typename XP>
+__device__ __forceinline__ float in_proj(float v, XP xv, float xscale, int D, const T* __restrict__ W, int ld, int c) {
+  if (D <= 16) {
+    float wv[16], xr[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const int kk = k < D ? k : 0;
+      wv[k] = to_f32(W[(size_t)kk * ld + c]);
+      xr[k] = xv[kk];
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v += (k < D) ? (xr[k] * xscale) * wv[k] : 0.f;
+    return v;
+  }
+  for (int k = 0; k < D; ++k) v += (xv[k] * xscale) * to_f32(W[(size_t)k * ld + c]);
+  return v;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const float* __restrict__ x, int ldx, int D, const T* __restrict__ w_in,
                                                     const float* __restrict__ b_in, const T* __restrict__ pos_table,
@@ -81,9 +101,8 @@ __global__ __launch_bounds__(256) void embed_kernel(const float* __restrict__ x,
   if (id >= 0) {
     v = to_f32(cond_table[(size_t)id * d + c]);
   } else {
-    v = b_in ? b_in[c] : 0.f;
-    for (int k = 0; k < D; ++k) v += x[(size_t)r * ldx + k] * to_f32(w_in[(size_t)k * d + c]);
-    if (pos_table) v += to_f32(pos_table[(size_t)row_pos[r] * d + c]);
+    const float pv = pos_table ? to_f32(pos_table[(size_t)row_pos[r] * d + c]) : 0.f;
+    v = in_proj<T>(b_in ? b_in[c] : 0.f, x + (size_t)r * ldx, 1.0f, D, w_in, d, c) + pv;
   }
   h[(size_t)r * d + c] = v;
 }
@@ -589,9 +608,7 @@ __global__ __launch_bounds__(256) void head_prep_kernel(const float* __restrict_
   const float* xr = xsrc + (size_t)(xmap ? xmap[r] : r) * D;
   if (c < w) {
     const float czv = cz[(size_t)r * w + c];
-    float v = b_in[c];
-    for (int k = 0; k < D; ++k) v += (xr[k] * xscale) * to_f32(w_in[(size_t)k * w + c]);
-    hh[(size_t)r * w + c] = v;
+    hh[(size_t)r * w + c] = in_proj<T>(b_in[c], xr, xscale, D, w_in, w, c);
     for (int k = 0; k < S; ++k) sc[((size_t)k * n + r) * w + c] = from_f32<T>(silu(czv + temb[(size_t)k * w + c]));
   }
   if (xt_out && blockIdx.x == 0 && threadIdx.x < D) xt_out[(size_t)r * D + threadIdx.x] = xr[threadIdx.x] * xscale;
@@ -711,11 +728,8 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   __syncthreads();
   // input projection of the next step
   const T* w_in = (const T*)a.w_in;
-  for (int c = threadIdx.x; c < w; c += 256) {
-    float v = a.b_in[c];
-    for (int k = 0; k < D; ++k) v += xs[k] * to_f32(w_in[(size_t)k * w + c]);
-    a.hh_next[(size_t)r * w + c] = v;
-  }
+  for (int c = threadIdx.x; c < w; c += 256)
+    a.hh_next[(size_t)r * w + c] = in_proj<T>(a.b_in[c], (const float*)xs, 1.0f, D, w_in, w, c);
 }
 
 template <typename T>
