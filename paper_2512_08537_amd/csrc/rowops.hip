@@ -123,7 +123,7 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
 // One workgroup per row.  The row is read once with 16-byte loads and stays in registers for the
 // statistics and the output pass (d <= 256 * 4 * NORM_VPT); everything a thread needs is requested
 // before the first reduction so that the loads overlap.
-constexpr int NORM_VPT = 8;
+constexpr int NORM_VPT = 8;         // largest instance; the launcher picks the smallest VPT that covers d
 template <typename T>
 __device__ __forceinline__ void store4(T* p, float a, float b, float c, float d);
 template <>
@@ -137,7 +137,7 @@ __device__ __forceinline__ void store4<bf16>(bf16* p, float a, float b, float c,
   *(bf16x4*)p = v;
 }
 
-template <typename T>
+template <typename T, int VPT>
 __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, int d, int M, const int* m_dev,
                                                    int norm_type, float eps, const float* __restrict__ g,
                                                    const float* __restrict__ b, const float* __restrict__ shift,
@@ -149,20 +149,20 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
   if (r >= Me) return;
   const float* row = h + (size_t)(in_map ? in_map[r] : r) * d;
   const int n4 = d >> 2;                                   // d % 4 == 0 (checked on the host)
-  f32x4 x[NORM_VPT];
+  f32x4 x[VPT];
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < NORM_VPT; ++i) {
+  for (int i = 0; i < VPT; ++i) {
     const int c4 = threadIdx.x + i * 256;
     x[i] = (c4 < n4) ? ((const f32x4*)row)[c4] : f32x4{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll
-  for (int i = 0; i < NORM_VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
+  for (int i = 0; i < VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
   float mean = 0.f;
   if (norm_type == 0) mean = block_sum(s, red) / (float)d;
   float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < NORM_VPT; ++i) {
+  for (int i = 0; i < VPT; ++i) {
     const int c4 = threadIdx.x + i * 256;
     if (c4 < n4) {
 #pragma unroll
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
   const float var = block_sum(q, red) / (float)d;
   const float rstd = 1.0f / sqrtf(var + eps);
 #pragma unroll
-  for (int i = 0; i < NORM_VPT; ++i) {
+  for (int i = 0; i < VPT; ++i) {
     const int c4 = threadIdx.x + i * 256;
     if (c4 >= n4) continue;
     f32x4 y;
@@ -832,10 +832,18 @@ hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M,
                        const int* in_map, void* out) {
   if (M <= 0) return hipSuccess;
   if (d % 4 != 0 || d > 256 * 4 * NORM_VPT || ldm % 4 != 0) return hipErrorInvalidValue;
-  if (is_bf16)
-    norm_kernel<bf16><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out);
-  else
-    norm_kernel<float><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out);
+#define FARD_NORM(VPT)                                                                                                 \
+  do {                                                                                                                 \
+    if (is_bf16)                                                                                                       \
+      norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out);  \
+    else                                                                                                               \
+      norm_kernel<float, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out); \
+  } while (0)
+  if (d <= 1024) FARD_NORM(1);
+  else if (d <= 2048) FARD_NORM(2);
+  else if (d <= 4096) FARD_NORM(4);
+  else FARD_NORM(8);
+#undef FARD_NORM
   return hipGetLastError();
 }
 
