@@ -728,8 +728,34 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   __syncthreads();
   // input projection of the next step
   const T* w_in = (const T*)a.w_in;
-  for (int c = threadIdx.x; c < w; c += 256)
-    a.hh_next[(size_t)r * w + c] = in_proj<T>(a.b_in[c], (const float*)xs, 1.0f, D, w_in, w, c);
+  if (D <= 16) {
+    // 4 columns per thread and pass, all 64 weight loads in flight together
+    float xr[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) xr[k] = (k < D) ? xs[k] : 0.f;
+    for (int c0 = threadIdx.x; c0 < w; c0 += 1024) {
+      float wv[4][16], bj[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = (c0 + 256 * j < w) ? c0 + 256 * j : c0;
+        bj[j] = a.b_in[c];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) wv[j][k] = to_f32(w_in[(size_t)(k < D ? k : 0) * w + c]);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = c0 + 256 * j;
+        if (c >= w) continue;
+        float v = bj[j];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v += xr[k] * wv[j][k];
+        a.hh_next[(size_t)r * w + c] = v;
+      }
+    }
+  } else {
+    for (int c = threadIdx.x; c < w; c += 256)
+      a.hh_next[(size_t)r * w + c] = in_proj<T>(a.b_in[c], (const float*)xs, 1.0f, D, w_in, w, c);
+  }
 }
 
 template <typename T>
