@@ -7,8 +7,8 @@
 // (v_mfma_f32_16x16x32_bf16: lane l holds row / column l % 16 and k = 8 (l / 16) .. + 8 of a 32-k step;
 // accumulator register e is row 4 (l / 16) + e); the 4 waves interleave the 32-k steps.  Weight and
 // activation fragments go straight from memory into MFMA operand registers -- the 16-column B fragment is
-// two 256-byte halves of the packed 32-column fragments -- so a wave's first SK_P steps are one memory
-// round trip with no LDS staging and no barrier before the MFMAs.  MT: 16-row tiles per workgroup;
+// two 256-byte halves of the packed 32-column fragments -- so a wave's first NS steps are one memory
+// round trip with no LDS staging and no barrier before the MFMAs.  MT: 16-row tiles per workgroup (1 or 2);
 // blockIdx.y walks the row slabs.
 //
 // Measured alternatives that lost and are not kept: 32-column tiles with K split over workgroups and fp32
@@ -21,7 +21,6 @@ namespace fard {
 
 namespace {
 
-constexpr int SK_P = 8;                 // fragments per operand a wave keeps in flight
 constexpr int NR_LDT = 20;              // floats per row of a partial tile in LDS
 
 // Epilogue of the narrow-tile kernels: thread -> (row, 2 columns) of the [16 MT, 16] tile.  The operands
@@ -83,7 +82,8 @@ struct NarrowEpi {
   }
 };
 
-template <int MT, bool ONESHOT>
+// NS: k-steps per operand a wave keeps in flight (its whole K range when ONESHOT).
+template <int MT, int NS, bool ONESHOT>
 __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * NR_LDT];
   const int M = eff_rows(a.M, a.m_dev);
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
     r = r < M ? r : M - 1;
     abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
   }
-  bf16x8 breg[SK_P], areg[SK_P][MT];
+  bf16x8 breg[NS], areg[NS][MT];
   auto load_ab = [&](int t, int p) {
     int s = kw + 4 * t;
     s = s < kb32 ? s : kb32 - 1;                           // past the end: a re-read, zeroed at use
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
     for (int i = 0; i < MT; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 32);
   };
 #pragma unroll
-  for (int p = 0; p < SK_P; ++p) load_ab(p, p);
+  for (int p = 0; p < NS; ++p) load_ab(p, p);
 
   NarrowEpi<MT> epi;
   epi.prefetch(a, M, m0, n0);
@@ -129,19 +129,19 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
   if constexpr (ONESHOT) {
 #pragma unroll
-    for (int g = 0; g < SK_P; ++g) {
+    for (int g = 0; g < NS; ++g) {
       const bf16x8 b = (g < my_steps) ? breg[g] : zero8;
 #pragma unroll
       for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
     }
   } else {
-    for (int t0 = 0; t0 < my_steps; t0 += SK_P) {
+    for (int t0 = 0; t0 < my_steps; t0 += NS) {
 #pragma unroll
-      for (int g = 0; g < SK_P; ++g) {
+      for (int g = 0; g < NS; ++g) {
         const bf16x8 b = (t0 + g < my_steps) ? breg[g] : zero8;
 #pragma unroll
         for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
-        load_ab(t0 + g + SK_P, g);
+        load_ab(t0 + g + NS, g);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -158,18 +158,21 @@ bool narrow_supported(const GemmArgs& a) {
 
 hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   if (!narrow_supported(a)) return hipErrorInvalidValue;
-  const bool oneshot = (a.K / 32 + 3) / 4 <= SK_P;
+  const int steps = (a.K / 32 + 3) / 4;                    // 32-k steps of the busiest wave
   // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
   // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
-#define FARD_NR(MTV)                                                                  \
-  do {                                                                                \
-    const dim3 grid(a.N / 16, (a.M + 16 * MTV - 1) / (16 * MTV));                     \
-    if (oneshot) gemm_narrow_kernel<MTV, true><<<grid, 256, 0, s>>>(a);               \
-    else gemm_narrow_kernel<MTV, false><<<grid, 256, 0, s>>>(a);                      \
-  } while (0)
-  if (a.M <= 16) FARD_NR(1);
-  else if (a.M <= 32 || a.M > 64) FARD_NR(2);
-  else FARD_NR(4);
+#define FARD_NR(MTV, NSV, ONE)                                                        \
+  gemm_narrow_kernel<MTV, NSV, ONE><<<dim3(a.N / 16, (a.M + 16 * MTV - 1) / (16 * MTV)), 256, 0, s>>>(a)
+  if (a.M <= 16) {
+    if (steps <= 8) FARD_NR(1, 8, true);
+    else if (steps <= 16) FARD_NR(1, 16, true);
+    else FARD_NR(1, 8, false);
+  } else {
+    if (steps <= 8) FARD_NR(2, 8, true);
+    else if (steps <= 12) FARD_NR(2, 12, true);
+    else if (steps <= 16) FARD_NR(2, 16, true);
+    else FARD_NR(2, 8, false);
+  }
 #undef FARD_NR
   return hipGetLastError();
 }
