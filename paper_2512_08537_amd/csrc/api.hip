@@ -400,6 +400,9 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
   if (M <= 64 && K <= 2048 && N <= 8192 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
   // a few hundred rows against a small square-ish matrix: still ahead of the split-K kernels (measured)
   if (M <= 640 && K <= 1536 && N <= 1536 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
+  // ... or a wide one with a store epilogue, through 64-column workgroups
+  if (M <= 640 && K <= 1024 && N <= 8192 && N % 64 == 0 && (epi == EPI_STORE || epi == EPI_STORE_F32) && narrow_supported(a))
+    return launch_gemm_narrow(c->stream, a);
   return launch_gemm_bf16(c->stream, a);
 }
 

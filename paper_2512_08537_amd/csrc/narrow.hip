@@ -8,8 +8,9 @@
 // accumulator register e is row 4 (l / 16) + e); the 4 waves interleave the 32-k steps.  Weight and
 // activation fragments go straight from memory into MFMA operand registers -- the 16-column B fragment is
 // two 256-byte halves of the packed 32-column fragments -- so a wave's first NS steps are one memory
-// round trip with no LDS staging and no barrier before the MFMAs.  MT: 16-row tiles per workgroup (1 or 2);
-// blockIdx.y walks the row slabs.
+// round trip with no LDS staging and no barrier before the MFMAs.  A workgroup owns MT x NT tiles of 16 x 16
+// (NT > 1 when many row slabs would otherwise re-read the activations too often); blockIdx.y walks the
+// row slabs.
 //
 // Measured alternatives that lost and are not kept: 32-column tiles with K split over workgroups and fp32
 // atomics (the atomics cost 1-2 us per launch and grow with the split count); folding the preceding
@@ -21,84 +22,92 @@ namespace fard {
 
 namespace {
 
-constexpr int NR_LDT = 20;              // floats per row of a partial tile in LDS
-
-// Epilogue of the narrow-tile kernels: thread -> (row, 2 columns) of the [16 MT, 16] tile.  The operands
-// that do not depend on the product (gate, old value of a read-modify-write target, bias) are requested by
-// prefetch() at kernel start; finish() adds the 4 waves' partial tiles through LDS and writes the result.
-template <int MT>
+// Epilogue of the narrow-tile kernels over the [16 MT, 16 NT] tile of a workgroup: a thread keeps one group of
+// 4 columns and walks the rows.  The operands that do not depend on the product (gate, old value of a
+// read-modify-write target, bias) are requested by prefetch() at kernel start; finish() adds the 4 waves'
+// partial tiles through LDS and writes 8-16 bytes per thread.
+template <int MT, int NT>
 struct NarrowEpi {
-  static constexpr int EP = (16 * MT + 31) / 32;           // passes of 32 rows
-  float2 gate[EP], old[EP], bias2;
+  static constexpr int CG = 4 * NT;                        // 4-column groups per row
+  static constexpr int RPP = 256 / CG;                     // rows per pass
+  static constexpr int EP = (16 * MT + RPP - 1) / RPP;     // passes
+  static constexpr int LDT = 16 * NT + 4;                  // floats per row of a partial tile in LDS
+  f32x4 gate[EP], old[EP], bias4;
   int er, ec;
   __device__ __forceinline__ void prefetch(const GemmArgs& a, int M, int m0, int n0) {
-    er = threadIdx.x >> 3;
-    ec = (threadIdx.x & 7) * 2;
-    bias2 = float2{0.f, 0.f};
+    er = threadIdx.x / CG;
+    ec = (threadIdx.x % CG) * 4;
+    bias4 = f32x4{0.f, 0.f, 0.f, 0.f};
     const bool rmw = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
 #pragma unroll
     for (int i = 0; i < EP; ++i) {
-      int r = m0 + er + 32 * i;
+      int r = m0 + er + RPP * i;
       r = r < M ? r : M - 1;
-      gate[i] = float2{1.f, 1.f};
-      old[i] = float2{0.f, 0.f};
-      if (a.epi == EPI_GATE_RESID) gate[i] = *(const float2*)(a.gate + (size_t)r * a.ldg + n0 + ec);
-      if (rmw) old[i] = *(const float2*)((const float*)a.out + (size_t)r * a.ldo + n0 + ec);
+      gate[i] = f32x4{1.f, 1.f, 1.f, 1.f};
+      old[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (a.epi == EPI_GATE_RESID) gate[i] = *(const f32x4*)(a.gate + (size_t)r * a.ldg + n0 + ec);
+      if (rmw) old[i] = *(const f32x4*)((const float*)a.out + (size_t)r * a.ldo + n0 + ec);
     }
-    if (a.bias != nullptr) bias2 = *(const float2*)(a.bias + n0 + ec);
+    if (a.bias != nullptr) bias4 = *(const f32x4*)(a.bias + n0 + ec);
   }
-  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT], float* red, int M, int m0, int n0) {
+  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT][NT], float* red, int M, int m0,
+                                         int n0) {
     const int lane = threadIdx.x & 63, kw = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        red[(kw * 16 * MT + 16 * i + 4 * (lane >> 4) + e) * NR_LDT + (lane & 15)] = acc[i][e];
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          red[(kw * 16 * MT + 16 * i + 4 * (lane >> 4) + e) * LDT + 16 * j + (lane & 15)] = acc[i][j][e];
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < EP; ++i) {
-      const int row = er + 32 * i;
+      const int row = er + RPP * i;
       if (m0 + row >= M || row >= 16 * MT) continue;
-      float2 v = bias2;
+      f32x4 v = bias4;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float2 pv = *(const float2*)(red + (k * 16 * MT + row) * NR_LDT + ec);
-        v.x += pv.x;
-        v.y += pv.y;
-      }
+      for (int k = 0; k < 4; ++k) v += *(const f32x4*)(red + (k * 16 * MT + row) * LDT + ec);
       const size_t o = (size_t)(m0 + row) * a.ldo + n0 + ec;
       if (a.epi == EPI_STORE) {
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        bf16x2 t;
-        t[0] = (bf16)apply_act(v.x, a.act);
-        t[1] = (bf16)apply_act(v.y, a.act);
-        *(bf16x2*)((bf16*)a.out + o) = t;
+        bf16x4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = (bf16)apply_act(v[e], a.act);
+        *(bf16x4*)((bf16*)a.out + o) = t;
       } else if (a.epi == EPI_STORE_F32) {
-        *(float2*)((float*)a.out + o) = float2{apply_act(v.x, a.act), apply_act(v.y, a.act)};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], a.act);
+        *(f32x4*)((float*)a.out + o) = v;
       } else {
-        *(float2*)((float*)a.out + o) = float2{old[i].x + gate[i].x * v.x, old[i].y + gate[i].y * v.y};
+        *(f32x4*)((float*)a.out + o) = old[i] + gate[i] * v;
       }
     }
   }
 };
 
-// NS: k-steps per operand a wave keeps in flight (its whole K range when ONESHOT).
-template <int MT, int NS, bool ONESHOT>
+// MT x NT: 16x16 output tiles of the workgroup (rows x columns).  NS: k-steps per operand a wave keeps in
+// flight (its whole K range when ONESHOT).
+template <int MT, int NT, int NS, bool ONESHOT>
 __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
-  __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * NR_LDT];
+  using Epi = NarrowEpi<MT, NT>;
+  __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * Epi::LDT];
   const int M = eff_rows(a.M, a.m_dev);
   const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
   if (m0 >= M) return;
-  const int c16 = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
   const int kb16 = a.K >> 4, kb32 = a.K >> 5;
   const int my_steps = (kb32 - kw + 3) >> 2;               // steps kw, kw + 4, ... (may be 0)
-  const int n0 = c16 * 16;
+  const int n0 = blockIdx.x * 16 * NT;
 
   // packed B: fragment (nb, kb16 index) holds lane L = 32 * (k / 8 % 2) + n % 32
   const int kg = lane >> 4;                                // k group of this lane inside a 32-k step
-  const bf16x8* __restrict__ bbase = (const bf16x8*)a.W + (size_t)(c16 >> 1) * kb16 * 64 + (kg >> 1) * 64 +
-                                     (kg & 1) * 32 + (c16 & 1) * 16 + (lane & 15);
+  const bf16x8* __restrict__ bbase[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    const int c16 = blockIdx.x * NT + j;
+    bbase[j] = (const bf16x8*)a.W + (size_t)(c16 >> 1) * kb16 * 64 + (kg >> 1) * 64 + (kg & 1) * 32 + (c16 & 1) * 16 +
+               (lane & 15);
+  }
   const bf16* __restrict__ abase[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
@@ -106,41 +115,46 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
     r = r < M ? r : M - 1;
     abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
   }
-  bf16x8 breg[NS], areg[NS][MT];
+  bf16x8 breg[NS][NT], areg[NS][MT];
   auto load_ab = [&](int t, int p) {
     int s = kw + 4 * t;
     s = s < kb32 ? s : kb32 - 1;                           // past the end: a re-read, zeroed at use
-    breg[p] = bbase[(size_t)s * 128];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) breg[p][j] = bbase[j][(size_t)s * 128];
 #pragma unroll
     for (int i = 0; i < MT; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 32);
   };
 #pragma unroll
   for (int p = 0; p < NS; ++p) load_ab(p, p);
 
-  NarrowEpi<MT> epi;
+  Epi epi;
   epi.prefetch(a, M, m0, n0);
   __builtin_amdgcn_sched_barrier(0);
 
-  f32x4 acc[MT];
+  f32x4 acc[MT][NT];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   bf16x8 zero8;
 #pragma unroll
   for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
+  auto step = [&](int g, bool live) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const bf16x8 af = live ? areg[g][i] : zero8;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, breg[g][j], acc[i][j], 0, 0, 0);
+    }
+  };
   if constexpr (ONESHOT) {
 #pragma unroll
-    for (int g = 0; g < NS; ++g) {
-      const bf16x8 b = (g < my_steps) ? breg[g] : zero8;
-#pragma unroll
-      for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
-    }
+    for (int g = 0; g < NS; ++g) step(g, g < my_steps);
   } else {
     for (int t0 = 0; t0 < my_steps; t0 += NS) {
 #pragma unroll
       for (int g = 0; g < NS; ++g) {
-        const bf16x8 b = (t0 + g < my_steps) ? breg[g] : zero8;
-#pragma unroll
-        for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(areg[g][i], b, acc[i], 0, 0, 0);
+        step(g, t0 + g < my_steps);
         load_ab(t0 + g + NS, g);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -161,17 +175,24 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   const int steps = (a.K / 32 + 3) / 4;                    // 32-k steps of the busiest wave
   // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
   // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
-#define FARD_NR(MTV, NSV, ONE)                                                        \
-  gemm_narrow_kernel<MTV, NSV, ONE><<<dim3(a.N / 16, (a.M + 16 * MTV - 1) / (16 * MTV)), 256, 0, s>>>(a)
+#define FARD_NR(MTV, NTV, NSV, ONE)                                                                        \
+  gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV)), 256, 0, s>>>(a)
+  const bool store = (a.epi == EPI_STORE || a.epi == EPI_STORE_F32);
   if (a.M <= 16) {
-    if (steps <= 8) FARD_NR(1, 8, true);
-    else if (steps <= 16) FARD_NR(1, 16, true);
-    else FARD_NR(1, 8, false);
+    if (steps <= 8) FARD_NR(1, 1, 8, true);
+    else if (steps <= 16) FARD_NR(1, 1, 16, true);
+    else FARD_NR(1, 1, 8, false);
+  } else if (a.M > 64 && a.N >= 2048 && steps <= 8 && store && a.N % 64 == 0) {
+    // many row slabs against a wide matrix: 64 columns per workgroup quarter the re-reads of the activations
+    FARD_NR(2, 4, 8, true);
+  } else if (a.M > 64 && a.N >= 2048 && steps <= 12) {
+    if (steps <= 8) FARD_NR(2, 2, 8, true);
+    else FARD_NR(2, 2, 12, true);
   } else {
-    if (steps <= 8) FARD_NR(2, 8, true);
-    else if (steps <= 12) FARD_NR(2, 12, true);
-    else if (steps <= 16) FARD_NR(2, 16, true);
-    else FARD_NR(2, 8, false);
+    if (steps <= 8) FARD_NR(2, 1, 8, true);
+    else if (steps <= 12) FARD_NR(2, 1, 12, true);
+    else if (steps <= 16) FARD_NR(2, 1, 16, true);
+    else FARD_NR(2, 1, 8, false);
   }
 #undef FARD_NR
   return hipGetLastError();

@@ -54,6 +54,8 @@ _NARROW_CASES = [
     (32, 1024, 1024, 0), (32, 1024, 1024, 3), (13, 64, 32, 1), (16, 1280, 96, 2), (17, 4096, 1024, 2),
     (64, 1024, 160, 3), (49, 1536, 64, 0), (1, 192, 32, 1), (288, 1024, 1024, 2), (130, 512, 96, 3),
     (97, 256, 64, 0), (32, 1024, 4096, 0), (5, 2048, 64, 2),
+    # many row slabs against wide matrices: 64- and 32-column workgroups
+    (288, 1024, 4096, 0), (130, 1280, 2048, 3), (97, 512, 2112, 1), (100, 1024, 2080, 0), (70, 1536, 2048, 2),
 ]
 
 
