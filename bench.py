@@ -112,7 +112,7 @@ def main():
     g_tflops = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
     peak = PEAK_BF16_TFLOPS if rc.dtype == 1 else PEAK_FP32_TFLOPS
     roofline = {"bound": "mfma" if rc.dtype == 1 else "alu",
-                "kernel": "GEMM kernels of the round (gemm_narrow_kernel, gemm_bf16_res_kernel, gemm_bf16_kernel)",
+                "kernel": "GEMM kernels of the round (gemm_narrow_kernel, gemm_bf16_kernel, gemm_bf16_res_kernel)",
                 "achieved": round(g_tflops, 3), "peak": peak, "unit": "TFLOP/s", "frac": round(g_tflops / peak, 5),
                 "traffic": hbm_traffic_per_launch(args.config), "launches_per_step": g["launches"] / args.steps,
                 "avg_launch_us": round(g_avg_us, 3),

@@ -45,7 +45,7 @@ def entropy():
         us = e0.elapsed_time(e1) * 1e3 / iters
         nbytes = B * K * L * 2 + B * K * 9
         gbs = nbytes / us / 1e3
-        print(json.dumps({"kernel": "entropy_prefilter_kernel<bf16>", "rows": B * K, "len": L, "us_per_launch": round(us, 2),
+        print(json.dumps({"kernel": "entropy_prefilter entry point, bf16 (small shapes: host-loop bound, see the kernel trace)", "rows": B * K, "len": L, "us_per_launch": round(us, 2),
                           "algorithmic_bytes": nbytes, "achieved_GBs": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4),
                           "n_surv": int(out[4].cpu()[0])}), flush=True)
     ctx.close()
