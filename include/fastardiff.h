@@ -195,6 +195,34 @@ int spec_round(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id,
                int32_t B, float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q,
                int32_t* n_accept, float* log_ratio, float* mu_p);
 
+/* Alg. 1 Step 5 (S3 item 3) and the token a round ends with, for every sample (device memory throughout):
+ *   n_accept[b] < n_keep[b]: draft n_accept[b]+1 was rejected; the token is drawn from the residual
+ *     max(0, Sigma p - q) by acceptance-rejection: proposal j = mu_p[b, n] + sigma_p * eps_res[b, j, :] is taken
+ *     when u_res[b, j] <= max(0, 1 - q(x_j) / (Sigma p(x_j))); J proposals at most, the last one is taken
+ *     if none passes (tries[b] = J);
+ *   otherwise: the target's own sample of row n_keep[b] under the shared noise,
+ *     mu_p[b, n_keep] + sigma_p * eps[S, b, n_keep, :] (tries[b] = 0).
+ *   mu_p fp32 [B,K+1,D], mu_q fp32 [B,K,D], eps fp32 [S+1,B,K+1,D] (the round's shared noise), eps_res fp32
+ *   [B,J,D], u_res fp32 [B,J]; x_next fp32 [B,D], tries int32 [B]. */
+int spec_resample(fard_ctx* ctx, const float* mu_p, const float* mu_q, const float* eps,
+                  const int32_t* n_accept, const int32_t* n_keep, const float* eps_res, const float* u_res,
+                  float log_sigma_factor, float sigma_p, float sigma_q, int32_t B, int32_t J, float* x_next,
+                  int32_t* tries);
+
+/* R rounds of Alg. 1 in a row (Steps 1-5) without a host synchronisation: spec_round, spec_resample, cache
+ * commit, and one single-row draft forward for the samples that accepted all K drafts (their draft model has
+ * not read draft K yet); the closing token of a round is the pending token of the next.
+ *   x_first fp32 [B,D] / first_id int32 [B] or NULL: the pending row of round 0 (as in spec_draft)
+ *   eps fp32 [R][S+1,B,K+1,D], r fp32 [R][B,K], eps_res fp32 [R][B,J,D], u_res fp32 [R][B,J]: pre-drawn
+ *   tokens fp32 [B, R*(K+1), D]: per sample the accepted drafts and the closing token of every round, in
+ *     order; n_tokens int32 [B] their count.  H fp32 [R,B,K], n_keep, n_accept, tries int32 [R,B]: per round.
+ * All samples stay active for all R rounds.  Errors: FARD_ECAPACITY unless cache_len + R*(K+1) <= max_ctx
+ * (and the learned position table) for both models: the host tracks only upper bounds of the lengths. */
+int spec_generate(fard_ctx* ctx, const float* x_first, const int32_t* first_id, const float* eps,
+                  const float* r, const float* eps_res, const float* u_res, float tau, float log_sigma_factor,
+                  float sigma_p, float sigma_q, int32_t B, int32_t R, int32_t J, float* tokens,
+                  int32_t* n_tokens, float* H, int32_t* n_keep, int32_t* n_accept, int32_t* tries);
+
 /* out = act(A W + b) through the library's GEMM kernel, for tests and kernel timing.
  *   A storage type [M,K]; W storage type [K,N] row-major (re-laid on every call); bias fp32 [N] or
  *   NULL; act: 0 none, 1 erf-GELU, 2 SiLU; out storage type [M,N].  bf16: K % 64 == 0, N % 32 == 0. */

@@ -64,6 +64,9 @@ _SIGS = {
     "spec_verify": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp],
     "spec_accept": [_vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _vp, _vp, _vp],
     "spec_round": [_vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
+    "spec_resample": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _i32, _vp, _vp],
+    "spec_generate": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
+                      _vp],
     "spec_gemm": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
     "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp],
     "spec_profile_enable": [_vp, _i32],
@@ -299,6 +302,35 @@ class Context:
                                  float(log_sigma), float(sigma_p), float(sigma_q), B, _ptr(o["H"]), _ptr(o["keep"]),
                                  _ptr(o["n_keep"]), _ptr(o["x_draft"]), _ptr(o["mu_q"]), _ptr(o["n_accept"]),
                                  _ptr(o["log_ratio"]), _ptr(o["mu_p"])))
+        return o
+
+    def _sigmas(self, sigma_p, sigma_q):
+        s = self.rc.head.sigma_last * self.rc.head.temperature
+        return float(s if sigma_p is None else sigma_p), float(s if sigma_q is None else sigma_q)
+
+    def spec_resample(self, mu_p, mu_q, eps, n_accept, n_keep, eps_res, u_res, log_sigma=0.0, sigma_p=None, sigma_q=None):
+        B, J = u_res.shape
+        D = mu_p.shape[-1]
+        sp, sq = self._sigmas(sigma_p, sigma_q)
+        x_next = self.empty((B, D), self.torch.float32)
+        tries = self.empty((B,), self.torch.int32)
+        self._chk(lib.spec_resample(self.h, _ptr(mu_p), _ptr(mu_q), _ptr(eps), _ptr(n_accept), _ptr(n_keep), _ptr(eps_res),
+                                    _ptr(u_res), float(log_sigma), sp, sq, B, J, _ptr(x_next), _ptr(tries)))
+        return x_next, tries
+
+    def spec_generate(self, x_first, eps, r, eps_res, u_res, tau, first_id=None, log_sigma=0.0, sigma_p=None, sigma_q=None):
+        """eps [R,S+1,B,K+1,D], r [R,B,K], eps_res [R,B,J,D], u_res [R,B,J] (device fp32)."""
+        t = self.torch
+        R, B, K = r.shape
+        J = u_res.shape[2]
+        D = x_first.shape[1]
+        sp, sq = self._sigmas(sigma_p, sigma_q)
+        o = dict(tokens=t.zeros((B, R * (K + 1), D), dtype=t.float32, device=self.dev),
+                 n_tokens=self.empty((B,), t.int32), H=self.empty((R, B, K), t.float32),
+                 n_keep=self.empty((R, B), t.int32), n_accept=self.empty((R, B), t.int32), tries=self.empty((R, B), t.int32))
+        self._chk(lib.spec_generate(self.h, _ptr(x_first), _ptr(first_id), _ptr(eps), _ptr(r), _ptr(eps_res), _ptr(u_res), float(tau),
+                                    float(log_sigma), sp, sq, B, R, J, _ptr(o["tokens"]), _ptr(o["n_tokens"]), _ptr(o["H"]),
+                                    _ptr(o["n_keep"]), _ptr(o["n_accept"]), _ptr(o["tries"])))
         return o
 
     def spec_gemm(self, A, W, bias=None, act=0):

@@ -125,6 +125,10 @@ struct fard_ctx {
   RowMaps maps{};
   int *aux_row = nullptr, *row_ids = nullptr;
   float* x_scratch = nullptr;
+  // multi-round generation: outputs of the current round, the closing token, catch-up rows
+  float *g_x = nullptr, *g_mu_q = nullptr, *g_mu_p = nullptr, *g_lr = nullptr, *g_next = nullptr, *g_cu_x = nullptr;
+  int* g_cu_nq = nullptr;
+  uint8_t* g_keep = nullptr;
   uint8_t* acc_tmp = nullptr;
   float *cz = nullptr, *hh = nullptr, *mod = nullptr, *xt = nullptr;
   void *sc = nullptr, *a1 = nullptr, *a2 = nullptr;
@@ -512,6 +516,15 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<int>(c, &c->emap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->omap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->ent_blk, ENT_MAX_BLOCKS))) return rc;
+  const size_t bk = (size_t)g.max_batch * g.K;
+  if ((rc = dalloc<float>(c, &c->g_x, bk * D))) return rc;
+  if ((rc = dalloc<float>(c, &c->g_mu_q, bk * D))) return rc;
+  if ((rc = dalloc<float>(c, &c->g_mu_p, (size_t)g.max_batch * (g.K + 1) * D))) return rc;
+  if ((rc = dalloc<float>(c, &c->g_lr, bk))) return rc;
+  if ((rc = dalloc<float>(c, &c->g_next, (size_t)g.max_batch * D))) return rc;
+  if ((rc = dalloc<float>(c, &c->g_cu_x, (size_t)g.max_batch * D))) return rc;
+  if ((rc = dalloc<int>(c, &c->g_cu_nq, g.max_batch))) return rc;
+  if ((rc = dalloc<uint8_t>(c, &c->g_keep, bk))) return rc;
   return FARD_OK;
 }
 
@@ -945,6 +958,66 @@ int spec_round(fard_ctx* c, const float* x_pending, const int32_t* pending_id, c
                    log_ratio, mu_p, nullptr);
   if (rc) return rc;
   return spec_kv_commit(c, -1, n_accept, B);
+}
+
+int spec_resample(fard_ctx* c, const float* mu_p, const float* mu_q, const float* eps, const int32_t* n_accept,
+                  const int32_t* n_keep, const float* eps_res, const float* u_res, float log_sigma_factor, float sigma_p,
+                  float sigma_q, int32_t B, int32_t J, float* x_next, int32_t* tries) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (J < 1) return fail(c, FARD_EINVAL, "J >= 1 required");
+  if (!(sigma_p > 0.f) || !(sigma_q > 0.f)) return fail(c, FARD_EINVAL, "sigma_p, sigma_q > 0 required");
+  if (B == 0) return FARD_OK;
+  if (!mu_p || !mu_q || !eps || !n_accept || !n_keep || !eps_res || !u_res || !x_next || !tries)
+    return fail(c, FARD_EINVAL, "null argument");
+  const int K = c->cfg.K, D = c->cfg.target.d_latent, S = c->cfg.head.n_steps;
+  const float* eps_last = eps + (size_t)S * B * (K + 1) * D;
+  Bracket br(c, CLS_OTHER);
+  HIPCHK(c, launch_round_finish(c->stream, mu_p, mu_q, eps_last, n_accept, n_keep, eps_res, u_res, nullptr, B, K, D, J,
+                                log_sigma_factor, sigma_p, sigma_q, x_next, tries, nullptr, 0, nullptr));
+  return FARD_OK;
+}
+
+int spec_generate(fard_ctx* c, const float* x_first, const int32_t* first_id, const float* eps, const float* r,
+                  const float* eps_res, const float* u_res, float tau, float log_sigma_factor, float sigma_p, float sigma_q,
+                  int32_t B, int32_t R, int32_t J, float* tokens, int32_t* n_tokens, float* H, int32_t* n_keep,
+                  int32_t* n_accept, int32_t* tries) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (R < 0 || J < 1) return fail(c, FARD_EINVAL, "R >= 0 and J >= 1 required");
+  if (B == 0 || R == 0) return FARD_OK;
+  if (!x_first || !eps || !r || !eps_res || !u_res || !tokens || !n_tokens || !H || !n_keep || !n_accept || !tries)
+    return fail(c, FARD_EINVAL, "null argument");
+  const int K = c->cfg.K, D = c->cfg.target.d_latent, S = c->cfg.head.n_steps;
+  // the host only knows upper bounds of the cache lengths: every round may add K + 1 positions
+  for (int w = 0; w < 2; ++w) {
+    const Model& m = c->mdl[w];
+    const long need = (long)m.len_hi + (long)R * (K + 1);
+    if (need > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "cache_len + R * (K + 1) exceeds max_ctx");
+    if (m.c.pos == FARD_POS_LEARNED && need > m.c.max_pos) return fail(c, FARD_ECAPACITY, "positions beyond the learned table");
+  }
+  hipStream_t s = c->stream;
+  const size_t eps_round = (size_t)(S + 1) * B * (K + 1) * D;
+  const int tok_cap = R * (K + 1);
+  HIPCHK(c, launch_fill_i32(s, n_tokens, 0, B));
+  uint8_t* keep = c->g_keep;
+  for (int t = 0; t < R; ++t) {
+    const float* eps_t = eps + (size_t)t * eps_round;
+    int rc = spec_round(c, t == 0 ? x_first : c->g_next, t == 0 ? first_id : nullptr, eps_t, r + (size_t)t * B * K, tau,
+                        log_sigma_factor, sigma_p, sigma_q, B, H + (size_t)t * B * K, keep, n_keep + (size_t)t * B, c->g_x,
+                        c->g_mu_q, n_accept + (size_t)t * B, c->g_lr, c->g_mu_p);
+    if (rc) return rc;
+    { Bracket br(c, CLS_OTHER);
+      HIPCHK(c, launch_round_finish(s, c->g_mu_p, c->g_mu_q, eps_t + (size_t)S * B * (K + 1) * D, n_accept + (size_t)t * B,
+                                    n_keep + (size_t)t * B, eps_res + (size_t)t * B * J * D, u_res + (size_t)t * B * J, c->g_x,
+                                    B, K, D, J, log_sigma_factor, sigma_p, sigma_q, c->g_next, tries + (size_t)t * B, tokens,
+                                    tok_cap, n_tokens));
+      // a draft that accepted all K drafts has not read draft K yet
+      HIPCHK(c, launch_catchup_pack(s, n_accept + (size_t)t * B, c->g_x, B, K, D, c->g_cu_nq, c->g_cu_x)); }
+    rc = spec_forward(c, FARD_DRAFT, c->g_cu_x, nullptr, c->g_cu_nq, 1, B, B, 1, c->z, nullptr, nullptr);
+    if (rc) return rc;
+  }
+  return FARD_OK;
 }
 
 int spec_gemm(fard_ctx* c, const void* A, const void* W, const float* bias, int32_t M, int32_t K, int32_t N, int32_t act, void* out) {

@@ -139,6 +139,16 @@ hipError_t launch_accept(hipStream_t s, const float* x, const float* mu_p, const
                          float sigma_q, int B, int K, int D, int* n_accept, float* log_ratio,
                          uint8_t* acc);
 
+// The token every sample's round ends with (Alg. 1 Step 5; bonus row when all kept drafts were accepted), one
+// wave per sample; optionally appends accepted drafts + that token to tokens[b, n_tokens[b] ...] (capacity tok_cap).
+hipError_t launch_round_finish(hipStream_t s, const float* mu_p, const float* mu_q, const float* eps_last,
+                               const int* n_accept, const int* n_keep, const float* eps_res, const float* u_res,
+                               const float* x_draft, int B, int K, int D, int J, float log_sigma, float sigma_p,
+                               float sigma_q, float* x_next, int* tries, float* tokens, int tok_cap, int* n_tokens);
+// nq[b] = (n_accept[b] == K); x_pack = draft K of those samples, packed in sample order.
+hipError_t launch_catchup_pack(hipStream_t s, const int* n_accept, const float* x_draft, int B, int K, int D,
+                               int* nq, float* x_pack);
+
 // cache_len[b] += base + (n ? n[b] : 0)
 hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int v, int n);

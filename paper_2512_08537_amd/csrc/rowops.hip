@@ -591,6 +591,74 @@ __global__ __launch_bounds__(256) void entropy_step_kernel(const float* __restri
   if (tid == 0) *n_act = s_carry;
 }
 
+// ================================================================== end of a round (Alg. 1 Step 5)
+// One wave per sample.  n_accept < n_keep: acceptance-rejection from the residual max(0, Sigma p - q) with
+// proposals mu_p[n] + sigma_p eps_res[j], accepted when u_res[j] <= max(0, 1 - exp(-ln rho)); the last proposal
+// is taken if none of the J is accepted.  Otherwise the target's own sample of row n_keep under the shared noise.
+// Optionally appends the accepted drafts and the closing token to the sample's token list.
+__global__ __launch_bounds__(64) void round_finish_kernel(const float* __restrict__ mu_p, const float* __restrict__ mu_q,
+                                                          const float* __restrict__ eps_last,
+                                                          const int* __restrict__ n_accept, const int* __restrict__ n_keep,
+                                                          const float* __restrict__ eps_res, const float* __restrict__ u_res,
+                                                          const float* __restrict__ x_draft, int K, int D, int J,
+                                                          float log_sigma, float sigma_p, float sigma_q,
+                                                          float* __restrict__ x_next, int* __restrict__ tries,
+                                                          float* __restrict__ tokens, int tok_cap,
+                                                          int* __restrict__ n_tokens) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int n = n_accept[b], nk = n_keep[b];
+  const bool on = lane < D;
+  float xn = 0.f;
+  int t = 0;
+  if (n < nk) {
+    const float mp = on ? mu_p[((size_t)b * (K + 1) + n) * D + lane] : 0.f;
+    const float mq = on ? mu_q[((size_t)b * K + n) * D + lane] : 0.f;
+    const float cst = log_sigma + (float)D * (logf(sigma_q) - logf(sigma_p));
+    const float ip = 1.0f / (2.0f * sigma_p * sigma_p), iq = 1.0f / (2.0f * sigma_q * sigma_q);
+    for (int j = 0; j < J; ++j) {
+      const float e = on ? eps_res[((size_t)b * J + j) * D + lane] : 0.f;
+      xn = mp + sigma_p * e;
+      const float a = xn - mp, c = xn - mq;
+      const float dp = wave_sum(on ? a * a : 0.f), dq = wave_sum(on ? c * c : 0.f);
+      const float lr = cst - dp * ip + dq * iq;
+      const float alpha = fmaxf(0.f, 1.0f - expf(-lr));
+      t = j + 1;
+      if (u_res[(size_t)b * J + j] <= alpha) break;        // uniform across the wave
+    }
+  } else {
+    const size_t o = ((size_t)b * (K + 1) + nk) * D + lane;
+    xn = on ? mu_p[o] + sigma_p * eps_last[o] : 0.f;
+  }
+  if (on) x_next[(size_t)b * D + lane] = xn;
+  if (lane == 0) tries[b] = t;
+  if (tokens != nullptr) {
+    const int pos = n_tokens[b];
+    for (int i = 0; i < n; ++i)
+      if (on && pos + i < tok_cap) tokens[((size_t)b * tok_cap + pos + i) * D + lane] = x_draft[((size_t)b * K + i) * D + lane];
+    if (on && pos + n < tok_cap) tokens[((size_t)b * tok_cap + pos + n) * D + lane] = xn;
+    if (lane == 0) n_tokens[b] = pos + n + 1;
+  }
+}
+
+// Rows that the draft still has to read before the next round: draft K of the samples that accepted all K.
+// One workgroup; nq[b] = (n_accept[b] == K), x_pack = those samples' last drafts in sample order.
+__global__ __launch_bounds__(256) void catchup_pack_kernel(const int* __restrict__ n_accept, const float* __restrict__ x_draft,
+                                                           int B, int K, int D, int* __restrict__ nq,
+                                                           float* __restrict__ x_pack) {
+  __shared__ int s_scan[256];
+  int carry = 0;
+  for (int base = 0; base < B; base += 256) {
+    const int b = base + threadIdx.x;
+    const int f = (b < B && n_accept[b] == K) ? 1 : 0;
+    if (b < B) nq[b] = f;
+    int total;
+    const int r = carry + block_excl_scan(f, s_scan, &total);
+    if (f)
+      for (int c = 0; c < D; ++c) x_pack[(size_t)r * D + c] = x_draft[((size_t)b * K + K - 1) * D + c];
+    carry += total;
+  }
+}
+
 // ================================================================== head pieces
 // First sampler step: hh = x_t W_in + b_in, x_t kept, and the conditioning silu(cz + temb_k) of all S steps
 // (step k in rows [k n, (k + 1) n) of sc), so that one GEMM produces the modulations of every step.
@@ -960,6 +1028,24 @@ hipError_t launch_head_out(hipStream_t s, int is_bf16, const HeadStepArgs& a) {
     head_out_kernel<bf16><<<a.n, 256, 0, s>>>(a);
   else
     head_out_kernel<float><<<a.n, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_round_finish(hipStream_t s, const float* mu_p, const float* mu_q, const float* eps_last, const int* n_accept,
+                               const int* n_keep, const float* eps_res, const float* u_res, const float* x_draft, int B, int K,
+                               int D, int J, float log_sigma, float sigma_p, float sigma_q, float* x_next, int* tries,
+                               float* tokens, int tok_cap, int* n_tokens) {
+  if (B <= 0) return hipSuccess;
+  if (D > 64 || J < 1) return hipErrorInvalidValue;
+  round_finish_kernel<<<B, 64, 0, s>>>(mu_p, mu_q, eps_last, n_accept, n_keep, eps_res, u_res, x_draft, K, D, J, log_sigma,
+                                       sigma_p, sigma_q, x_next, tries, tokens, tok_cap, n_tokens);
+  return hipGetLastError();
+}
+
+hipError_t launch_catchup_pack(hipStream_t s, const int* n_accept, const float* x_draft, int B, int K, int D, int* nq,
+                               float* x_pack) {
+  if (B <= 0) return hipSuccess;
+  catchup_pack_kernel<<<1, 256, 0, s>>>(n_accept, x_draft, B, K, D, nq, x_pack);
   return hipGetLastError();
 }
 
