@@ -89,8 +89,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
   constexpr int RED_FLOATS = (KW > 1) ? NWN * WM * WN * 16 * 64 : 0;
   constexpr int LDS_BYTES = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
   static_assert(G % P == 0 && G % SPW == 0, "ring depth and steps per wave must be powers of two");
-  __shared__ __attribute__((aligned(16))) char lds_raw[LDS_BYTES];
+  extern __shared__ __attribute__((aligned(16))) char lds_raw[];   // LDS_BYTES, passed at launch
   bf16* lds = (bf16*)lds_raw;
+  (void)LDS_BYTES;
 
   // blockIdx -> (weight panel, m tile): panels are dealt to XCDs, the m tiles of a panel are
   // consecutive slots of that XCD.
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
 
 template <int WM, int WN, int KW, int P, int KC>
 hipError_t launch_cfg(hipStream_t s, const GemmArgs& a, int splits) {
-  const int BN = 32 * WN * (4 / KW), BM = 32 * WM;
+  constexpr int BN = 32 * WN * (4 / KW), BM = 32 * WM;
   const int n_tiles = (a.N + BN - 1) / BN;
   const int m_tiles = (a.M + BM - 1) / BM;
   const int total_chunks = (a.K + KC - 1) / KC;
@@ -263,7 +264,20 @@ hipError_t launch_cfg(hipStream_t s, const GemmArgs& a, int splits) {
   splits = (total_chunks + cps - 1) / cps;
   const int panels = n_tiles * splits;
   const int grid = ((panels + 7) / 8) * 8 * m_tiles;
-  gemm_bf16_kernel<WM, WN, KW, P, KC><<<grid, 256, 0, s>>>(a, n_tiles, m_tiles, splits, cps);
+  // same formula as in the kernel: the activation chunk or the partial sums of the KW wave groups
+  constexpr int LDS_STRIDE = KC + 8;
+  constexpr int RED_FLOATS = (KW > 1) ? (4 / KW) * WM * WN * 16 * 64 : 0;
+  constexpr int LDS_BYTES = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
+  if constexpr (LDS_BYTES > 64 * 1024) {
+    static bool attr_set = false;                          // per template instance
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<WM, WN, KW, P, KC>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+  }
+  gemm_bf16_kernel<WM, WN, KW, P, KC><<<grid, 256, LDS_BYTES, s>>>(a, n_tiles, m_tiles, splits, cps);
   return hipGetLastError();
 }
 
