@@ -212,7 +212,7 @@ int spec_resample(fard_ctx* ctx, const float* mu_p, const float* mu_q, const flo
 /* R rounds of Alg. 1 in a row (Steps 1-5) without a host synchronisation: spec_round, spec_resample, cache
  * commit, and one single-row draft forward for the samples that accepted all K drafts (their draft model has
  * not read draft K yet); the closing token of a round is the pending token of the next.
- *   x_first fp32 [B,D] / first_id int32 [B] or NULL: the pending row of round 0 (as in spec_draft)
+ *   x_first fp32 [B,D] / first_id int32 [B] or NULL: the pending row of the first round (as in spec_draft)
  *   eps fp32 [R][S+1,B,K+1,D], r fp32 [R][B,K], eps_res fp32 [R][B,J,D], u_res fp32 [R][B,J]: pre-drawn
  *   tokens fp32 [B, R*(K+1), D]: per sample the accepted drafts and the closing token of every round, in
  *     order; n_tokens int32 [B] their count.  H fp32 [R,B,K], n_keep, n_accept, tries int32 [R,B]: per round.

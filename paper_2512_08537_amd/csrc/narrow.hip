@@ -90,7 +90,7 @@ struct NarrowEpi {
 template <int MT, int NT, int NS, bool ONESHOT>
 __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   using Epi = NarrowEpi<MT, NT>;
-  __shared__ __attribute__((aligned(16))) float red[4 * 16 * MT * Epi::LDT];
+  extern __shared__ __attribute__((aligned(16))) float red[];   // 4 * 16 * MT * Epi::LDT floats
   const int M = eff_rows(a.M, a.m_dev);
   const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
   if (m0 >= M) return;
@@ -176,16 +176,28 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
   // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
 #define FARD_NR(MTV, NTV, NSV, ONE)                                                                        \
-  gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV)), 256, 0, s>>>(a)
-  const bool store = (a.epi == EPI_STORE || a.epi == EPI_STORE_F32);
+  do {                                                                                                     \
+    constexpr size_t lds = (size_t)4 * 16 * MTV * (16 * NTV + 4) * sizeof(float);                          \
+    if constexpr (lds > 64 * 1024) {                                                                       \
+      static bool attr_set = false;                                                                        \
+      if (!attr_set) {                                                                                     \
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_narrow_kernel<MTV, NTV, NSV, ONE>,            \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+        if (e != hipSuccess) return e;                                                                     \
+        attr_set = true;                                                                                   \
+      }                                                                                                    \
+    }                                                                                                      \
+    gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV)), 256, lds, s>>>(a); \
+  } while (0)
   if (a.M <= 16) {
     if (steps <= 8) FARD_NR(1, 1, 8, true);
     else if (steps <= 16) FARD_NR(1, 1, 16, true);
     else FARD_NR(1, 1, 8, false);
-  } else if (a.M > 64 && a.N >= 2048 && steps <= 8 && store && a.N % 64 == 0) {
-    // many row slabs against a wide matrix: 64 columns per workgroup quarter the re-reads of the activations
+  } else if (a.M > 64 && steps <= 8 && a.N % 64 == 0) {
+    // several row slabs: 64 columns per workgroup quarter the re-reads of the activations (measured best at
+    // 288 rows for N = 1024 .. 4096)
     FARD_NR(2, 4, 8, true);
-  } else if (a.M > 64 && a.N >= 2048 && steps <= 12) {
+  } else if (a.M > 64 && steps <= 12) {
     if (steps <= 8) FARD_NR(2, 2, 8, true);
     else FARD_NR(2, 2, 12, true);
   } else {
