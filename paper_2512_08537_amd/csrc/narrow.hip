@@ -189,21 +189,23 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
     }                                                                                                      \
     gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV)), 256, lds, s>>>(a); \
   } while (0)
-  if (a.M <= 16) {
-    if (steps <= 8) FARD_NR(1, 1, 8, true);
-    else if (steps <= 16) FARD_NR(1, 1, 16, true);
+  if (a.M <= 64) {
+    // a few dozen rows: 16-row workgroups (more of them, half the activation bytes each) measured ahead of
+    // 32-row ones; two column tiles per workgroup once the matrix is wide
+    const bool wide = a.N >= 2048;
+    if (steps <= 8) { if (wide) FARD_NR(1, 2, 8, true); else FARD_NR(1, 1, 8, true); }
+    else if (steps <= 12) { if (wide) FARD_NR(1, 2, 12, true); else FARD_NR(1, 1, 12, true); }
+    else if (steps <= 16) { if (wide) FARD_NR(1, 2, 16, true); else FARD_NR(1, 1, 16, true); }
     else FARD_NR(1, 1, 8, false);
-  } else if (a.M > 64 && steps <= 8 && a.N % 64 == 0) {
+  } else if (steps <= 8 && a.N % 64 == 0) {
     // several row slabs: 64 columns per workgroup quarter the re-reads of the activations (measured best at
     // 288 rows for N = 1024 .. 4096)
     FARD_NR(2, 4, 8, true);
-  } else if (a.M > 64 && steps <= 12) {
+  } else if (steps <= 12) {
     if (steps <= 8) FARD_NR(2, 2, 8, true);
     else FARD_NR(2, 2, 12, true);
   } else {
-    if (steps <= 8) FARD_NR(2, 1, 8, true);
-    else if (steps <= 12) FARD_NR(2, 1, 12, true);
-    else if (steps <= 16) FARD_NR(2, 1, 16, true);
+    if (steps <= 16) FARD_NR(2, 1, 16, true);
     else FARD_NR(2, 1, 8, false);
   }
 #undef FARD_NR
