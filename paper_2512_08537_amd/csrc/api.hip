@@ -129,6 +129,10 @@ struct fard_ctx {
   float *g_x = nullptr, *g_mu_q = nullptr, *g_mu_p = nullptr, *g_lr = nullptr, *g_next = nullptr, *g_cu_x = nullptr;
   int* g_cu_nq = nullptr;
   uint8_t* g_keep = nullptr;
+  // deferred residual update: K-slice partial sums of the last down-projection, folded in by the next norm
+  float* parts = nullptr;
+  int pend_n = 0;
+  size_t pend_stride = 0;
   uint8_t* acc_tmp = nullptr;
   float *cz = nullptr, *hh = nullptr, *mod = nullptr, *xt = nullptr;
   void *sc = nullptr, *a1 = nullptr, *a2 = nullptr;
@@ -469,6 +473,9 @@ int load_head(fard_ctx* c, Loader& ld) {
   return FARD_OK;
 }
 
+constexpr int PART_MAX_SLICES = 8;      // K slices of a deferred residual update
+constexpr int PART_MAX_ROWS = 640;
+
 int alloc_workspace(fard_ctx* c) {
   const fard_round_cfg& g = c->cfg;
   const int M = c->m_max;
@@ -525,6 +532,7 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<float>(c, &c->g_cu_x, (size_t)g.max_batch * D))) return rc;
   if ((rc = dalloc<int>(c, &c->g_cu_nq, g.max_batch))) return rc;
   if ((rc = dalloc<uint8_t>(c, &c->g_keep, bk))) return rc;
+  if (c->bf16 && (rc = dalloc<float>(c, &c->parts, (size_t)PART_MAX_SLICES * std::min(M, PART_MAX_ROWS) * dmax))) return rc;
   return FARD_OK;
 }
 
@@ -539,6 +547,40 @@ KvGeom kv_geom(fard_ctx* c, Model& m, int layer) {
   return g;
 }
 
+// The down-projection with a long K and a few hundred rows at most: K slices of 1024 as separate workgroups of
+// the narrow kernel, each writing its partial sums to its own plane; no atomics.  The planes stay pending until
+// the next norm (or flush_parts) adds them to the residual stream.
+bool parts_eligible(const fard_ctx* c, int M, int N, int K) {
+  return c->bf16 && c->parts != nullptr && M <= PART_MAX_ROWS && K > 2048 && (K + 1023) / 1024 <= PART_MAX_SLICES && N <= 8192 &&
+         N % 32 == 0 && K % 64 == 0;
+}
+
+hipError_t gemm_parts(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
+                      const int* m_dev) {
+  GemmArgs a;
+  a.A = A; a.lda = lda; a.W = W; a.bias = bias; a.out = c->parts; a.ldo = N; a.gate = nullptr; a.ldg = 0;
+  a.M = M; a.N = N; a.K = K; a.m_dev = m_dev; a.act = ACT_NONE; a.epi = EPI_PARTIAL;
+  a.k_slices = (K + 1023) / 1024;
+  a.part_stride = (size_t)M * N;
+  const double fl = 2.0 * M * (double)N * K;
+  const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * N * 4;
+  Bracket br(c, CLS_GEMM, fl, by);
+  hipError_t e = launch_gemm_narrow(c->stream, a);
+  if (e == hipSuccess) {
+    c->pend_n = a.k_slices;
+    c->pend_stride = a.part_stride;
+  }
+  return e;
+}
+
+int flush_parts(fard_ctx* c, int d, int M, const int* m_dev) {
+  if (c->pend_n == 0) return FARD_OK;
+  Bracket br(c, CLS_OTHER);
+  HIPCHK(c, launch_add_parts(c->stream, c->h, c->parts, c->pend_n, c->pend_stride, d, M, m_dev));
+  c->pend_n = 0;
+  return FARD_OK;
+}
+
 // Layers [l0, l1) of one model over the packed rows described by c->maps (h in, h out).
 int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max, const int* m_dev, int ent_layer) {
   Model& m = c->mdl[which];
@@ -548,7 +590,9 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
   for (int l = l0; l < l1; ++l) {
     const LayerW& L = m.L[l];
     { Bracket br(c, CLS_OTHER);
-      HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, nullptr, nullptr, 0, nullptr, c->u)); }
+      HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, nullptr, nullptr, 0, nullptr, c->u,
+                            c->parts, c->pend_n, c->pend_stride, c->h));
+      c->pend_n = 0; }
     HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
     KvGeom kg = kv_geom(c, m, l);
     // learned positions, bf16: the attention kernel stores the new K / V rows itself
@@ -569,7 +613,8 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
     } else {
       HIPCHK(c, gemm(c, c->u, d, L.w1, nullptr, c->ff, F, M, 2 * F, d, m_dev, EPI_SWIGLU, ACT_NONE));
     }
-    HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
+    if (parts_eligible(c, M, d, F)) HIPCHK(c, gemm_parts(c, c->ff, F, L.w2, L.b2, M, d, F, m_dev));
+    else HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
   }
   return FARD_OK;
 }
@@ -581,7 +626,8 @@ int run_final(fard_ctx* c, int which, int n, const int* n_dev, const int* in_map
   const bool up = m.up != nullptr;
   { Bracket br(c, CLS_OTHER);
     HIPCHK(c, launch_norm(c->stream, c->bf16, c->h, t.d_model, n, n_dev, t.norm, t.norm_eps, m.nfg, m.nfb, nullptr, nullptr,
-                          0, in_map, up ? c->ztmp : z_out)); }
+                          0, in_map, up ? c->ztmp : z_out, c->parts, c->pend_n, c->pend_stride, nullptr));
+    c->pend_n = 0; }
   if (up) HIPCHK(c, gemm(c, c->ztmp, t.d_model, m.up, nullptr, z_out, t.d_out, n, t.d_out, t.d_model, n_dev, EPI_STORE, ACT_NONE));
   return FARD_OK;
 }
@@ -796,6 +842,7 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
   int rc;
   if (want_sh) {
     if ((rc = run_layers(c, which, 0, ls, B, M, cap, md, h_attn_out ? ls : 0))) return rc;
+    if ((rc = flush_parts(c, m.c.d_model, M, md))) return rc;
     if (shallow_out) {
       Bracket br(c, CLS_OTHER);
       HIPCHK(c, launch_scatter_rows(s, c->h, shallow_out, nullptr, m.c.d_model, 4, M, md));
@@ -887,6 +934,7 @@ int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, c
                              c->h, d, B, nullptr)); }
     const bool attn_mode = c->cfg.entropy_mode == FARD_ENT_ATTN;
     if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0))) return rc;
+    if ((rc = flush_parts(c, d, B, nullptr))) return rc;
     { Bracket br(c, CLS_ENT, 0, (double)B * d * 4);
       if (!attn_mode) HIPCHK(c, launch_entropy_rows_f32(s, c->h, d, B, d, c->h_row));
       HIPCHK(c, launch_entropy_step(s, attn_mode ? c->ent_heads : nullptr, m.c.n_heads, c->h_row, B, K, i, tau, H, keep, c->alive,

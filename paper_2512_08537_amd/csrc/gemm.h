@@ -11,6 +11,8 @@ enum Epi {
   EPI_RESID = 2,       // out_f32[m, n] += acc + bias[n]                    (residual stream update)
   EPI_GATE_RESID = 3,  // out_f32[m, n] += gate[m, n] * (acc + bias[n])
   EPI_SWIGLU = 4,      // out_T[m, j]   = silu(acc[m, gate col j]) * acc[m, up col j]  (interleaved columns)
+  EPI_PARTIAL = 5,     // out_f32[z][m, n] = partial sum of K slice z (+ bias[n] in slice 0); narrow kernel only:
+                       // the consumer (the next norm) adds the k_slices planes to the residual stream
 };
 
 struct GemmArgs {
@@ -26,6 +28,8 @@ struct GemmArgs {
   const int* m_dev;    // optional device-side row count (rows >= *m_dev are skipped)
   int act;
   int epi;
+  int k_slices = 1;    // EPI_PARTIAL: K slices (blockIdx.z), plane z at out + z * part_stride
+  size_t part_stride = 0;
 };
 
 // Packed bf16 weight size in elements for a [K, N] matrix (K % 16 == 0, N % 32 == 0).

@@ -44,7 +44,12 @@ hipError_t launch_embed(hipStream_t s, int is_bf16, const float* x, int ldx, int
 // in_map (optional) gathers: output row r is computed from input row in_map[r].
 hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M, const int* m_dev,
                        int norm_type, float eps, const float* g, const float* b, const float* shift,
-                       const float* scale, int ldm, const int* in_map, void* out);
+                       const float* scale, int ldm, const int* in_map, void* out,
+                       const float* parts = nullptr, int n_parts = 0, size_t part_stride = 0, float* h_wb = nullptr);
+// parts / n_parts / part_stride: K-slice partial sums [n_parts][M, d] that a preceding GEMM left for the
+// residual stream; the norm adds them to its input row first and writes the completed row to h_wb (if given).
+hipError_t launch_add_parts(hipStream_t s, float* h, const float* parts, int n_parts, size_t part_stride, int d,
+                            int M, const int* m_dev);
 
 // ---- KV cache addressing (device side)
 // bf16 cache, blocks of 32 positions.  K block: [d/16][lane][8] with lane = (pos%32) + 32*((d%16)/8):

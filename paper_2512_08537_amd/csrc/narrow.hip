@@ -48,7 +48,7 @@ struct NarrowEpi {
       if (a.epi == EPI_GATE_RESID) gate[i] = *(const f32x4*)(a.gate + (size_t)r * a.ldg + n0 + ec);
       if (rmw) old[i] = *(const f32x4*)((const float*)a.out + (size_t)r * a.ldo + n0 + ec);
     }
-    if (a.bias != nullptr) bias4 = *(const f32x4*)(a.bias + n0 + ec);
+    if (a.bias != nullptr && blockIdx.z == 0) bias4 = *(const f32x4*)(a.bias + n0 + ec);
   }
   __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT][NT], float* red, int M, int m0,
                                          int n0) {
@@ -78,6 +78,8 @@ struct NarrowEpi {
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], a.act);
         *(f32x4*)((float*)a.out + o) = v;
+      } else if (a.epi == EPI_PARTIAL) {
+        *(f32x4*)((float*)a.out + (size_t)blockIdx.z * a.part_stride + o) = v;
       } else {
         *(f32x4*)((float*)a.out + o) = old[i] + gate[i] * v;
       }
@@ -95,8 +97,12 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
   if (m0 >= M) return;
   const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
-  const int kb16 = a.K >> 4, kb32 = a.K >> 5;
-  const int my_steps = (kb32 - kw + 3) >> 2;               // steps kw, kw + 4, ... (may be 0)
+  const int kb16 = a.K >> 4;
+  // K slice of this workgroup (blockIdx.z; the whole K unless EPI_PARTIAL): 32-k steps [s0, s0 + kb32)
+  const int sps = ((a.K >> 5) + (int)gridDim.z - 1) / (int)gridDim.z;
+  const int s0 = blockIdx.z * sps;
+  const int kb32 = min(sps, (a.K >> 5) - s0);
+  const int my_steps = (kb32 - kw + 3) >> 2;               // steps s0 + kw, s0 + kw + 4, ... (may be 0)
   const int n0 = blockIdx.x * 16 * NT;
 
   // packed B: fragment (nb, kb16 index) holds lane L = 32 * (k / 8 % 2) + n % 32
@@ -118,7 +124,7 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   bf16x8 breg[NS][NT], areg[NS][MT];
   auto load_ab = [&](int t, int p) {
     int s = kw + 4 * t;
-    s = s < kb32 ? s : kb32 - 1;                           // past the end: a re-read, zeroed at use
+    s = s0 + (s < kb32 ? s : kb32 - 1);                    // past the end: a re-read, zeroed at use
 #pragma unroll
     for (int j = 0; j < NT; ++j) breg[p][j] = bbase[j][(size_t)s * 128];
 #pragma unroll
@@ -167,12 +173,14 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
 }  // namespace
 
 bool narrow_supported(const GemmArgs& a) {
+  if (a.epi == EPI_PARTIAL && (a.k_slices < 1 || a.k_slices > 64 || (a.k_slices > 1 && a.part_stride < (size_t)a.M * a.ldo))) return false;
   return a.M >= 1 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
 }
 
 hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   if (!narrow_supported(a)) return hipErrorInvalidValue;
-  const int steps = (a.K / 32 + 3) / 4;                    // 32-k steps of the busiest wave
+  const int kz = (a.epi == EPI_PARTIAL && a.k_slices > 1) ? a.k_slices : 1;
+  const int steps = ((a.K / 32 + kz - 1) / kz + 3) / 4;      // 32-k steps of the busiest wave
   // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
   // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
 #define FARD_NR(MTV, NTV, NSV, ONE)                                                                        \
@@ -187,7 +195,7 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
         attr_set = true;                                                                                   \
       }                                                                                                    \
     }                                                                                                      \
-    gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV)), 256, lds, s>>>(a); \
+    gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV), kz), 256, lds, s>>>(a); \
   } while (0)
   if (a.M <= 64) {
     // a few dozen rows: 16-row workgroups (more of them, half the activation bytes each) measured ahead of

@@ -142,7 +142,9 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
                                                    int norm_type, float eps, const float* __restrict__ g,
                                                    const float* __restrict__ b, const float* __restrict__ shift,
                                                    const float* __restrict__ scale, int ldm,
-                                                   const int* __restrict__ in_map, T* __restrict__ out) {
+                                                   const int* __restrict__ in_map, T* __restrict__ out,
+                                                   const float* __restrict__ parts, int n_parts, size_t part_stride,
+                                                   float* __restrict__ h_wb) {
   __shared__ float red[8];
   const int Me = eff_rows(M, m_dev);
   const int r = blockIdx.x;
@@ -155,6 +157,18 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
   for (int i = 0; i < VPT; ++i) {
     const int c4 = threadIdx.x + i * 256;
     x[i] = (c4 < n4) ? ((const f32x4*)row)[c4] : f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  if (n_parts > 0) {
+    // deferred residual update: the preceding GEMM left K-slice partial sums; fold them in (and write the row back)
+    const size_t ro = (size_t)(in_map ? in_map[r] : r) * d;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c4 = threadIdx.x + i * 256;
+      if (c4 < n4) {
+        for (int p = 0; p < n_parts; ++p) x[i] += *(const f32x4*)(parts + (size_t)p * part_stride + ro + c4 * 4);
+        if (h_wb != nullptr) *(f32x4*)(h_wb + ro + c4 * 4) = x[i];
+      }
+    }
   }
 #pragma unroll
   for (int i = 0; i < VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
@@ -921,17 +935,39 @@ hipError_t launch_embed(hipStream_t s, int is_bf16, const float* x, int ldx, int
   return hipGetLastError();
 }
 
+// h[r, :] += sum_p parts[p][r, :] for r < M (device-side count honoured): the residual update that a K-sliced GEMM
+// left undone, for consumers of the stream that are not a norm.
+__global__ __launch_bounds__(256) void add_parts_kernel(float* __restrict__ h, const float* __restrict__ parts, int n_parts,
+                                                        size_t part_stride, int d, int M, const int* m_dev) {
+  const int Me = eff_rows(M, m_dev);
+  const int r = blockIdx.x;
+  if (r >= Me) return;
+  for (int c4 = threadIdx.x; c4 < (d >> 2); c4 += 256) {
+    const size_t o = (size_t)r * d + c4 * 4;
+    f32x4 v = *(const f32x4*)(h + o);
+    for (int p = 0; p < n_parts; ++p) v += *(const f32x4*)(parts + (size_t)p * part_stride + o);
+    *(f32x4*)(h + o) = v;
+  }
+}
+
+hipError_t launch_add_parts(hipStream_t s, float* h, const float* parts, int n_parts, size_t part_stride, int d, int M,
+                            const int* m_dev) {
+  if (M <= 0 || n_parts <= 0) return hipSuccess;
+  add_parts_kernel<<<M, 256, 0, s>>>(h, parts, n_parts, part_stride, d, M, m_dev);
+  return hipGetLastError();
+}
+
 hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M, const int* m_dev, int norm_type,
                        float eps, const float* g, const float* b, const float* shift, const float* scale, int ldm,
-                       const int* in_map, void* out) {
+                       const int* in_map, void* out, const float* parts, int n_parts, size_t part_stride, float* h_wb) {
   if (M <= 0) return hipSuccess;
   if (d % 4 != 0 || d > 256 * 4 * NORM_VPT || ldm % 4 != 0) return hipErrorInvalidValue;
 #define FARD_NORM(VPT)                                                                                                 \
   do {                                                                                                                 \
     if (is_bf16)                                                                                                       \
-      norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out);  \
+      norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out, parts, n_parts, part_stride, h_wb);  \
     else                                                                                                               \
-      norm_kernel<float, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out); \
+      norm_kernel<float, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out, parts, n_parts, part_stride, h_wb); \
   } while (0)
   if (d <= 1024) FARD_NORM(1);
   else if (d <= 2048) FARD_NORM(2);

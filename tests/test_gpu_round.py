@@ -167,6 +167,10 @@ def test_config1_full_size_sampled_samples():
     o = run_oracle_round(case, tau=-1.0, samples=idx)
     _compare_round(case, g, o, -1.0, samples=idx)
     assert np.isfinite(g["mu_p"]).all() and np.isfinite(g["log_ratio"]).all()
+    # no kernel on this path combines partial sums with atomics: a second run gives the same bits
+    g2 = run_gpu_round(case, tau=-1.0)
+    for k in ("H", "x_draft", "mu_q", "mu_p", "log_ratio", "n_accept"):
+        assert np.array_equal(g[k], g2[k]), k
 
 
 def _compare_round_chain(case, g, o, tau, idx, tol):
