@@ -31,8 +31,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
+  // merge area: one slab of partial O^T per wave when the four fit (SLABS), else one shared accumulator
+  constexpr bool SLABS = 4 * DH * (NCOL + 1) * 4 <= 40 * 1024;
+  constexpr int OLD = SLABS ? NCOL + 1 : NCOL;             // padded row: conflict-free column-major reads
   __shared__ float s_m[4][NCOL], s_l[4][NCOL], s_a[4][NCOL];
-  __shared__ float s_o[DH * NCOL];
+  __shared__ float s_o[(SLABS ? 4 : 1) * DH * OLD];
 
   const int Hk = kv.n_kv_heads;
   const int G = n_heads / Hk;
@@ -190,7 +193,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
       s_a[wave][cl + 32 * qb] = a_run[qb];
     }
   }
-  for (int i = tid; i < DH * NCOL; i += 256) s_o[i] = 0.f;
+  if constexpr (!SLABS) {
+    for (int i = tid; i < DH * NCOL; i += 256) s_o[i] = 0.f;
+  }
   __syncthreads();
   float f_me[NQB];
 #pragma unroll
@@ -200,19 +205,34 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
     for (int w = 0; w < 4; ++w) mstar = fmaxf(mstar, s_m[w][c]);
     f_me[qb] = (m_run[qb] == -INFINITY) ? 0.f : __expf(m_run[qb] - mstar);
   }
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
+  if constexpr (SLABS) {
+    // every wave lays its rescaled partial O^T down in its own slab: one barrier, no read-modify-write rounds
+    float* slab = s_o + (size_t)wave * DH * OLD;
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb)
+    for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
-            s_o[dim * NCOL + cl + 32 * qb] += o[db][qb][e] * f_me[qb];
-          }
-    }
+        for (int e = 0; e < 16; ++e) {
+          const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
+          slab[dim * OLD + cl + 32 * qb] = o[db][qb][e] * f_me[qb];
+        }
     __syncthreads();
+  } else {
+    for (int w = 0; w < 4; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
+              s_o[dim * OLD + cl + 32 * qb] += o[db][qb][e] * f_me[qb];
+            }
+      }
+      __syncthreads();
+    }
   }
   // ---- normalise and write: thread -> (column, 8 consecutive dims)
   constexpr int D8 = DH / 8;
@@ -234,7 +254,14 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
     const int head = hk * G + gq;
     bf16x8 v;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = (bf16)(s_o[(d8 * 8 + i) * NCOL + c] * inv);
+    for (int i = 0; i < 8; ++i) {
+      float acc = s_o[(d8 * 8 + i) * OLD + c];
+      if constexpr (SLABS) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
+      }
+      v[i] = (bf16)(acc * inv);
+    }
     *(bf16x8*)(out + (size_t)(r0 + j) * ldo + (size_t)head * DH + d8 * 8) = v;
     if (ent_heads != nullptr && d8 == 0) ent_heads[(size_t)(r0 + j) * n_heads + head] = logf(lstar) - astar * inv;
   }
