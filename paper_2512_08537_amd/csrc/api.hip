@@ -934,9 +934,13 @@ int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, c
                              c->h, d, B, nullptr)); }
     const bool attn_mode = c->cfg.entropy_mode == FARD_ENT_ATTN;
     if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0))) return rc;
-    if ((rc = flush_parts(c, d, B, nullptr))) return rc;
+    // pending partial planes of the last shallow layer: the entropy rows add them on the fly and the next norm
+    // folds them into the stream; otherwise they are folded here
+    const bool ent_folds = !attn_mode && ls < m.c.n_layers && ent_rows_in_regs_f32(c->h, d, d);
+    if (!ent_folds && (rc = flush_parts(c, d, B, nullptr))) return rc;
     { Bracket br(c, CLS_ENT, 0, (double)B * d * 4);
-      if (!attn_mode) HIPCHK(c, launch_entropy_rows_f32(s, c->h, d, B, d, c->h_row));
+      if (!attn_mode)
+        HIPCHK(c, launch_entropy_rows_f32(s, c->h, d, B, d, c->h_row, c->parts, ent_folds ? c->pend_n : 0, c->pend_stride));
       HIPCHK(c, launch_entropy_step(s, attn_mode ? c->ent_heads : nullptr, m.c.n_heads, c->h_row, B, K, i, tau, H, keep, c->alive,
                                     n_keep, c->act_idx, c->n_act, c->emap, c->omap)); }
     if ((rc = run_layers(c, FARD_DRAFT, ls, m.c.n_layers, B, B, 1, nullptr, 0))) return rc;

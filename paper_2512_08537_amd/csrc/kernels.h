@@ -97,7 +97,10 @@ hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat
                                     int* n_surv, int* blk_cnt);
 
 // H[r] = softmax entropy of the fp32 row feat[r*ld .. r*ld+L) (one wave per row).
-hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H);
+// parts (n_parts > 0): pending partial planes added to the rows on the fly; only when ent_rows_in_regs_f32 holds.
+bool ent_rows_in_regs_f32(const float* feat, int ld, int L);
+hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H,
+                                   const float* parts = nullptr, int n_parts = 0, size_t part_stride = 0);
 
 // One draft step's threshold on per-row entropies already computed elsewhere (ATTN mode) or per
 // head (mean over heads taken here): alive[b] &= (H >= tau); n_keep[b] += alive[b]; writes H and keep

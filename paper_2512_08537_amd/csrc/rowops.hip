@@ -416,9 +416,13 @@ __device__ __forceinline__ int block_excl_scan(int v, int* s_scan, int* total) {
 }
 
 // H[r] = entropy of row r (one wave per row, rows `ld` elements apart).
+// With n_parts > 0 (fp32 rows held in registers only; the host checks ent_rows_in_regs) the row is
+// feat[r] + sum_p parts[p * part_stride + r * L + .]: pending partial planes of a K-sliced GEMM, added in
+// plane order.
 template <typename T>
 __global__ __launch_bounds__(256) void entropy_rows_kernel(const T* __restrict__ feat, int ld, int rows, int L,
-                                                           float* __restrict__ H) {
+                                                           float* __restrict__ H, const float* __restrict__ parts = nullptr,
+                                                           int n_parts = 0, size_t part_stride = 0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * 4 + wave;
   if (r >= rows) return;
@@ -428,6 +432,14 @@ __global__ __launch_bounds__(256) void entropy_rows_kernel(const T* __restrict__
   if ((((uintptr_t)row) & 15) == 0 && L % VE == 0 && L >= VE && L / VE <= ENT_NCH * WAVE) {
     typename EntVec<T>::type v[ENT_NCH];
     ent_fetch<T>(row, 0, L / VE, lane, v);
+    if constexpr (sizeof(T) == 4) {
+      for (int p = 0; p < n_parts; ++p) {
+        f32x4 w[ENT_NCH];
+        ent_fetch<float>(parts + p * part_stride + (size_t)r * L, 0, L / VE, lane, w);
+#pragma unroll
+        for (int j = 0; j < ENT_NCH; ++j) v[j] += w[j];
+      }
+    }
     h = ent_row_regs<T>(v, L / VE, lane);
   } else {
     h = row_entropy_wave(row, L, lane);
@@ -1029,9 +1041,16 @@ hipError_t launch_entropy_prefilter(hipStream_t s, int is_bf16, const void* feat
   return hipGetLastError();
 }
 
-hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H) {
+bool ent_rows_in_regs_f32(const float* feat, int ld, int L) {
+  return (((uintptr_t)feat) & 15) == 0 && ld % 4 == 0 && L % 4 == 0 && L >= 4 && L / 4 <= ENT_NCH * WAVE;
+}
+
+hipError_t launch_entropy_rows_f32(hipStream_t s, const float* feat, int ld, int rows, int L, float* H, const float* parts,
+                                   int n_parts, size_t part_stride) {
   if (rows <= 0) return hipSuccess;
-  entropy_rows_kernel<float><<<(rows + 3) / 4, 256, 0, s>>>(feat, ld, rows, L, H);
+  if (n_parts > 0 && (!ent_rows_in_regs_f32(feat, ld, L) || (((uintptr_t)parts) & 15) != 0 || part_stride % 4 != 0))
+    return hipErrorInvalidValue;
+  entropy_rows_kernel<float><<<(rows + 3) / 4, 256, 0, s>>>(feat, ld, rows, L, H, parts, n_parts, part_stride);
   return hipGetLastError();
 }
 
