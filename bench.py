@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="BASELINE config index (0..4)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-graph", action="store_true", help="time kernel-by-kernel launches instead of graph replays")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--deep-gain", type=float, default=0.02)
     ap.add_argument("--cpu-samples", type=int, default=8)
@@ -65,7 +66,7 @@ def main():
     # truncated draft predicts the target's feature about as well as a trained draft (acceptance ~0.7/token)
     case = build_case(args.config, seed=args.seed, affine=False, cache_layers_shared=shared, deep_gain=args.deep_gain)
     rc, B, K = case.rc, case.B, case.rc.K
-    ctx = make_ctx(case)
+    ctx = make_ctx(case, stream=torch.cuda.Stream())   # a stream of its own: rounds can be captured into a HIP graph
     gi = gpu_inputs(ctx, case)
     out = ctx._round_bufs(B)
     lens = np.full(B, case.n_ctx, dtype=np.int32)
@@ -85,15 +86,24 @@ def main():
         reset()
         ctx.spec_round(gi["pending"], gi["eps"], gi["r"], tau, out=out)
 
-    for _ in range(args.warmup):
-        step()
-    ctx.sync()
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    ctx.sync()
-    dt = time.perf_counter() - t1
-    ms = dt / args.steps * 1e3
+    def timed():
+        for _ in range(args.warmup):
+            step()
+        ctx.sync()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        ctx.sync()
+        return (time.perf_counter() - t1) / args.steps * 1e3
+
+    # kernel-by-kernel launches first (reported beside the headline), then the library's graph replay of the
+    # same round: identical kernels and arguments, recorded on the second call and replayed afterwards
+    ms_eager = timed()
+    ms = ms_eager
+    if not args.no_graph:
+        ctx.spec_graph_enable(True)
+        step(); step()                                   # first sighting of the arguments, then the recording call
+        ms = timed()
 
     n_keep = out["n_keep"].cpu().numpy()
     n_acc = out["n_accept"].cpu().numpy()
@@ -182,6 +192,8 @@ def main():
                                f"target L={t.n_layers} d={t.d_model}, draft L={d.n_layers}, head {rc.head.n_blocks}x"
                                f"{rc.head.width} S={rc.head.n_steps}; weights N(0,0.02), draft = first layers of the target, "
                                f"deep-layer output projections x{args.deep_gain}",
+                   "launch": "kernel by kernel" if args.no_graph else "HIP graph replay of the round (spec_graph_enable)",
+                   "ms_per_step_kernel_by_kernel": round(ms_eager, 4),
                    "tau_ent": round(tau, 4), "accepted_per_round": accepted, "verified_per_round": verified,
                    "acceptance_rate": round(accepted / max(verified, 1.0), 4),
                    "prefilter_rate": round(1.0 - verified / (B * K), 4),

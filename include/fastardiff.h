@@ -195,6 +195,17 @@ int spec_round(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id,
                int32_t B, float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q,
                int32_t* n_accept, float* log_ratio, float* mu_p);
 
+/* Launch-bound rounds as one HIP graph (a round of Alg. 1 at a few tens of samples is several hundred short
+ * dependent kernels).  enable = 1: spec_round called with exactly the arguments of the call before it
+ * (same pointers, scalars and B) records its launches into a graph on the second such call and replays that
+ * graph on every later one; a call with other arguments launches kernel by kernel again and starts over.
+ * Replays read the cache lengths on the device, so spec_kv_reset / spec_kv_load between calls are fine; the
+ * host-side capacity rules (FARD_ECAPACITY) are checked on every call as usual.  The buffers the arguments
+ * name must stay allocated while the graph is in use; their contents may change freely.
+ * enable = 0 drops the graph.  Per-kernel timing (spec_profile_enable) switches replay off while it is on.
+ * Errors: FARD_ESTATE if the context runs on the default stream (it cannot be captured). */
+int spec_graph_enable(fard_ctx* ctx, int32_t enable);
+
 /* Alg. 1 Step 5 (S3 item 3) and the token a round ends with, for every sample (device memory throughout):
  *   n_accept[b] < n_keep[b]: draft n_accept[b]+1 was rejected; the token is drawn from the residual
  *     max(0, Sigma p - q) by acceptance-rejection: proposal j = mu_p[b, n] + sigma_p * eps_res[b, j, :] is taken

@@ -69,6 +69,7 @@ _SIGS = {
                       _vp],
     "spec_gemm": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
     "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp],
+    "spec_graph_enable": [_vp, _i32],
     "spec_profile_enable": [_vp, _i32],
     "spec_profile_read": [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                           C.POINTER(C.c_double)],
@@ -346,6 +347,9 @@ class Context:
         N = W.shape[1]
         self._chk(lib.spec_gemm_narrow(self.h, _ptr(A), _ptr(W), _ptr(bias), _ptr(gate), M, K, N, epi, act, _ptr(out)))
         return out
+
+    def spec_graph_enable(self, on: bool):
+        self._chk(lib.spec_graph_enable(self.h, 1 if on else 0))
 
     def spec_profile_enable(self, on: bool):
         self._chk(lib.spec_profile_enable(self.h, int(on)))

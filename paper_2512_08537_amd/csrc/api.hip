@@ -106,6 +106,29 @@ struct Prof {
   double flops[4] = {0, 0, 0, 0}, bytes[4] = {0, 0, 0, 0};
 };
 
+// A captured round: spec_round called again with the arguments of `key` replays `exec` instead of launching
+// its kernels one by one.
+struct RoundKey {
+  const void* ptr[13];
+  float f[4];
+  int32_t B;
+  int32_t pad;
+};
+struct RoundGraph {
+  bool on = false;
+  bool have_key = false;                   // key = the arguments of the last eager spec_round call
+  RoundKey key;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;           // non-null: replays key
+  void drop() {
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    exec = nullptr;
+    graph = nullptr;
+    have_key = false;
+  }
+};
+
 }  // namespace
 
 struct fard_ctx {
@@ -133,6 +156,7 @@ struct fard_ctx {
   float* parts = nullptr;
   int pend_n = 0;
   size_t pend_stride = 0;
+  RoundGraph rgraph;
   uint8_t* acc_tmp = nullptr;
   float *cz = nullptr, *hh = nullptr, *mod = nullptr, *xt = nullptr;
   void *sc = nullptr, *a1 = nullptr, *a2 = nullptr;
@@ -747,6 +771,7 @@ int spec_round_destroy(fard_ctx* c) {
   if (!c) return FARD_EINVAL;
   (void)hipStreamSynchronize(c->stream);
   for (auto& ev : c->prof.pool) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
+  c->rgraph.drop();
   if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
   for (void* p : c->allocs) (void)hipFree(p);
   delete c;
@@ -997,19 +1022,111 @@ int spec_verify(fard_ctx* c, const float* x_pending, const int32_t* pending_id, 
   { Bracket br(c, CLS_OTHER);
     HIPCHK(c, launch_accept(s, x_draft, mu_p, mu_q, r, n_keep, log_sigma_factor, sigma_p, sigma_q, B, K, D, n_accept, log_ratio,
                             c->acc_tmp)); }
+  m.len_hi += K + 1;                       // what a commit may keep at most
   m.written = K + 1;
   return FARD_OK;
 }
 
-int spec_round(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, const float* r, float tau,
-               float log_sigma_factor, float sigma_p, float sigma_q, int32_t B, float* H, uint8_t* keep, int32_t* n_keep,
-               float* x_draft, float* mu_q, int32_t* n_accept, float* log_ratio, float* mu_p) {
+static int round_eager(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, const float* r,
+                       float tau, float log_sigma_factor, float sigma_p, float sigma_q, int32_t B, float* H, uint8_t* keep,
+                       int32_t* n_keep, float* x_draft, float* mu_q, int32_t* n_accept, float* log_ratio, float* mu_p) {
   int rc = spec_draft(c, x_pending, pending_id, eps, tau, B, H, keep, n_keep, x_draft, mu_q);
   if (rc) return rc;
   rc = spec_verify(c, x_pending, pending_id, x_draft, mu_q, n_keep, r, eps, log_sigma_factor, sigma_p, sigma_q, B, n_accept,
                    log_ratio, mu_p, nullptr);
   if (rc) return rc;
   return spec_kv_commit(c, -1, n_accept, B);
+}
+
+// The cache-capacity rules of spec_draft and spec_verify, for a round that launches no kernel of its own.
+static int round_capacity(fard_ctx* c) {
+  const int K = c->cfg.K;
+  for (int w = 0; w < 2; ++w) {
+    const Model& m = c->mdl[w];
+    const int add = (w == FARD_TARGET) ? K + 1 : K;
+    if (m.len_hi + add > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "cache_len + K (+ 1) exceeds max_ctx");
+    if (m.c.pos == FARD_POS_LEARNED && m.len_hi + add > m.c.max_pos) return fail(c, FARD_ECAPACITY, "position beyond the learned table");
+  }
+  return FARD_OK;
+}
+
+int spec_graph_enable(fard_ctx* c, int32_t on) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (on && c->stream == nullptr) return fail(c, FARD_ESTATE, "rounds on the default stream cannot be captured");
+  c->rgraph.drop();
+  c->rgraph.on = on != 0;
+  return FARD_OK;
+}
+
+int spec_round(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, const float* r, float tau,
+               float log_sigma_factor, float sigma_p, float sigma_q, int32_t B, float* H, uint8_t* keep, int32_t* n_keep,
+               float* x_draft, float* mu_q, int32_t* n_accept, float* log_ratio, float* mu_p) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  RoundGraph& g = c->rgraph;
+  auto eager = [&]() {
+    return round_eager(c, x_pending, pending_id, eps, r, tau, log_sigma_factor, sigma_p, sigma_q, B, H, keep, n_keep, x_draft,
+                       mu_q, n_accept, log_ratio, mu_p);
+  };
+  if (!g.on || c->prof.on || B <= 0) return eager();
+  RoundKey key;
+  memset(&key, 0, sizeof(key));
+  const void* ptrs[13] = {x_pending, pending_id, eps, r, H, keep, n_keep, x_draft, mu_q, n_accept, log_ratio, mu_p, nullptr};
+  memcpy(key.ptr, ptrs, sizeof(ptrs));
+  key.f[0] = tau; key.f[1] = log_sigma_factor; key.f[2] = sigma_p; key.f[3] = sigma_q;
+  key.B = B;
+  const bool same = g.have_key && memcmp(&key, &g.key, sizeof(key)) == 0;
+  const int K = c->cfg.K;
+  if (same && g.exec) {
+    // replay: the kernels read the cache lengths on the device; the host repeats its capacity rules and bounds
+    int rc = round_capacity(c);
+    if (rc) return rc;
+    HIPCHK(c, hipGraphLaunch(g.exec, c->stream));
+    c->mdl[FARD_DRAFT].len_hi += K;
+    c->mdl[FARD_TARGET].len_hi += K + 1;
+    c->mdl[FARD_DRAFT].written = c->mdl[FARD_TARGET].written = 0;
+    return FARD_OK;
+  }
+  if (!same) {
+    // first call with these arguments: launch as usual (this also validates them) and remember them
+    g.drop();
+    int rc = eager();
+    if (rc == FARD_OK) {
+      g.key = key;
+      g.have_key = true;
+    }
+    return rc;
+  }
+  // second call in a row with the same arguments: record the launches into a graph, then launch the graph
+  int rc = round_capacity(c);
+  if (rc) return rc;
+  const int hi0[2] = {c->mdl[0].len_hi, c->mdl[1].len_hi}, wr0[2] = {c->mdl[0].written, c->mdl[1].written};
+  auto undo = [&]() {
+    for (int w = 0; w < 2; ++w) { c->mdl[w].len_hi = hi0[w]; c->mdl[w].written = wr0[w]; }
+    c->pend_n = 0;
+    g.drop();
+  };
+  HIPCHK(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed));
+  rc = eager();
+  hipGraph_t graph = nullptr;
+  hipError_t e = hipStreamEndCapture(c->stream, &graph);
+  if (rc != FARD_OK || e != hipSuccess || !graph) {
+    if (graph) (void)hipGraphDestroy(graph);
+    undo();
+    if (rc != FARD_OK) return rc;
+    return fail(c, FARD_EHIP, std::string("graph capture: ") + hipGetErrorString(e));
+  }
+  hipGraphExec_t exec = nullptr;
+  e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  if (e == hipSuccess) e = hipGraphLaunch(exec, c->stream);
+  if (e != hipSuccess) {
+    if (exec) (void)hipGraphExecDestroy(exec);
+    (void)hipGraphDestroy(graph);
+    undo();
+    return fail(c, FARD_EHIP, std::string("graph launch: ") + hipGetErrorString(e));
+  }
+  g.graph = graph;
+  g.exec = exec;
+  return FARD_OK;
 }
 
 int spec_resample(fard_ctx* c, const float* mu_p, const float* mu_q, const float* eps, const int32_t* n_accept,
@@ -1055,7 +1172,7 @@ int spec_generate(fard_ctx* c, const float* x_first, const int32_t* first_id, co
   uint8_t* keep = c->g_keep;
   for (int t = 0; t < R; ++t) {
     const float* eps_t = eps + (size_t)t * eps_round;
-    int rc = spec_round(c, t == 0 ? x_first : c->g_next, t == 0 ? first_id : nullptr, eps_t, r + (size_t)t * B * K, tau,
+    int rc = round_eager(c, t == 0 ? x_first : c->g_next, t == 0 ? first_id : nullptr, eps_t, r + (size_t)t * B * K, tau,
                         log_sigma_factor, sigma_p, sigma_q, B, H + (size_t)t * B * K, keep, n_keep + (size_t)t * B, c->g_x,
                         c->g_mu_q, n_accept + (size_t)t * B, c->g_lr, c->g_mu_p);
     if (rc) return rc;

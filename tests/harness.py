@@ -68,9 +68,9 @@ def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_d
 
 
 # ------------------------------------------------------------------------------ GPU side
-def make_ctx(case: Case):
+def make_ctx(case: Case, stream=None):
     from paper_2512_08537_amd import binding
-    ctx = binding.Context(case.rc, case.W)
+    ctx = binding.Context(case.rc, case.W, stream=stream)
     load_caches(ctx, case)
     return ctx
 
