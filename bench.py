@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="BASELINE config index (0..4)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-generate", action="store_true", help="skip the multi-round generation figure (counter runs: "
+                    "fewer dispatches to collect)")
     ap.add_argument("--no-graph", action="store_true", help="time kernel-by-kernel launches instead of graph replays")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--deep-gain", type=float, default=0.02)
@@ -66,7 +68,8 @@ def main():
     # truncated draft predicts the target's feature about as well as a trained draft (acceptance ~0.7/token)
     case = build_case(args.config, seed=args.seed, affine=False, cache_layers_shared=shared, deep_gain=args.deep_gain)
     rc, B, K = case.rc, case.B, case.rc.K
-    ctx = make_ctx(case, stream=torch.cuda.Stream())   # a stream of its own: rounds can be captured into a HIP graph
+    # a stream of its own, so that rounds can be captured into a HIP graph (--no-graph: the default stream)
+    ctx = make_ctx(case, stream=None if args.no_graph else torch.cuda.Stream())
     gi = gpu_inputs(ctx, case)
     out = ctx._round_bufs(B)
     lens = np.full(B, case.n_ctx, dtype=np.int32)
@@ -121,14 +124,22 @@ def main():
     g_avg_us = g["ms"] / max(g["launches"], 1) * 1e3
     g_tflops = g["flops"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
     peak = PEAK_BF16_TFLOPS if rc.dtype == 1 else PEAK_FP32_TFLOPS
-    roofline = {"bound": "mfma" if rc.dtype == 1 else "alu",
+    g_gbs = g["bytes"] / (g["ms"] * 1e-3) / 1e9 if g["ms"] > 0 else 0.0
+    # which roof the GEMMs of this workload sit under: flops per algorithmic byte against the ridge peak_flops / peak_bytes
+    # (a few tens to a few hundred rows per weight matrix: the weights are streamed once, the roof is HBM)
+    intensity = g["flops"] / max(g["bytes"], 1.0)
+    hbm_bound = intensity < peak * 1e12 / (PEAK_HBM_GBS * 1e9)
+    roofline = {"bound": "hbm" if hbm_bound else ("mfma" if rc.dtype == 1 else "alu"),
                 "kernel": "GEMM kernels of the round (gemm_narrow_kernel, gemm_bf16_kernel, gemm_bf16_res_kernel)",
-                "achieved": round(g_tflops, 3), "peak": peak, "unit": "TFLOP/s", "frac": round(g_tflops / peak, 5),
+                "achieved": round(g_gbs, 1) if hbm_bound else round(g_tflops, 3),
+                "peak": PEAK_HBM_GBS if hbm_bound else peak, "unit": "GB/s" if hbm_bound else "TFLOP/s",
+                "frac": round(g_gbs / PEAK_HBM_GBS, 5) if hbm_bound else round(g_tflops / peak, 5),
                 "traffic": hbm_traffic_per_launch(args.config), "launches_per_step": g["launches"] / args.steps,
                 "avg_launch_us": round(g_avg_us, 3),
                 "flops_per_launch": g["flops"] / max(g["launches"], 1),
                 "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
-                "achieved_GBs": round(g["bytes"] / (g["ms"] * 1e-3) / 1e9, 1) if g["ms"] > 0 else 0.0}
+                "flops_per_byte": round(intensity, 1), "achieved_TFLOPs": round(g_tflops, 3),
+                "frac_mfma": round(g_tflops / peak, 5), "achieved_GBs": round(g_gbs, 1)}
     # attention: algorithmic K/V bytes of the verify forward + the K draft steps
     t, d = rc.target, rc.draft
     esz = 2 if rc.dtype == 1 else 4
@@ -150,7 +161,7 @@ def main():
     R = min(16, (rc.max_ctx - case.n_ctx) // (K + 1))
     if rc.target.pos == 0 and rc.target.max_pos:
         R = min(R, (rc.target.max_pos - case.n_ctx) // (K + 1))
-    if R >= 1:
+    if R >= 1 and not args.no_generate:
         J, D, S = 16, rc.target.d_latent, rc.head.n_steps
         gt = torch.Generator(device=ctx.dev).manual_seed(args.seed)
         g_eps = torch.randn((R, S + 1, B, K + 1, D), generator=gt, device=ctx.dev)
