@@ -168,6 +168,7 @@ def main():
         g_r = torch.rand((R, B, K), generator=gt, device=ctx.dev)
         g_er = torch.randn((R, B, J, D), generator=gt, device=ctx.dev)
         g_ur = torch.rand((R, B, J), generator=gt, device=ctx.dev)
+        torch.cuda.synchronize()                         # (torch filled these on its own stream)
         reps = max(1, min(5, args.steps))
         for i in range(reps + 1):
             if i == 1:
@@ -181,6 +182,41 @@ def main():
         gen_stats = {"rounds": R, "ms_per_round": round(tg / R * 1e3, 4), "tokens": n_tok,
                      "tokens_per_s": round(n_tok / tg, 1), "resample_tries_mean":
                      round(float(go["tries"].float().sum().item()) / max(1.0, float((go["tries"] > 0).sum().item())), 2)}
+
+    # Prefill (the next row after the round itself): both caches rebuilt from a prefix of n_ctx known tokens per sample
+    # (a class token and latents), timed on the stream; GEMM and attention time of the target's prefill from HIP events
+    pf_stats = None
+    if not args.no_generate:
+        npf = np.full(B, case.n_ctx, dtype=np.int32)
+        gp = torch.Generator(device=ctx.dev).manual_seed(args.seed + 1)
+        xpf = torch.randn((B, case.n_ctx, rc.target.d_latent), generator=gp, device=ctx.dev)
+        ids = None
+        if rc.target.n_cond_ids > 0:
+            ids = torch.randint(0, rc.target.n_cond_ids, (B,), generator=gp, device=ctx.dev, dtype=torch.int32)
+        torch.cuda.synchronize()
+        pf_ms = {}
+        for which, name in ((binding.TARGET, "target"), (binding.DRAFT, "draft")):
+            reps = 3
+            for i in range(reps + 1):
+                if i == 1:
+                    ctx.sync()
+                    tp0 = time.perf_counter()
+                ctx.spec_kv_reset(which, None)
+                ctx.spec_prefill(which, xpf, npf, first_id=ids, want_z=False)
+            ctx.sync()
+            pf_ms[name] = (time.perf_counter() - tp0) / reps * 1e3
+        ctx.spec_profile_enable(True)
+        ctx.spec_kv_reset(binding.TARGET, None)
+        ctx.spec_prefill(binding.TARGET, xpf, npf, first_id=ids, want_z=False)
+        pg, pa = ctx.spec_profile_read(0), ctx.spec_profile_read(1)
+        ctx.spec_profile_enable(False)
+        ntok = float(B * case.n_ctx)
+        pf_tflops = pg["flops"] / (pg["ms"] * 1e-3) / 1e12 if pg["ms"] > 0 else 0.0
+        pf_stats = {"tokens": ntok, "ms_target": round(pf_ms["target"], 3), "ms_draft": round(pf_ms["draft"], 3),
+                    "tokens_per_s_target": round(ntok / (pf_ms["target"] * 1e-3), 1),
+                    "gemm": {"ms": round(pg["ms"], 3), "launches": pg["launches"], "achieved_TFLOPs": round(pf_tflops, 1),
+                             "frac_mfma": round(pf_tflops / peak, 5)},
+                    "attention_ms": round(pa["ms"], 3)}
 
     cpu = None
     if not args.no_cpu:
@@ -210,7 +246,7 @@ def main():
                    "prefilter_rate": round(1.0 - verified / (B * K), 4),
                    "accepted_plus_bonus_tokens_per_s": round((accepted + B) / (ms * 1e-3), 1),
                    "verified_tokens_per_s": round(verified / (ms * 1e-3), 1)},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "generate": gen_stats,
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels, "generate": gen_stats, "prefill": pf_stats,
     }
     ctx.close()
     print(json.dumps(line))

@@ -133,7 +133,7 @@ int spec_kv_commit(fard_ctx* ctx, int32_t which, const int32_t* n_accept, int32_
  * draft; causal structure of Sec. 3.1).  Sample b owns n_q[b] consecutive rows; row j of a sample
  * sits at position cache_len[b] + j and attends to the cache and to rows 0..j.
  *   x_in     fp32 [M, D] latent rows         cond_id  int32 [M] or NULL; >= 0: the row is an id row
- *   n_q      device int32 [B], sum <= M      M <= max_batch*(K+1)
+ *   n_q      device int32 [B], sum <= M      M <= max_batch * max(K+1, rows of a prefill pass)
  *   nq_max   host upper bound of n_q[b]; device values are clamped to it; bf16: nq_max * (H/H_kv) <= 64.
  *            Capacity (cache_len + nq_max <= max_ctx) is checked against it on the host.
  *   commit   1: cache_len[b] += n_q[b]
@@ -142,6 +142,21 @@ int spec_kv_commit(fard_ctx* ctx, int32_t which, const int32_t* n_accept, int32_
 int spec_forward(fard_ctx* ctx, int32_t which, const float* x_in, const int32_t* cond_id,
                  const int32_t* n_q, int32_t nq_max, int32_t B, int32_t M, int32_t commit, void* z_out,
                  float* shallow_out, float* h_attn_out);
+
+/* Prefill: builds the KV cache of one model from a prefix of known tokens instead of loading it (the prefix that
+ * Alg. 1 starts from; causal structure of Sec. 3.1).  Sample b's rows x[b, 0 .. n[b]-1, :] are appended at
+ * positions cache_len[b] .. cache_len[b] + n[b] - 1; row j attends to the cache and to rows 0..j.  The prefix is
+ * taken in passes of at most 64 / (n_heads / n_kv_heads) rows per sample (what one attention workgroup holds; 64 in
+ * fp32), each a spec_forward with commit = 1, so the result is that of one causal forward over all rows.
+ *   x        device fp32 [B, n_max, D] latent rows (rows at or beyond n[b] are not read)
+ *   first_id device int32 [B] or NULL: >= 0 makes row 0 of the prefix an id row (class token); needs an id table
+ *   n        HOST int32 [B], 0 <= n[b] <= n_max (copied before return)
+ *   z_last   storage type [B, d_out] or NULL: the feature of each sample's last prefix row (what the head decodes
+ *            into the first token); rows of samples with n[b] = 0 are left untouched
+ * Errors: FARD_ECAPACITY if cache_len + max n exceeds max_ctx or the learned position table; FARD_EINVAL for
+ * n[b] outside [0, n_max].  Synchronises once at the start (for the copy of n). */
+int spec_prefill(fard_ctx* ctx, int32_t which, const float* x, const int32_t* first_id, const int32_t* n,
+                 int32_t n_max, int32_t B, void* z_last);
 
 /* Shallow-layer entropy indicator + pre-filter (abstract; Eq. 1; Sec. 4.3; Alg. 1 Step 1):
  * H[b,i] = -sum_c p_c ln p_c, p = softmax(feat[b,i,:]); keep[b,i] = all_{j<=i}(H[b,j] >= tau);

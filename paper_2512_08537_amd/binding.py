@@ -70,6 +70,7 @@ _SIGS = {
     "spec_gemm": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
     "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp],
     "spec_graph_enable": [_vp, _i32],
+    "spec_prefill": [_vp, _i32, _vp, _vp, C.POINTER(C.c_int32), _i32, _i32, _vp],
     "spec_profile_enable": [_vp, _i32],
     "spec_profile_read": [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                           C.POINTER(C.c_double)],
@@ -231,6 +232,20 @@ class Context:
         self._chk(lib.spec_forward(self.h, which, _ptr(x_in), _ptr(cond_id), _ptr(n_q), int(nq_max), B, M, int(commit),
                                    _ptr(z), _ptr(sh), _ptr(ha)))
         return z, sh, ha
+
+    def spec_prefill(self, which, x, n, first_id=None, want_z=True):
+        """x: device fp32 [B, n_max, D]; n: host int32 [B]; first_id: device int32 [B] or None."""
+        B, n_max, _ = x.shape
+        n = np.ascontiguousarray(n, dtype=np.int32)
+        assert n.shape == (B,)
+        tc = self.rc.target if which == TARGET else self.rc.draft
+        z = self.empty((B, tc.d_out or tc.d_model), self.tdtype) if want_z else None
+        if z is not None:
+            z.zero_()
+            self.torch.cuda.synchronize()
+        self._chk(lib.spec_prefill(self.h, which, _ptr(x), _ptr(first_id), n.ctypes.data_as(C.POINTER(C.c_int32)), n_max, B,
+                                   _ptr(z)))
+        return z
 
     def entropy_prefilter(self, feat, tau):
         t = self.torch

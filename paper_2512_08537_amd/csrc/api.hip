@@ -49,6 +49,39 @@ __global__ void copy_i32_kernel(const int* src, int* dst, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = src[i];
 }
+// Prefill, one chunk: sample b contributes nq[b] = clamp(n[b] - c0, 0, chunk) rows.
+__global__ void prefill_chunk_kernel(const int* __restrict__ n, int c0, int chunk, int* __restrict__ nq, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) nq[b] = min(max(n[b] - c0, 0), chunk);
+}
+// Packed row (sample b, j) <- x[b, c0 + j, :]; its id is first_id[b] at position 0 of the prefix, else -1 (a
+// latent row).  One workgroup per sample; the sample's first packed row is the sum of the counts before it.
+__global__ __launch_bounds__(64) void prefill_pack_kernel(const float* __restrict__ x, int n_max, int D, int c0,
+                                                          const int* __restrict__ nq, const int* __restrict__ first_id,
+                                                          float* __restrict__ x_out, int* __restrict__ ids) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  int start = 0;
+  for (int i = lane; i < b; i += 64) start += nq[i];
+  for (int o = 32; o > 0; o >>= 1) start += __shfl_xor(start, o, 64);
+  const int cnt = nq[b];
+  for (int e = lane; e < cnt * D; e += 64) {
+    const int j = e / D, k = e - j * D;
+    x_out[(size_t)(start + j) * D + k] = x[((size_t)b * n_max + c0 + j) * D + k];
+  }
+  for (int j = lane; j < cnt; j += 64) ids[start + j] = (first_id && c0 + j == 0) ? first_id[b] : -1;
+}
+// z_last[b, :] <- the packed feature row of sample b's last prefix position, in the chunk that holds it.
+template <typename T>
+__global__ __launch_bounds__(64) void prefill_last_kernel(const T* __restrict__ z, int ldz, const int* __restrict__ n, int c0,
+                                                          const int* __restrict__ nq, T* __restrict__ z_last) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int cnt = nq[b];
+  if (cnt == 0 || c0 + cnt != n[b]) return;
+  int start = 0;
+  for (int i = lane; i < b; i += 64) start += nq[i];
+  for (int o = 32; o > 0; o >>= 1) start += __shfl_xor(start, o, 64);
+  for (int k = lane; k < ldz; k += 64) z_last[(size_t)b * ldz + k] = z[(size_t)(start + cnt - 1) * ldz + k];
+}
 __global__ void temb_feat_kernel(float t, float t_scale, int half, float* out) {
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k < half) {
@@ -136,7 +169,9 @@ struct fard_ctx {
   hipStream_t stream = nullptr;
   int bf16 = 1;
   size_t esz = 2;
-  int m_max = 0;
+  int m_max = 0;                           // rows of a round: max_batch * (K + 1)
+  int m_rows = 0;                          // rows of the transformer workspace: max_batch * max(K + 1, prefill chunk)
+  int *pf_n = nullptr, *pf_nq = nullptr;   // prefill: prefix lengths and the current chunk's row counts
   Model mdl[2];
   HeadW head;
   std::vector<void*> allocs;
@@ -502,7 +537,7 @@ constexpr int PART_MAX_ROWS = 640;
 
 int alloc_workspace(fard_ctx* c) {
   const fard_round_cfg& g = c->cfg;
-  const int M = c->m_max;
+  const int M = c->m_max, MR = c->m_rows;
   int dmax = 0, qmax = 0, hdmax = 0, fmax = 0, omax = 0, hmax = 0;
   for (int i = 0; i < 2; ++i) {
     const Model& m = c->mdl[i];
@@ -515,23 +550,23 @@ int alloc_workspace(fard_ctx* c) {
   }
   const int w = g.head.width, D = g.head.d_latent;
   int rc;
-  if ((rc = dalloc<float>(c, &c->h, (size_t)M * dmax))) return rc;
-  if ((rc = dalloc<float>(c, &c->x_in, (size_t)M * 16))) return rc;
-  if ((rc = dalloc<float>(c, &c->ent_heads, (size_t)M * hmax))) return rc;
-  if ((rc = dalloc<float>(c, &c->h_row, (size_t)M))) return rc;
-  if ((rc = dalloc_bytes(c, &c->u, (size_t)M * dmax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->qkv, (size_t)M * qmax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->ao, (size_t)M * hdmax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->ff, (size_t)M * fmax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->z, (size_t)M * omax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->ztmp, (size_t)M * dmax * c->esz))) return rc;
+  if ((rc = dalloc<float>(c, &c->h, (size_t)MR * dmax))) return rc;
+  if ((rc = dalloc<float>(c, &c->x_in, (size_t)MR * 16))) return rc;
+  if ((rc = dalloc<float>(c, &c->ent_heads, (size_t)MR * hmax))) return rc;
+  if ((rc = dalloc<float>(c, &c->h_row, (size_t)MR))) return rc;
+  if ((rc = dalloc_bytes(c, &c->u, (size_t)MR * dmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->qkv, (size_t)MR * qmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ao, (size_t)MR * hdmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ff, (size_t)MR * fmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->z, (size_t)MR * omax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ztmp, (size_t)MR * dmax * c->esz))) return rc;
   if ((rc = dalloc<int>(c, &c->maps.row_start, g.max_batch + 2))) return rc;
-  if ((rc = dalloc<int>(c, &c->maps.row_sample, M))) return rc;
-  if ((rc = dalloc<int>(c, &c->maps.row_j, M))) return rc;
-  if ((rc = dalloc<int>(c, &c->maps.row_pos, M))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_sample, MR))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_j, MR))) return rc;
+  if ((rc = dalloc<int>(c, &c->maps.row_pos, MR))) return rc;
   if ((rc = dalloc<int>(c, &c->maps.m_total, 4))) return rc;
-  if ((rc = dalloc<int>(c, &c->aux_row, M))) return rc;
-  if ((rc = dalloc<int>(c, &c->row_ids, M))) return rc;
+  if ((rc = dalloc<int>(c, &c->aux_row, MR))) return rc;
+  if ((rc = dalloc<int>(c, &c->row_ids, MR))) return rc;
   if ((rc = dalloc<float>(c, &c->x_scratch, (size_t)M * 16))) return rc;
   if ((rc = dalloc<uint8_t>(c, &c->acc_tmp, (size_t)g.max_batch * g.K))) return rc;
   if ((rc = dalloc<float>(c, &c->cz, (size_t)M * w))) return rc;
@@ -547,6 +582,8 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<int>(c, &c->emap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->omap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->ent_blk, ENT_MAX_BLOCKS))) return rc;
+  if ((rc = dalloc<int>(c, &c->pf_n, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->pf_nq, g.max_batch))) return rc;
   const size_t bk = (size_t)g.max_batch * g.K;
   if ((rc = dalloc<float>(c, &c->g_x, bk * D))) return rc;
   if ((rc = dalloc<float>(c, &c->g_mu_q, bk * D))) return rc;
@@ -660,6 +697,8 @@ int cap_nq(const fard_ctx* c, int which) {
   const fard_tf_cfg& t = c->mdl[which].c;
   return c->bf16 ? 64 / (t.n_heads / t.n_kv_heads) : 1 << 20;
 }
+// Rows per sample that one prefill pass takes: what one attention workgroup holds, at most 64.
+int prefill_chunk(const fard_ctx* c, int which) { return std::min(std::min(cap_nq(c, which), 64), c->cfg.max_ctx); }
 
 // S sampler steps of the head over n rows of z (compact), noise / output rows through emap / omap.
 int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* eps, size_t eps_step_stride,
@@ -748,6 +787,7 @@ int spec_round_init(const fard_round_cfg* cfg, const fard_tensor* weights, int32
   if (c->bf16 && (hc.width % 64 != 0 || hc.d_cond % 64 != 0)) return bail(fail(c, FARD_ESHAPE, "bf16 head widths must be multiples of 64"));
   if (!(hc.sigma_last > 0.f)) return bail(fail(c, FARD_EINVAL, "sigma_last must be > 0"));
   c->m_max = cfg->max_batch * (cfg->K + 1);
+  c->m_rows = cfg->max_batch * std::max(cfg->K + 1, std::max(prefill_chunk(c, FARD_TARGET), prefill_chunk(c, FARD_DRAFT)));
 
   Loader ld;
   ld.c = c;
@@ -845,7 +885,7 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
   if (check_ctx(c)) return FARD_EINVAL;
   if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
   if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
-  if (M < 0 || M > c->m_max) return fail(c, FARD_ECAPACITY, "M > max_batch*(K+1)");
+  if (M < 0 || M > c->m_rows) return fail(c, FARD_ECAPACITY, "M beyond the workspace rows");
   if (B == 0 || M == 0) return FARD_OK;
   if (!x_in || !n_q || !z_out) return fail(c, FARD_EINVAL, "null x_in / n_q / z_out");
   Model& m = c->mdl[which];
@@ -885,6 +925,49 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
   if (commit) {
     HIPCHK(c, launch_len_add(s, m.len, n_q, 0, B));
     m.len_hi += cap;
+  }
+  return FARD_OK;
+}
+
+int spec_prefill(fard_ctx* c, int32_t which, const float* x, const int32_t* first_id, const int32_t* n, int32_t n_max,
+                 int32_t B, void* z_last) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (n_max < 0) return fail(c, FARD_EINVAL, "n_max < 0");
+  if (B == 0 || n_max == 0) return FARD_OK;
+  if (!x || !n) return fail(c, FARD_EINVAL, "null x / n");
+  Model& m = c->mdl[which];
+  if (first_id && !m.cond) return fail(c, FARD_EINVAL, "first_id given but the model has no id table");
+  int n_hi = 0;
+  for (int b = 0; b < B; ++b) {
+    if (n[b] < 0 || n[b] > n_max) return fail(c, FARD_EINVAL, "n[b] outside [0, n_max]");
+    n_hi = std::max(n_hi, n[b]);
+  }
+  if (n_hi == 0) return FARD_OK;
+  if (m.len_hi + n_hi > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "cache_len + n exceeds max_ctx");
+  if (m.c.pos == FARD_POS_LEARNED && m.len_hi + n_hi > m.c.max_pos) return fail(c, FARD_ECAPACITY, "position beyond the learned table");
+  hipStream_t s = c->stream;
+  HIPCHK(c, hipMemcpyAsync(c->pf_n, n, (size_t)B * 4, hipMemcpyHostToDevice, s));
+  HIPCHK(c, hipStreamSynchronize(s));      // the host array may go away after return
+  const int chunk = prefill_chunk(c, which), D = m.c.d_latent, ldz = m.d_out();
+  for (int c0 = 0; c0 < n_hi; c0 += chunk) {
+    const int cap = std::min(chunk, n_hi - c0);
+    int M = 0;
+    for (int b = 0; b < B; ++b) M += std::min(std::max(n[b] - c0, 0), cap);
+    { Bracket br(c, CLS_OTHER);
+      prefill_chunk_kernel<<<(B + 255) / 256, 256, 0, s>>>(c->pf_n, c0, cap, c->pf_nq, B);
+      HIPCHK(c, hipGetLastError());
+      prefill_pack_kernel<<<B, 64, 0, s>>>(x, n_max, D, c0, c->pf_nq, first_id, c->x_in, c->row_ids);
+      HIPCHK(c, hipGetLastError()); }
+    int rc = spec_forward(c, which, c->x_in, m.cond ? c->row_ids : nullptr, c->pf_nq, cap, B, M, 1, c->z, nullptr, nullptr);
+    if (rc) return rc;
+    if (z_last) {
+      Bracket br(c, CLS_OTHER);
+      if (c->bf16) prefill_last_kernel<bf16><<<B, 64, 0, s>>>((const bf16*)c->z, ldz, c->pf_n, c0, c->pf_nq, (bf16*)z_last);
+      else prefill_last_kernel<float><<<B, 64, 0, s>>>((const float*)c->z, ldz, c->pf_n, c0, c->pf_nq, (float*)z_last);
+      HIPCHK(c, hipGetLastError());
+    }
   }
   return FARD_OK;
 }

@@ -123,7 +123,8 @@ def test_capacity_and_argument_errors():
     with pytest.raises(FardError) as e:
         ctx.spec_kv_reset(0, np.full(B, case.rc.max_ctx + 1, np.int32))
     assert e.value.code == -3
-    big = ctx.dev_f32(np.zeros((case.rc.max_batch * (case.rc.K + 1) + 1, D), np.float32))
+    # the workspace holds max_batch * max(K + 1, rows of a prefill pass = 64 here) packed rows
+    big = ctx.dev_f32(np.zeros((case.rc.max_batch * 64 + 1, D), np.float32))
     ctx.spec_kv_reset(0, np.zeros(B, np.int32))
     with pytest.raises(FardError) as e:
         ctx.spec_forward(0, big, np.ones(B))
