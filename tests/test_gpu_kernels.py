@@ -32,7 +32,11 @@ def ctx_f32():
 @pytest.mark.parametrize("M,K,N", [(1, 64, 32), (5, 64, 32), (32, 128, 128), (33, 192, 96), (96, 256, 256),
                                    (97, 128, 160), (288, 1024, 1024), (72, 512, 2048), (200, 2048, 320),
                                    (288, 1024, 3072), (130, 768, 4096), (576, 1280, 3840), (65, 256, 64),
-                                   (2304, 1280, 3840), (500, 256, 12288)])
+                                   (2304, 1280, 3840), (500, 256, 12288),
+                                   # a thousand rows and more (prefill passes): ragged rows, few and ragged column
+                                   # blocks
+                                   (1025, 64, 32), (1100, 256, 96), (1300, 320, 160), (2048, 1024, 1024),
+                                   (4100, 128, 416)])
 @pytest.mark.parametrize("act", [0, 1, 2])
 def test_gemm_bf16_matches_fp64(ctx_bf16, M, K, N, act):
     from oracle import transformer as otf
