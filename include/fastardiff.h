@@ -266,6 +266,24 @@ int spec_gemm(fard_ctx* ctx, const void* A, const void* W, const float* bias, in
 int spec_gemm_narrow(fard_ctx* ctx, const void* A, const void* W, const float* bias, const float* gate,
                      int32_t M, int32_t K, int32_t N, int32_t epi, int32_t act, void* out);
 
+/* Training side of the draft model (Sec. 3, "Add feature-level entropy loss"; S2.1): the attention-entropy loss
+ *   L_entropy = (1 / (B N R)) sum_{b, heads, rows r, columns c} Omega_{r,c} ln Omega_{r,c}      (<= 0)
+ * of the causal attention maps Omega = softmax(q k^T / sqrt(d_head)) (row r sees columns 0..r; query head h reads kv
+ * head h / (H / H_kv)), and its gradients with respect to q and k.  Nothing of size R x R is written to memory.
+ *   q   storage type [B, H, R, d_head]        k   storage type [B, H_kv, R, d_head]   (bf16 contexts only; 16-byte aligned)
+ *   loss fp32 [1]      h_rows fp32 [B, H, R] row entropies H_r = -sum_c Omega ln Omega, or NULL
+ *   dq  fp32 like q, or NULL                  dk  fp32 like k, or NULL   (written, not accumulated)
+ * d_head in {32, 64, 128}.  Scratch grows inside the context (hipMalloc on first use or growth: not for capture).
+ * Errors: FARD_ESTATE in an fp32 context, FARD_ESHAPE for unsupported sizes, FARD_ENOMEM. */
+int spec_entropy_loss(fard_ctx* ctx, const void* q, const void* k, int32_t B, int32_t H, int32_t H_kv, int32_t R,
+                      int32_t d_head, float* loss, float* h_rows, float* dq, float* dk);
+
+/* The feature regression loss that the method keeps from EAGLE (Sec. 2, L_reg; Sec. 3 "Retain feature-level
+ * regression loss"): mean over n elements of 0.5 d^2 / beta (|d| < beta) or |d| - 0.5 beta, d = pred - target.
+ *   pred, target storage type [n]; loss fp32 [1]; dpred fp32 [n] = dloss/dpred, or NULL.  beta > 0. */
+int spec_smooth_l1(fard_ctx* ctx, const void* pred, const void* target, int64_t n, float beta, float* loss,
+                   float* dpred);
+
 /* Per-kernel timing with HIP events on the context's stream.  enable = 1 brackets every launch of
  * the named kernel class between two events; spec_profile_read synchronises and returns the
  * accumulated time (ms) and launch count since enable, then clears them.

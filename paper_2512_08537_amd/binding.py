@@ -70,6 +70,8 @@ _SIGS = {
     "spec_gemm": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
     "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp],
     "spec_graph_enable": [_vp, _i32],
+    "spec_entropy_loss": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
+    "spec_smooth_l1": [_vp, _vp, _vp, C.c_int64, _f32, _vp, _vp],
     "spec_prefill": [_vp, _i32, _vp, _vp, C.POINTER(C.c_int32), _i32, _i32, _vp],
     "spec_profile_enable": [_vp, _i32],
     "spec_profile_read": [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_double),
@@ -362,6 +364,26 @@ class Context:
         N = W.shape[1]
         self._chk(lib.spec_gemm_narrow(self.h, _ptr(A), _ptr(W), _ptr(bias), _ptr(gate), M, K, N, epi, act, _ptr(out)))
         return out
+
+    def spec_entropy_loss(self, q, k, want_rows=True, want_dq=True, want_dk=True):
+        """q: [B, H, R, dh], k: [B, Hkv, R, dh] device tensors of the storage type."""
+        t = self.torch
+        B, H, R, dh = q.shape
+        Hkv = k.shape[1]
+        loss = self.empty((1,), t.float32)
+        hr = self.empty((B, H, R), t.float32) if want_rows else None
+        dq = self.empty(tuple(q.shape), t.float32) if want_dq else None
+        dk = self.empty(tuple(k.shape), t.float32) if want_dk else None
+        self._chk(lib.spec_entropy_loss(self.h, _ptr(q), _ptr(k), B, H, Hkv, R, dh, _ptr(loss), _ptr(hr), _ptr(dq), _ptr(dk)))
+        return loss, hr, dq, dk
+
+    def spec_smooth_l1(self, pred, target, beta=1.0, want_grad=True):
+        t = self.torch
+        n = pred.numel()
+        loss = self.empty((1,), t.float32)
+        g = self.empty(tuple(pred.shape), t.float32) if want_grad else None
+        self._chk(lib.spec_smooth_l1(self.h, _ptr(pred), _ptr(target), n, float(beta), _ptr(loss), _ptr(g)))
+        return loss, g
 
     def spec_graph_enable(self, on: bool):
         self._chk(lib.spec_graph_enable(self.h, 1 if on else 0))

@@ -192,6 +192,8 @@ struct fard_ctx {
   int pend_n = 0;
   size_t pend_stride = 0;
   RoundGraph rgraph;
+  void* loss_tmp = nullptr;                // scratch of the training-side losses, grown on demand
+  size_t loss_tmp_bytes = 0;
   uint8_t* acc_tmp = nullptr;
   float *cz = nullptr, *hh = nullptr, *mod = nullptr, *xt = nullptr;
   void *sc = nullptr, *a1 = nullptr, *a2 = nullptr;
@@ -813,6 +815,7 @@ int spec_round_destroy(fard_ctx* c) {
   for (auto& ev : c->prof.pool) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
   c->rgraph.drop();
   if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
+  if (c->loss_tmp) (void)hipFree(c->loss_tmp);
   for (void* p : c->allocs) (void)hipFree(p);
   delete c;
   return FARD_OK;
@@ -969,6 +972,49 @@ int spec_prefill(fard_ctx* c, int32_t which, const float* x, const int32_t* firs
       HIPCHK(c, hipGetLastError());
     }
   }
+  return FARD_OK;
+}
+
+static int loss_scratch(fard_ctx* c, size_t bytes) {
+  if (bytes <= c->loss_tmp_bytes) return FARD_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (c->loss_tmp) (void)hipFree(c->loss_tmp);
+  c->loss_tmp = nullptr;
+  c->loss_tmp_bytes = 0;
+  if (hipMalloc(&c->loss_tmp, bytes) != hipSuccess) return fail(c, FARD_ENOMEM, "loss scratch hipMalloc failed");
+  c->loss_tmp_bytes = bytes;
+  return FARD_OK;
+}
+
+int spec_entropy_loss(fard_ctx* c, const void* q, const void* k, int32_t B, int32_t H, int32_t H_kv, int32_t R, int32_t d_head,
+                      float* loss, float* h_rows, float* dq, float* dk) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (!c->bf16) return fail(c, FARD_ESTATE, "spec_entropy_loss needs a bf16 context");
+  if (B < 1 || H < 1 || H_kv < 1 || R < 1 || H % H_kv != 0) return fail(c, FARD_ESHAPE, "B, H, H_kv, R >= 1 and H % H_kv == 0 required");
+  if (d_head != 32 && d_head != 64 && d_head != 128) return fail(c, FARD_ESHAPE, "d_head must be 32, 64 or 128");
+  if (!q || !k || !loss) return fail(c, FARD_EINVAL, "null argument");
+  if ((((uintptr_t)q) | ((uintptr_t)k)) & 15) return fail(c, FARD_EINVAL, "q and k must be 16-byte aligned");
+  const EntLossScratch lay = entropy_loss_scratch(B, H, H_kv, R, d_head);
+  int rc = loss_scratch(c, lay.bytes);
+  if (rc) return rc;
+  // score tiles: forward once, once more per gradient; second products: one per gradient
+  const double tiles = (double)B * H * 0.5 * R * (double)R;
+  const double fl = 2.0 * d_head * tiles * (1.0 + (dq ? 2.0 : 0.0) + (dk ? 2.0 : 0.0));
+  Bracket br(c, CLS_ATTN, fl, (double)B * (H + H_kv) * R * d_head * 2.0);
+  HIPCHK(c, launch_entropy_loss(c->stream, q, k, B, H, H_kv, R, d_head, c->loss_tmp, loss, h_rows, dq, dk));
+  return FARD_OK;
+}
+
+int spec_smooth_l1(fard_ctx* c, const void* pred, const void* target, int64_t n, float beta, float* loss, float* dpred) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (n < 1) return fail(c, FARD_ESHAPE, "n >= 1 required");
+  if (!(beta > 0.f)) return fail(c, FARD_EINVAL, "beta > 0 required");
+  if (!pred || !target || !loss) return fail(c, FARD_EINVAL, "null argument");
+  const int n_part = (int)std::min<int64_t>(1024, (n + 255) / 256);
+  int rc = loss_scratch(c, (size_t)n_part * 4);
+  if (rc) return rc;
+  Bracket br(c, CLS_OTHER);
+  HIPCHK(c, launch_smooth_l1(c->stream, c->bf16, pred, target, (long)n, beta, (float*)c->loss_tmp, n_part, loss, dpred));
   return FARD_OK;
 }
 

@@ -165,4 +165,18 @@ hipError_t launch_fill_f32(hipStream_t s, float* p, float v, size_t n);
 hipError_t launch_scatter_rows(hipStream_t s, const void* src, void* dst, const int* dmap, int width,
                                int elem_size, int n, const int* n_dev);
 
+// ---- training-side losses (losses.hip) -------------------------------------------------------------------
+// Byte offsets of the scratch areas of launch_entropy_loss inside one buffer of `bytes` bytes (256-byte aligned base).
+struct EntLossScratch {
+  size_t qT, kT, lse, hrow, bytes;
+};
+EntLossScratch entropy_loss_scratch(int B, int H, int Hkv, int R, int dh);
+// Attention-entropy loss of causal attention maps and its gradients.  q [B, H, R, dh], k [B, Hkv, R, dh] bf16;
+// loss fp32 [1]; h_rows fp32 [B, H, R] or null; dq fp32 like q or null; dk fp32 like k or null.  dh in {32, 64, 128}.
+hipError_t launch_entropy_loss(hipStream_t s, const void* q, const void* k, int B, int H, int Hkv, int R, int dh, void* scratch,
+                               float* loss, float* h_rows, float* dq, float* dk);
+// Smooth-L1 loss (mean over n elements) and its gradient; partial: n_part floats of scratch.
+hipError_t launch_smooth_l1(hipStream_t s, int is_bf16, const void* pred, const void* target, long n, float beta, float* partial,
+                            int n_part, float* loss, float* dpred);
+
 }  // namespace fard
