@@ -167,8 +167,9 @@ hipError_t launch_scatter_rows(hipStream_t s, const void* src, void* dst, const 
 
 // ---- training-side losses (losses.hip) -------------------------------------------------------------------
 // Byte offsets of the scratch areas of launch_entropy_loss inside one buffer of `bytes` bytes (256-byte aligned base).
+constexpr int ENT_LOSS_PARTS = 1024;      // partial sums of the loss reduction
 struct EntLossScratch {
-  size_t qT, kT, lse, hrow, bytes;
+  size_t qT, kT, lse, hrow, partial, bytes;
 };
 EntLossScratch entropy_loss_scratch(int B, int H, int Hkv, int R, int dh);
 // Attention-entropy loss of causal attention maps and its gradients.  q [B, H, R, dh], k [B, Hkv, R, dh] bf16;

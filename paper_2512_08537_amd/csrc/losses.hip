@@ -271,13 +271,14 @@ __global__ __launch_bounds__(256) void ent_dk_kernel(const bf16* __restrict__ q,
     }
 }
 
-// loss = -(sum of hrow over the valid rows) / n_rows; optionally copies the valid rows to h_out [BH, R].
-__global__ __launch_bounds__(256) void ent_loss_kernel(const float* __restrict__ hrow, int BH, int R, int Rp, float* __restrict__ loss,
-                                                       float* __restrict__ h_out) {
+// partial[blk] = sum of hrow over this workgroup's share of the valid rows (fixed order); optionally copies the valid
+// rows to h_out [BH, R].  sum_partials_kernel turns the partial sums into the loss.
+__global__ __launch_bounds__(256) void ent_loss_kernel(const float* __restrict__ hrow, int BH, int R, int Rp,
+                                                       float* __restrict__ partial, float* __restrict__ h_out) {
   __shared__ float part[4];
   float s = 0.f;
   const long n = (long)BH * R;
-  for (long i = threadIdx.x; i < n; i += 256) {
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) {
     const long bh = i / R, r = i - bh * R;
     const float v = hrow[bh * Rp + r];
     if (h_out) h_out[i] = v;
@@ -286,7 +287,7 @@ __global__ __launch_bounds__(256) void ent_loss_kernel(const float* __restrict__
   s = wave_sum(s);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
   __syncthreads();
-  if (threadIdx.x == 0) *loss = -(part[0] + part[1] + part[2] + part[3]) / (float)n;
+  if (threadIdx.x == 0) partial[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
 }
 
 // Smooth-L1: per-workgroup partial sums (fixed order), gradient per element.
@@ -328,7 +329,11 @@ hipError_t entropy_loss_t(hipStream_t s, const bf16* q, const bf16* k, int B, in
   const float cc = scale / ((float)B * (float)H * (float)R);
   const int wq = B * H * nb, wk = B * Hkv * nb;
   ent_stats_kernel<DH><<<(wq + 3) / 4, 256, 0, s>>>(q, k, H, Hkv, R, Rp, wq, scale, lse, hrow);
-  ent_loss_kernel<<<1, 256, 0, s>>>(hrow, B * H, R, Rp, loss, h_rows);
+  float* partial = (float*)(base + lay.partial);
+  const long n_rows = (long)B * H * R;
+  const int n_part = (int)((n_rows + 1023) / 1024 < ENT_LOSS_PARTS ? (n_rows + 1023) / 1024 : ENT_LOSS_PARTS);
+  ent_loss_kernel<<<n_part, 256, 0, s>>>(hrow, B * H, R, Rp, partial, h_rows);
+  sum_partials_kernel<<<1, 64, 0, s>>>(partial, n_part, -1.0f / (float)n_rows, loss);
   if (dq) {
     transpose_kernel<<<dim3(nb, DH / 32, B * Hkv), 256, 0, s>>>(k, kT, R, Rp, DH);
     ent_dq_kernel<DH><<<(wq + 3) / 4, 256, 0, s>>>(q, k, kT, H, Hkv, R, Rp, wq, scale, cc, lse, hrow, dq);
@@ -349,7 +354,8 @@ EntLossScratch entropy_loss_scratch(int B, int H, int Hkv, int R, int dh) {
   l.kT = l.qT + (size_t)B * H * dh * Rp * 2;
   l.lse = l.kT + (size_t)B * Hkv * dh * Rp * 2;
   l.hrow = l.lse + (size_t)B * H * Rp * 4;
-  l.bytes = l.hrow + (size_t)B * H * Rp * 4;
+  l.partial = l.hrow + (size_t)B * H * Rp * 4;
+  l.bytes = l.partial + (size_t)ENT_LOSS_PARTS * 4;
   return l;
 }
 

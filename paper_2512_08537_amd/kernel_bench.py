@@ -3,6 +3,7 @@
 
   python -m paper_2512_08537_amd.kernel_bench entropy     # entropy pre-filter: config shapes + 2^20-row shape
   python -m paper_2512_08537_amd.kernel_bench narrow      # narrow-tile GEMM launches (time them with rocprofv3 --kernel-trace)
+  python -m paper_2512_08537_amd.kernel_bench losses      # attention-entropy loss + gradients at training shapes
   python -m paper_2512_08537_amd.kernel_bench copy        # 256 MiB copy: calibration of the HBM traffic counters
 
 Prints one JSON line per measurement: algorithmic bytes / HIP-event time on the library's stream.
@@ -87,6 +88,35 @@ def copy():
     print(json.dumps({"kernel": "torch copy_", "bytes_read": n * 4, "bytes_written": n * 4, "launches": 5}), flush=True)
 
 
+def losses():
+    """The attention-entropy loss with both gradients at the draft's training shapes (batch x heads x sequence x head
+    dim); flops = score tiles (forward, and once more per gradient) + the two second products, causal half only."""
+    import torch
+    from tests.harness import build_case, make_ctx
+    case = build_case("ln-gelu-bf16", seed=0)
+    ctx = make_ctx(case)
+    for (B, H, Hkv, R, dh) in [(32, 16, 16, 256, 64), (64, 20, 20, 256, 64), (8, 16, 16, 1024, 64), (8, 40, 8, 1024, 128)]:
+        g = torch.Generator(device="cuda").manual_seed(0)
+        q = torch.randn((B, H, R, dh), generator=g, device="cuda").to(torch.bfloat16)
+        k = torch.randn((B, Hkv, R, dh), generator=g, device="cuda").to(torch.bfloat16)
+        torch.cuda.synchronize()
+        for _ in range(2):
+            out = ctx.spec_entropy_loss(q, k)
+        ctx.sync()
+        ctx.spec_profile_enable(True)
+        iters = 10
+        for _ in range(iters):
+            out = ctx.spec_entropy_loss(q, k)
+        p = ctx.spec_profile_read(1)
+        ctx.spec_profile_enable(False)
+        us = p["ms"] / iters * 1e3
+        tf = p["flops"] / (p["ms"] * 1e-3) / 1e12
+        print(json.dumps({"kernel": "spec_entropy_loss (statistics, dq, dk passes + two transposes)", "B": B, "H": H, "H_kv": Hkv, "R": R,
+                          "d_head": dh, "us_per_call": round(us, 1), "flops": p["flops"] / iters, "achieved_TFLOPs": round(tf, 1),
+                          "frac_mfma": round(tf / 2500.0, 4), "loss": round(float(out[0].item()), 5)}), flush=True)
+    ctx.close()
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "entropy"
-    {"entropy": entropy, "narrow": narrow, "copy": copy}[what]()
+    {"entropy": entropy, "narrow": narrow, "copy": copy, "losses": losses}[what]()

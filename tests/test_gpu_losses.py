@@ -34,6 +34,7 @@ def _inputs(seed, B, H, Hkv, R, dh, std):
     (2, 5, 1, 70, 128, 0.7),        # 5:1 groups, head dim 128
     (3, 4, 4, 256, 64, 1.2),        # several tiles, the sequence length of the 256-token setting
     (1, 2, 2, 300, 64, 2.0),        # peaky rows
+    (32, 16, 16, 256, 64, 1.0),     # the shape kernel_bench times (draft of configs[1]: 16 heads, 256 tokens)
 ])
 def test_entropy_loss_and_gradients_match_oracle(ctx, B, H, Hkv, R, dh, std):
     from oracle import losses
