@@ -261,10 +261,22 @@ int spec_gemm(fard_ctx* ctx, const void* A, const void* W, const float* bias, in
  * bias fp32 [N] or NULL; M <= 1024, K % 64 == 0, N % 32 == 0.
  *   epi 0  out storage type [M,N] = act(A W + bias);   1: the same, out fp32
  *   epi 2  out fp32 [M,N] += A W + bias;   3: out fp32 [M,N] += gate[m,n] * (A W + bias), gate fp32 [M,N]
+ *   out_bf16 (epi 2, 3 only; or NULL): the updated out is also stored as bf16 [M,N] there.
  * K is never split: no atomics, results are deterministic.
  * Errors: FARD_ESHAPE for sizes outside the limits above, FARD_EINVAL for bad selectors or NULLs. */
 int spec_gemm_narrow(fard_ctx* ctx, const void* A, const void* W, const float* bias, const float* gate,
-                     int32_t M, int32_t K, int32_t N, int32_t epi, int32_t act, void* out);
+                     int32_t M, int32_t K, int32_t N, int32_t epi, int32_t act, void* out, void* out_bf16);
+
+/* The norm of Sec. 3.1's transformer blocks folded into the GEMM that follows it (how the round runs the second norm
+ * of a block without a launch of its own): out = act(norm(x) W + bias), norm(x)_k = g_k (x_k - mean) rstd + beta_k
+ * (LayerNorm, norm_type 0; beta NULL = 0) or g_k x_k rstd (RMSNorm, norm_type 1), statistics over the K entries of a
+ * row.  Computed as rstd (x W' - mean colsum(W')) + (bias + beta W) with W' = diag(g) W rounded to bf16: the row
+ * statistics are summed from the bf16 activation fragments on their way into the matrix cores.
+ *   x bf16 [M, K] (the raw rows); W bf16 [K, N] row-major; g, beta fp32 [K]; bias fp32 [N] or NULL; out bf16 [M, N].
+ *   M <= 1024, K % 64 == 0, N % 32 == 0; act 0 none, 1 GELU, 2 SiLU.  bf16 contexts only. */
+int spec_gemm_norm(fard_ctx* ctx, const void* x, const void* W, const float* g, const float* beta,
+                   const float* bias, int32_t M, int32_t K, int32_t N, int32_t norm_type, float eps, int32_t act,
+                   void* out);
 
 /* Training side of the draft model (Sec. 3, "Add feature-level entropy loss"; S2.1): the attention-entropy loss
  *   L_entropy = (1 / (B N R)) sum_{b, heads, rows r, columns c} Omega_{r,c} ln Omega_{r,c}      (<= 0)

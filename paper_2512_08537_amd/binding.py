@@ -68,7 +68,8 @@ _SIGS = {
     "spec_generate": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp,
                       _vp],
     "spec_gemm": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp],
-    "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp],
+    "spec_gemm_narrow": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp],
+    "spec_gemm_norm": [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _f32, _i32, _vp],
     "spec_graph_enable": [_vp, _i32],
     "spec_entropy_loss": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "spec_smooth_l1": [_vp, _vp, _vp, C.c_int64, _f32, _vp, _vp],
@@ -358,11 +359,20 @@ class Context:
         self._chk(lib.spec_gemm(self.h, _ptr(A), _ptr(W), _ptr(bias), M, K, N, act, _ptr(out)))
         return out
 
-    def spec_gemm_narrow(self, A, W, out, bias=None, gate=None, epi=0, act=0):
+    def spec_gemm_narrow(self, A, W, out, bias=None, gate=None, epi=0, act=0, out_bf16=None):
         """`out` is written (epi 0, 1) or accumulated into (epi 2, 3) in place and returned."""
         M, K = A.shape
         N = W.shape[1]
-        self._chk(lib.spec_gemm_narrow(self.h, _ptr(A), _ptr(W), _ptr(bias), _ptr(gate), M, K, N, epi, act, _ptr(out)))
+        self._chk(lib.spec_gemm_narrow(self.h, _ptr(A), _ptr(W), _ptr(bias), _ptr(gate), M, K, N, epi, act, _ptr(out),
+                                       _ptr(out_bf16)))
+        return out
+
+    def spec_gemm_norm(self, x, W, g, beta=None, bias=None, norm_type=0, eps=1e-5, act=0):
+        M, K = x.shape
+        N = W.shape[1]
+        out = self.empty((M, N), self.torch.bfloat16)
+        self._chk(lib.spec_gemm_norm(self.h, _ptr(x), _ptr(W), _ptr(g), _ptr(beta), _ptr(bias), M, K, N, norm_type, float(eps),
+                                     act, _ptr(out)))
         return out
 
     def spec_entropy_loss(self, q, k, want_rows=True, want_dq=True, want_dk=True):

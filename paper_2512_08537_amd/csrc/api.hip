@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -82,6 +83,25 @@ __global__ __launch_bounds__(64) void prefill_last_kernel(const T* __restrict__ 
   for (int o = 32; o > 0; o >>= 1) start += __shfl_xor(start, o, 64);
   for (int k = lane; k < ldz; k += 64) z_last[(size_t)b * ldz + k] = z[(size_t)(start + cnt - 1) * ldz + k];
 }
+// Folding a norm's affine part into the GEMM that follows it: scaled[k, n] = bf16(g[k] w[k, n]),
+// cs[n] = sum_k scaled[k, n], bf[n] = b0[n] + sum_k beta[k] w[k, n].  One thread per column.
+template <typename TS>
+__global__ void ln_fold_kernel(const TS* __restrict__ w, const float* __restrict__ g, const float* __restrict__ beta,
+                               const float* __restrict__ b0, int K, int N, bf16* __restrict__ scaled, float* __restrict__ cs,
+                               float* __restrict__ bf) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float c = 0.f, bb = b0 ? b0[n] : 0.f;
+  for (int k = 0; k < K; ++k) {
+    const float wv = to_f32(w[(size_t)k * N + n]);
+    const bf16 ws = (bf16)(g[k] * wv);
+    scaled[(size_t)k * N + n] = ws;
+    c += (float)ws;
+    if (beta) bb = fmaf(beta[k], wv, bb);
+  }
+  cs[n] = c;
+  bf[n] = bb;
+}
 __global__ void temb_feat_kernel(float t, float t_scale, int half, float* out) {
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k < half) {
@@ -106,6 +126,9 @@ struct LayerW {
   float *n1g = nullptr, *n1b = nullptr, *n2g = nullptr, *n2b = nullptr;
   void *wqkv = nullptr, *wo = nullptr, *w1 = nullptr, *w2 = nullptr;   // w1 = up (GELU) or gate|up (SwiGLU), w2 = down
   float *bqkv = nullptr, *bo = nullptr, *b1 = nullptr, *b2 = nullptr;
+  // norm 2 folded into the up-projection (bf16, GELU layers): diag(n2g) w1 packed, its column sums, b1 + n2b w1
+  void* w1f = nullptr;
+  float *cs1 = nullptr, *b1f = nullptr;
 };
 struct Model {
   fard_tf_cfg c;
@@ -376,6 +399,31 @@ struct Loader {
   }
 };
 
+// w1f / cs1 / b1f of a layer (see LayerW) from the layer's w1 [K, N], norm gain g, norm bias beta (or null), b1 (or null).
+int fold_norm_into(fard_ctx* c, Loader& ld, const std::string& name, int K, int N, const float* g, const float* beta,
+                   const float* b0, void** w_out, float** cs_out, float** bf_out) {
+  const fard_tensor* t;
+  int rc = ld.need(name, (int64_t)K * N, &t);
+  if (rc) return rc;
+  const void* src;
+  if ((rc = ld.device_src(t, &src))) return rc;
+  void* scaled = nullptr;
+  if (hipMalloc(&scaled, (size_t)K * N * 2) != hipSuccess) return fail(c, FARD_ENOMEM, "staging hipMalloc failed");
+  ld.staging.push_back(scaled);
+  if ((rc = dalloc_bytes(c, w_out, (size_t)K * N * 2)) || (rc = dalloc<float>(c, cs_out, (size_t)N)) ||
+      (rc = dalloc<float>(c, bf_out, (size_t)N)))
+    return rc;
+  const unsigned blocks = (unsigned)((N + 127) / 128);
+  if (t->dtype == FARD_BF16)
+    ln_fold_kernel<bf16><<<blocks, 128, 0, c->stream>>>((const bf16*)src, g, beta, b0, K, N, (bf16*)scaled, *cs_out, *bf_out);
+  else
+    ln_fold_kernel<float><<<blocks, 128, 0, c->stream>>>((const float*)src, g, beta, b0, K, N, (bf16*)scaled, *cs_out, *bf_out);
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, launch_pack_weight(c->stream, scaled, 1, N, K, N, *w_out, 0, 1));
+  if (ld.staging.size() > 8) ld.release_staging();
+  return FARD_OK;
+}
+
 int check_tf(fard_ctx* c, const fard_tf_cfg& t, const char* who) {
   std::string w(who);
   if (t.n_layers < 1 || t.d_model < 1 || t.n_heads < 1 || t.n_kv_heads < 1 || t.d_head < 1 || t.d_ff < 1 || t.d_latent < 1)
@@ -430,6 +478,8 @@ int load_model(fard_ctx* c, Loader& ld, int which) {
         if ((rc = ld.vec(q + "b1", F, 0.f, false, &L.b1))) return rc;
         if ((rc = ld.vec(q + "b2", d, 0.f, false, &L.b2))) return rc;
       }
+      if (c->bf16 && (rc = fold_norm_into(c, ld, q + "w1", d, F, L.n2g, ln ? L.n2b : nullptr, L.b1, &L.w1f, &L.cs1, &L.b1f)))
+        return rc;
     } else {
       if ((rc = ld.gemm_weight({q + "wg", q + "wu"}, d, {F, F}, true, &L.w1))) return rc;
       if ((rc = ld.gemm_weight({q + "wd"}, F, {d}, false, &L.w2))) return rc;
@@ -455,23 +505,42 @@ int load_model(fard_ctx* c, Loader& ld, int which) {
   return FARD_OK;
 }
 
+// Which GEMMs of the bf16 path go to the narrow-tile kernel (no K split, no atomics, any epilogue).
+bool routes_narrow(int M, int N, int K, int epi) {
+  if (epi == EPI_SWIGLU || N % 32 != 0 || K % 64 != 0 || M < 1) return false;
+  // a few dozen rows against a weight matrix that 16-column tiles spread over enough workgroups: the
+  // narrow-tile kernel finishes in one memory round trip
+  if (M <= 64 && K <= 2048 && N <= 8192) return true;
+  // a few hundred rows against a small square-ish matrix: still ahead of the split-K kernels (measured)
+  if (M <= 640 && K <= 1536 && N <= 1536) return true;
+  // ... or a wide one with a store epilogue, through 64-column workgroups
+  if (M <= 640 && K <= 1024 && N <= 8192 && N % 64 == 0 && (epi == EPI_STORE || epi == EPI_STORE_F32)) return true;
+  return false;
+}
+
+// Extras of the narrow kernel: a bf16 copy of a residual update; the preceding norm applied in the epilogue.
+struct GemmExtra {
+  void* copy_bf16 = nullptr;
+  const float* ln_cs = nullptr;
+  float ln_eps = 0.f;
+  int ln_rms = 0;
+};
+
 hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, void* out, int ldo, int M,
-                int N, int K, const int* m_dev, int epi, int act, const float* gate = nullptr, int ldg = 0) {
+                int N, int K, const int* m_dev, int epi, int act, const float* gate = nullptr, int ldg = 0,
+                const GemmExtra* ex = nullptr) {
   GemmArgs a;
   a.A = A; a.lda = lda; a.W = W; a.bias = bias; a.out = out; a.ldo = ldo; a.gate = gate; a.ldg = ldg;
   a.M = M; a.N = N; a.K = K; a.m_dev = m_dev; a.act = act; a.epi = epi;
+  if (ex) {
+    if (!c->bf16 || !routes_narrow(M, N, K, epi)) return hipErrorInvalidValue;   // only the narrow kernel has them
+    a.copy_bf16 = ex->copy_bf16; a.ln_cs = ex->ln_cs; a.ln_eps = ex->ln_eps; a.ln_rms = ex->ln_rms;
+  }
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
   Bracket br(c, CLS_GEMM, fl, by);
   if (!c->bf16) return launch_gemm_f32(c->stream, a);
-  // a few dozen rows against a weight matrix that 16-column tiles spread over enough workgroups: the
-  // narrow-tile kernel finishes in one memory round trip, without atomics
-  if (M <= 64 && K <= 2048 && N <= 8192 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
-  // a few hundred rows against a small square-ish matrix: still ahead of the split-K kernels (measured)
-  if (M <= 640 && K <= 1536 && N <= 1536 && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
-  // ... or a wide one with a store epilogue, through 64-column workgroups
-  if (M <= 640 && K <= 1024 && N <= 8192 && N % 64 == 0 && (epi == EPI_STORE || epi == EPI_STORE_F32) && narrow_supported(a))
-    return launch_gemm_narrow(c->stream, a);
+  if (routes_narrow(M, N, K, epi) && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
   return launch_gemm_bf16(c->stream, a);
 }
 
@@ -668,13 +737,26 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
     { Bracket br(c, CLS_ATTN);
       HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, m.len, c->maps.row_start, B, nq_max, c->ao, HD,
                                  (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0)); }
-    HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
-    { Bracket br(c, CLS_OTHER);
-      HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u)); }
-    if (t.act == FARD_ACT_GELU) {
-      HIPCHK(c, gemm(c, c->u, d, L.w1, L.b1, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU));
+    // norm 2 without a launch of its own, when both GEMMs around it run in the narrow kernel: the output
+    // projection also leaves the updated stream as bf16, and the up-projection (weights pre-scaled by the norm's
+    // gain) sums the row statistics from its activation fragments and applies them in its epilogue
+    const bool fold2 = c->bf16 && L.w1f != nullptr && t.act == FARD_ACT_GELU && routes_narrow(M, d, HD, EPI_RESID) &&
+                       routes_narrow(M, F, d, EPI_STORE);
+    if (fold2) {
+      GemmExtra ex_o, ex_1;
+      ex_o.copy_bf16 = c->u;
+      HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE, nullptr, 0, &ex_o));
+      ex_1.ln_cs = L.cs1; ex_1.ln_eps = t.norm_eps; ex_1.ln_rms = t.norm == FARD_NORM_RMS;
+      HIPCHK(c, gemm(c, c->u, d, L.w1f, L.b1f, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU, nullptr, 0, &ex_1));
     } else {
-      HIPCHK(c, gemm(c, c->u, d, L.w1, nullptr, c->ff, F, M, 2 * F, d, m_dev, EPI_SWIGLU, ACT_NONE));
+      HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
+      { Bracket br(c, CLS_OTHER);
+        HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u)); }
+      if (t.act == FARD_ACT_GELU) {
+        HIPCHK(c, gemm(c, c->u, d, L.w1, L.b1, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU));
+      } else {
+        HIPCHK(c, gemm(c, c->u, d, L.w1, nullptr, c->ff, F, M, 2 * F, d, m_dev, EPI_SWIGLU, ACT_NONE));
+      }
     }
     if (parts_eligible(c, M, d, F)) HIPCHK(c, gemm_parts(c, c->ff, F, L.w2, L.b2, M, d, F, m_dev));
     else HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
@@ -1344,7 +1426,7 @@ int spec_gemm(fard_ctx* c, const void* A, const void* W, const float* bias, int3
 }
 
 int spec_gemm_narrow(fard_ctx* c, const void* A, const void* W, const float* bias, const float* gate, int32_t M,
-                     int32_t K, int32_t N, int32_t epi, int32_t act, void* out) {
+                     int32_t K, int32_t N, int32_t epi, int32_t act, void* out, void* out_bf16) {
   if (check_ctx(c)) return FARD_EINVAL;
   if (!c->bf16) return fail(c, FARD_EINVAL, "spec_gemm_narrow needs a bf16 context");
   if (M < 0 || K < 1 || N < 1) return fail(c, FARD_ESHAPE, "M >= 0, K, N >= 1 required");
@@ -1352,9 +1434,11 @@ int spec_gemm_narrow(fard_ctx* c, const void* A, const void* W, const float* bia
   if (!A || !W || !out) return fail(c, FARD_EINVAL, "null argument");
   if (act < 0 || act > 2 || epi < 0 || epi > 3) return fail(c, FARD_EINVAL, "selector");
   if (epi == 3 && !gate) return fail(c, FARD_EINVAL, "epi 3 needs gate");
+  if (out_bf16 && epi < 2) return fail(c, FARD_EINVAL, "out_bf16 goes with epi 2 or 3");
   GemmArgs a;
   a.A = A; a.lda = K; a.W = nullptr; a.bias = bias; a.out = out; a.ldo = N; a.gate = gate; a.ldg = N;
   a.M = M; a.N = N; a.K = K; a.m_dev = nullptr; a.act = act; a.epi = epi;
+  a.copy_bf16 = out_bf16;
   if (!narrow_supported(a) || M > 1024) return fail(c, FARD_ESHAPE, "narrow GEMM needs M <= 1024, K % 64 == 0, N % 32 == 0");
   const size_t bytes = (size_t)K * N * 2;
   if (bytes > c->gemm_tmp_bytes) {
@@ -1367,6 +1451,44 @@ int spec_gemm_narrow(fard_ctx* c, const void* A, const void* W, const float* bia
   }
   HIPCHK(c, launch_pack_weight(c->stream, W, 1, N, K, N, c->gemm_tmp, 0, 1));
   a.W = c->gemm_tmp;
+  { Bracket br(c, CLS_GEMM, 2.0 * M * (double)N * K, (double)K * N * 2);
+    HIPCHK(c, launch_gemm_narrow(c->stream, a)); }
+  return FARD_OK;
+}
+
+int spec_gemm_norm(fard_ctx* c, const void* x, const void* W, const float* g, const float* beta, const float* bias, int32_t M,
+                   int32_t K, int32_t N, int32_t norm_type, float eps, int32_t act, void* out) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (!c->bf16) return fail(c, FARD_EINVAL, "spec_gemm_norm needs a bf16 context");
+  if (M < 0 || K < 1 || N < 1) return fail(c, FARD_ESHAPE, "M >= 0, K, N >= 1 required");
+  if (M == 0) return FARD_OK;
+  if (!x || !W || !g || !out) return fail(c, FARD_EINVAL, "null argument");
+  if (act < 0 || act > 2 || (norm_type != FARD_NORM_LAYER && norm_type != FARD_NORM_RMS)) return fail(c, FARD_EINVAL, "selector");
+  if (K % 64 != 0 || N % 32 != 0 || M > 1024) return fail(c, FARD_ESHAPE, "needs M <= 1024, K % 64 == 0, N % 32 == 0");
+  // scratch: diag(g) W as bf16 [K, N], its packed form, column sums and folded bias
+  const size_t wbytes = (size_t)K * N * 2, bytes = 2 * wbytes + (size_t)N * 8 + 256;
+  if (bytes > c->gemm_tmp_bytes) {
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
+    c->gemm_tmp = nullptr;
+    c->gemm_tmp_bytes = 0;
+    HIPCHK(c, hipMalloc(&c->gemm_tmp, bytes));
+    c->gemm_tmp_bytes = bytes;
+  }
+  char* base = (char*)c->gemm_tmp;
+  bf16* scaled = (bf16*)base;
+  void* packed = base + wbytes;
+  float* cs = (float*)(base + 2 * wbytes);
+  float* bf = cs + N;
+  ln_fold_kernel<bf16><<<(N + 127) / 128, 128, 0, c->stream>>>((const bf16*)W, g, norm_type == FARD_NORM_LAYER ? beta : nullptr, bias,
+                                                             K, N, scaled, cs, bf);
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, launch_pack_weight(c->stream, scaled, 1, N, K, N, packed, 0, 1));
+  GemmArgs a;
+  a.A = x; a.lda = K; a.W = packed; a.bias = bf; a.out = out; a.ldo = N; a.gate = nullptr; a.ldg = 0;
+  a.M = M; a.N = N; a.K = K; a.m_dev = nullptr; a.act = act; a.epi = EPI_STORE;
+  a.ln_cs = cs; a.ln_eps = eps; a.ln_rms = norm_type == FARD_NORM_RMS;
+  if (!narrow_supported(a)) return fail(c, FARD_ESHAPE, "unsupported shape");
   { Bracket br(c, CLS_GEMM, 2.0 * M * (double)N * K, (double)K * N * 2);
     HIPCHK(c, launch_gemm_narrow(c->stream, a)); }
   return FARD_OK;

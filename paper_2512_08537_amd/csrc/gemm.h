@@ -30,6 +30,13 @@ struct GemmArgs {
   int epi;
   int k_slices = 1;    // EPI_PARTIAL: K slices (blockIdx.z), plane z at out + z * part_stride
   size_t part_stride = 0;
+  // narrow kernel only:
+  void* copy_bf16 = nullptr;       // EPI_RESID / EPI_GATE_RESID: the updated values are also stored as bf16 [M, ldo] here
+  const float* ln_cs = nullptr;    // non-null: A holds the raw rows x and W = diag(g) W0; the epilogue applies the norm
+                                   // of the rows, rstd_r (acc - mean_r ln_cs[n]) + bias[n], with ln_cs[n] = sum_k W[k, n]
+                                   // and bias = b0 + beta W0 folded by the caller; statistics come from the A fragments
+  float ln_eps = 0.f;
+  int ln_rms = 0;                  // 1: RMS norm (no mean)
 };
 
 // Packed bf16 weight size in elements for a [K, N] matrix (K % 16 == 0, N % 32 == 0).

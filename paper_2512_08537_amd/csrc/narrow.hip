@@ -32,7 +32,7 @@ struct NarrowEpi {
   static constexpr int RPP = 256 / CG;                     // rows per pass
   static constexpr int EP = (16 * MT + RPP - 1) / RPP;     // passes
   static constexpr int LDT = 16 * NT + 4;                  // floats per row of a partial tile in LDS
-  f32x4 gate[EP], old[EP], bias4;
+  f32x4 gate[EP], old[EP], bias4, cs4;
   int er, ec;
   __device__ __forceinline__ void prefetch(const GemmArgs& a, int M, int m0, int n0) {
     er = threadIdx.x / CG;
@@ -49,9 +49,13 @@ struct NarrowEpi {
       if (rmw) old[i] = *(const f32x4*)((const float*)a.out + (size_t)r * a.ldo + n0 + ec);
     }
     if (a.bias != nullptr && blockIdx.z == 0) bias4 = *(const f32x4*)(a.bias + n0 + ec);
+    cs4 = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (a.ln_cs != nullptr) cs4 = *(const f32x4*)(a.ln_cs + n0 + ec);
   }
-  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT][NT], float* red, int M, int m0,
-                                         int n0) {
+  // LNF: stat holds the 4 waves' (sum x, sum x^2) of every row of the tile, over their shares of K
+  template <bool LNF>
+  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT][NT], float* red, const float* stat, int M,
+                                         int m0, int n0) {
     const int lane = threadIdx.x & 63, kw = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -65,9 +69,23 @@ struct NarrowEpi {
     for (int i = 0; i < EP; ++i) {
       const int row = er + RPP * i;
       if (m0 + row >= M || row >= 16 * MT) continue;
-      f32x4 v = bias4;
+      f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int k = 0; k < 4; ++k) v += *(const f32x4*)(red + (k * 16 * MT + row) * LDT + ec);
+      if constexpr (LNF) {
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          s1 += stat[(k * 16 * MT + row) * 2];
+          s2 += stat[(k * 16 * MT + row) * 2 + 1];
+        }
+        const float inv_k = 1.0f / (float)a.K;
+        const float mean = a.ln_rms ? 0.f : s1 * inv_k;
+        const float var = fmaxf(s2 * inv_k - mean * mean, 0.f);
+        const float rstd = rsqrtf(var + a.ln_eps);
+        v = (v - cs4 * mean) * rstd;
+      }
+      v += bias4;
       const size_t o = (size_t)(m0 + row) * a.ldo + n0 + ec;
       if (a.epi == EPI_STORE) {
         bf16x4 t;
@@ -81,7 +99,14 @@ struct NarrowEpi {
       } else if (a.epi == EPI_PARTIAL) {
         *(f32x4*)((float*)a.out + (size_t)blockIdx.z * a.part_stride + o) = v;
       } else {
-        *(f32x4*)((float*)a.out + o) = old[i] + gate[i] * v;
+        const f32x4 nv = old[i] + gate[i] * v;
+        *(f32x4*)((float*)a.out + o) = nv;
+        if (a.copy_bf16 != nullptr) {
+          bf16x4 t;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) t[e] = (bf16)nv[e];
+          *(bf16x4*)((bf16*)a.copy_bf16 + o) = t;
+        }
       }
     }
   }
@@ -89,10 +114,13 @@ struct NarrowEpi {
 
 // MT x NT: 16x16 output tiles of the workgroup (rows x columns).  NS: k-steps per operand a wave keeps in
 // flight (its whole K range when ONESHOT).
-template <int MT, int NT, int NS, bool ONESHOT>
-__global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
+// LNF: the norm of the rows is applied in the epilogue (GemmArgs::ln_cs); the row statistics are summed from the
+// activation fragments on their way into the MFMAs.
+template <int MT, int NT, int NS, bool ONESHOT, bool LNF>
+__global__ __launch_bounds__(256, (LNF && NS == 8) ? 2 : 1) void gemm_narrow_kernel(GemmArgs a) {   // (the statistics must
+  // not cost the 32 x 64 tile its second workgroup per compute unit: 16 registers over the limit otherwise)
   using Epi = NarrowEpi<MT, NT>;
-  extern __shared__ __attribute__((aligned(16))) float red[];   // 4 * 16 * MT * Epi::LDT floats
+  extern __shared__ __attribute__((aligned(16))) float red[];   // 4 * 16 * MT * Epi::LDT floats (+ 4 * 16 * MT * 2 if LNF)
   const int M = eff_rows(a.M, a.m_dev);
   const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
   if (m0 >= M) return;
@@ -145,10 +173,21 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
   bf16x8 zero8;
 #pragma unroll
   for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
+  float s1[MT], s2[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) s1[i] = s2[i] = 0.f;
   auto step = [&](int g, bool live) {
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
       const bf16x8 af = live ? areg[g][i] : zero8;
+      if constexpr (LNF) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float x = (float)af[e];
+          s1[i] += x;
+          s2[i] = fmaf(x, x, s2[i]);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, breg[g][j], acc[i][j], 0, 0, 0);
     }
@@ -167,13 +206,29 @@ __global__ __launch_bounds__(256) void gemm_narrow_kernel(GemmArgs a) {
     }
   }
 
-  epi.finish(a, acc, red, M, m0, n0);
+  float* stat = red + 4 * 16 * MT * Epi::LDT;
+  if constexpr (LNF) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      s1[i] += __shfl_xor(s1[i], 16, WAVE);
+      s1[i] += __shfl_xor(s1[i], 32, WAVE);
+      s2[i] += __shfl_xor(s2[i], 16, WAVE);
+      s2[i] += __shfl_xor(s2[i], 32, WAVE);
+      if (lane < 16) {
+        stat[(kw * 16 * MT + 16 * i + lane) * 2] = s1[i];
+        stat[(kw * 16 * MT + 16 * i + lane) * 2 + 1] = s2[i];
+      }
+    }
+  }
+  epi.template finish<LNF>(a, acc, red, stat, M, m0, n0);
 }
 
 }  // namespace
 
 bool narrow_supported(const GemmArgs& a) {
   if (a.epi == EPI_PARTIAL && (a.k_slices < 1 || a.k_slices > 64 || (a.k_slices > 1 && a.part_stride < (size_t)a.M * a.ldo))) return false;
+  if (a.ln_cs != nullptr && (a.epi == EPI_PARTIAL || a.k_slices > 1)) return false;
+  if (a.copy_bf16 != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
   return a.M >= 1 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
 }
 
@@ -183,19 +238,24 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   const int steps = ((a.K / 32 + kz - 1) / kz + 3) / 4;      // 32-k steps of the busiest wave
   // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
   // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
-#define FARD_NR(MTV, NTV, NSV, ONE)                                                                        \
+#define FARD_NR_L(MTV, NTV, NSV, ONE, LNFV)                                                                \
   do {                                                                                                     \
-    constexpr size_t lds = (size_t)4 * 16 * MTV * (16 * NTV + 4) * sizeof(float);                          \
+    constexpr size_t lds = (size_t)4 * 16 * MTV * (16 * NTV + 4 + (LNFV ? 2 : 0)) * sizeof(float);         \
     if constexpr (lds > 64 * 1024) {                                                                       \
       static bool attr_set = false;                                                                        \
       if (!attr_set) {                                                                                     \
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_narrow_kernel<MTV, NTV, NSV, ONE>,            \
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_narrow_kernel<MTV, NTV, NSV, ONE, LNFV>,      \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
         if (e != hipSuccess) return e;                                                                     \
         attr_set = true;                                                                                   \
       }                                                                                                    \
     }                                                                                                      \
-    gemm_narrow_kernel<MTV, NTV, NSV, ONE><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV), kz), 256, lds, s>>>(a); \
+    gemm_narrow_kernel<MTV, NTV, NSV, ONE, LNFV><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV), kz), 256, lds, s>>>(a); \
+  } while (0)
+#define FARD_NR(MTV, NTV, NSV, ONE)                      \
+  do {                                                   \
+    if (a.ln_cs != nullptr) FARD_NR_L(MTV, NTV, NSV, ONE, true); \
+    else FARD_NR_L(MTV, NTV, NSV, ONE, false);           \
   } while (0)
   if (a.M <= 64) {
     // a few dozen rows: 16-row workgroups (more of them, half the activation bytes each) measured ahead of
@@ -217,6 +277,7 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
     else FARD_NR(2, 1, 8, false);
   }
 #undef FARD_NR
+#undef FARD_NR_L
   return hipGetLastError();
 }
 

@@ -94,6 +94,62 @@ def test_gemm_narrow_matches_fp64(ctx_bf16, M, K, N, epi):
     assert err < 1e-2, err
 
 
+@pytest.mark.parametrize("M,K,N,epi", [(32, 1024, 1024, 2), (288, 1024, 1024, 2), (45, 512, 96, 3), (130, 1280, 2048, 3)])
+def test_gemm_narrow_bf16_copy_of_a_residual_update(ctx_bf16, M, K, N, epi):
+    import torch
+    ctx, _ = ctx_bf16
+    tag = f"c{M}.{K}.{N}.{epi}"
+    A = ctx.dev_store(gen.normal(15, "A" + tag, (M, K), 1.0, DT_BF16))
+    W = ctx.dev_store(gen.normal(15, "W" + tag, (K, N), 0.05, DT_BF16))
+    base = gen.normal(15, "o" + tag, (M, N), 1.0, DT_F32)
+    gate = ctx.dev_f32(gen.normal(15, "g" + tag, (M, N), 1.0, DT_F32)) if epi == 3 else None
+    o1, o2 = ctx.dev_f32(base), ctx.dev_f32(base)
+    cp = torch.zeros((M, N), dtype=torch.bfloat16, device=ctx.dev)
+    torch.cuda.synchronize()
+    ctx.spec_gemm_narrow(A, W, o1, gate=gate, epi=epi)
+    ctx.spec_gemm_narrow(A, W, o2, gate=gate, epi=epi, out_bf16=cp)
+    ctx.sync()
+    assert torch.equal(o1, o2)                                       # the copy changes nothing else
+    assert torch.equal(cp, o2.to(torch.bfloat16))                    # and is the rounded new value
+    with pytest.raises(Exception):
+        ctx.spec_gemm_narrow(A, W, ctx.empty((M, N), ctx.tdtype), epi=0, out_bf16=cp)
+
+
+def _norm_ref(x, g, beta, norm_type, eps):
+    x = x.astype(np.float64)
+    if norm_type == 0:
+        mu = x.mean(axis=1, keepdims=True)
+        var = ((x - mu) ** 2).mean(axis=1, keepdims=True)
+        return (x - mu) / np.sqrt(var + eps) * g + (0.0 if beta is None else beta)
+    return x / np.sqrt((x ** 2).mean(axis=1, keepdims=True) + eps) * g
+
+
+@pytest.mark.parametrize("M,K,N,norm_type,act,offset", [
+    (32, 1024, 4096, 0, 1, 0.0), (288, 1024, 4096, 0, 1, 0.0), (33, 512, 96, 0, 0, 0.0), (64, 1280, 5120, 0, 1, 0.3),
+    (100, 1024, 2080, 1, 2, 0.0), (17, 256, 64, 1, 0, 0.5), (288, 1024, 1024, 0, 0, 1.0), (130, 1536, 2048, 0, 1, 0.0),
+])
+def test_gemm_with_folded_norm_matches_fp64(ctx_bf16, M, K, N, norm_type, act, offset):
+    """norm(x) W + b with the norm applied in the GEMM's epilogue, against the plain definition in fp64 on the same
+    bf16-rounded inputs.  offset: mean of the rows in units of their standard deviation (the fold subtracts
+    mean * colsum(W') after the product, so a large mean costs accuracy: 1 sigma must still meet the bar)."""
+    from oracle import transformer as otf
+    ctx, _ = ctx_bf16
+    tag = f"n{M}.{K}.{N}.{norm_type}"
+    x = gen.bf16_round((gen.normal(16, "x" + tag, (M, K), 1.0, DT_F32) + offset).astype(np.float32))
+    W = gen.normal(16, "W" + tag, (K, N), 0.05, DT_BF16)
+    g = (1.0 + gen.normal(16, "g" + tag, (K,), 0.2, DT_F32)).astype(np.float32)
+    beta = gen.normal(16, "be" + tag, (K,), 0.1, DT_F32) if norm_type == 0 else None
+    b = gen.normal(16, "b" + tag, (N,), 0.1, DT_F32)
+    out = ctx.spec_gemm_norm(ctx.dev_store(x), ctx.dev_store(W), ctx.dev_f32(g), None if beta is None else ctx.dev_f32(beta),
+                             ctx.dev_f32(b), norm_type=norm_type, eps=1e-5, act=act)
+    ctx.sync()
+    ref = _norm_ref(x, g, beta, norm_type, 1e-5) @ W.astype(np.float64) + b
+    ref = {0: lambda v: v, 1: otf.gelu_erf, 2: otf.silu}[act](ref)
+    err = rel_inf(out.float().cpu().numpy(), ref)
+    print(f"folded norm: {err:.2e}")
+    assert err < 1e-2, err
+
+
 def test_gemm_narrow_is_deterministic_and_rejects_bad_shapes(ctx_bf16):
     import torch
     ctx, _ = ctx_bf16
