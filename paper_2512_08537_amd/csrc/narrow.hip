@@ -181,11 +181,18 @@ __global__ __launch_bounds__(256, (LNF && NS == 8) ? 2 : 1) void gemm_narrow_ker
     for (int i = 0; i < MT; ++i) {
       const bf16x8 af = live ? areg[g][i] : zero8;
       if constexpr (LNF) {
+        // sum x and sum x^2 of the fragment's 8 values, two per instruction (v_dot2c_f32_bf16: fp32 accumulate)
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 ones;
+        ones[0] = (bf16)1.0f;
+        ones[1] = (bf16)1.0f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float x = (float)af[e];
-          s1[i] += x;
-          s2[i] = fmaf(x, x, s2[i]);
+        for (int e = 0; e < 4; ++e) {
+          bf16x2 pr;
+          pr[0] = af[2 * e];
+          pr[1] = af[2 * e + 1];
+          s1[i] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, s1[i], false);
+          s2[i] = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, s2[i], false);
         }
       }
 #pragma unroll
