@@ -1160,9 +1160,10 @@ int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, c
     // dropped drafts keep finite values: they still travel through the dense draft rows
     HIPCHK(c, launch_fill_f32(s, x_draft, 0.f, (size_t)B * K * D));
     HIPCHK(c, launch_fill_f32(s, mu_q, 0.f, (size_t)B * K * D)); }
+  // one row per sample in every step: the row maps are built once, the positions move on with the lengths
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_build_rows(s, nullptr, 1, B, K, D, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, B, 1)); }
   for (int i = 0; i < K; ++i) {
-    { Bracket br(c, CLS_OTHER);
-      HIPCHK(c, launch_build_rows(s, nullptr, 1, B, K, D, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, B, 1)); }
     const float* xs = (i == 0) ? x_pending : x_draft + (size_t)(i - 1) * D;
     const int ldx = (i == 0) ? D : K * D;
     { Bracket br(c, CLS_OTHER);
@@ -1183,7 +1184,7 @@ int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, c
     // only samples that are still speculating reach the head
     if ((rc = run_final(c, FARD_DRAFT, B, c->n_act, c->act_idx, c->z))) return rc;
     if ((rc = run_head(c, c->z, B, c->n_act, eps, eps_stride, c->emap, c->omap, mu_q, x_draft))) return rc;
-    HIPCHK(c, launch_len_add(s, m.len, nullptr, 1, B));
+    HIPCHK(c, launch_len_add(s, m.len, nullptr, 1, B, c->maps.row_pos));
   }
   m.len_hi += K;
   m.written = K;

@@ -158,7 +158,8 @@ hipError_t launch_catchup_pack(hipStream_t s, const int* n_accept, const float* 
                                int* nq, float* x_pack);
 
 // cache_len[b] += base + (n ? n[b] : 0)
-hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B);
+// row_pos (optional, one row per sample): row b's position is refreshed to the new length
+hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B, int* row_pos = nullptr);
 hipError_t launch_fill_i32(hipStream_t s, int* p, int v, int n);
 hipError_t launch_fill_f32(hipStream_t s, float* p, float v, size_t n);
 // copy rows: dst[dmap ? dmap[r] : r, :] = src[r, :] for r < n (fp32 or storage type by elem_size)

@@ -901,9 +901,13 @@ __global__ __launch_bounds__(64) void accept_kernel(const float* __restrict__ x,
   }
 }
 
-__global__ void len_add_kernel(int* cache_len, const int* n, int base, int B) {
+__global__ void len_add_kernel(int* cache_len, const int* n, int base, int B, int* row_pos) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) cache_len[b] += base + (n ? n[b] : 0);
+  if (b < B) {
+    const int v = cache_len[b] + base + (n ? n[b] : 0);
+    cache_len[b] = v;
+    if (row_pos) row_pos[b] = v;             // one row per sample: row b's next position
+  }
 }
 __global__ void fill_i32_kernel(int* p, int v, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1121,8 +1125,8 @@ hipError_t launch_accept(hipStream_t s, const float* x, const float* mu_p, const
   return hipGetLastError();
 }
 
-hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B) {
-  len_add_kernel<<<(B + 255) / 256, 256, 0, s>>>(cache_len, n, base, B);
+hipError_t launch_len_add(hipStream_t s, int* cache_len, const int* n, int base, int B, int* row_pos) {
+  len_add_kernel<<<(B + 255) / 256, 256, 0, s>>>(cache_len, n, base, B, row_pos);
   return hipGetLastError();
 }
 hipError_t launch_fill_i32(hipStream_t s, int* p, int v, int n) {
