@@ -714,17 +714,21 @@ int flush_parts(fard_ctx* c, int d, int M, const int* m_dev) {
 }
 
 // Layers [l0, l1) of one model over the packed rows described by c->maps (h in, h out).
-int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max, const int* m_dev, int ent_layer) {
+// first_norm_done: c->u already holds the first norm of layer l0 (the embedding kernel wrote it).
+int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max, const int* m_dev, int ent_layer,
+               bool first_norm_done = false) {
   Model& m = c->mdl[which];
   const fard_tf_cfg& t = m.c;
   hipStream_t s = c->stream;
   const int d = t.d_model, F = t.d_ff, HD = t.n_heads * t.d_head, QN = m.qkv_n();
   for (int l = l0; l < l1; ++l) {
     const LayerW& L = m.L[l];
-    { Bracket br(c, CLS_OTHER);
+    if (!(first_norm_done && l == l0 && c->pend_n == 0)) {
+      Bracket br(c, CLS_OTHER);
       HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, nullptr, nullptr, 0, nullptr, c->u,
                             c->parts, c->pend_n, c->pend_stride, c->h));
-      c->pend_n = 0; }
+      c->pend_n = 0;
+    }
     HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
     KvGeom kg = kv_geom(c, m, l);
     // learned positions, bf16: the attention kernel stores the new K / V rows itself
@@ -762,6 +766,16 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
     else HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
   }
   return FARD_OK;
+}
+
+// Embedding of the packed rows into c->h together with the first norm of layer 0 into c->u.
+hipError_t embed_first_norm(fard_ctx* c, int which, const float* x, int ldx, const int* cond_id, int M, const int* m_dev) {
+  Model& m = c->mdl[which];
+  const fard_tf_cfg& t = m.c;
+  const LayerW& L = m.L[0];
+  Bracket br(c, CLS_OTHER);
+  return launch_embed_norm(c->stream, c->bf16, x, ldx, t.d_latent, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, cond_id, c->h,
+                           t.d_model, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, c->u);
 }
 
 // Final norm (optionally gathering rows through in_map) and up-projection -> z [n, d_out] storage type.
@@ -984,14 +998,12 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
   { Bracket br(c, CLS_OTHER);
     HIPCHK(c, launch_build_rows(s, n_q, 0, B, c->cfg.K, m.c.d_latent, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, M, cap)); }
   const int* md = c->maps.m_total;
-  { Bracket br(c, CLS_OTHER);
-    HIPCHK(c, launch_embed(s, c->bf16, x_in, m.c.d_latent, m.c.d_latent, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, cond_id,
-                           c->h, m.c.d_model, M, md)); }
+  HIPCHK(c, embed_first_norm(c, which, x_in, m.c.d_latent, cond_id, M, md));
   const int ls = c->cfg.entropy_layer;
   const bool want_sh = (shallow_out || h_attn_out) && ls <= m.c.n_layers;
   int rc;
   if (want_sh) {
-    if ((rc = run_layers(c, which, 0, ls, B, M, cap, md, h_attn_out ? ls : 0))) return rc;
+    if ((rc = run_layers(c, which, 0, ls, B, M, cap, md, h_attn_out ? ls : 0, true))) return rc;
     if ((rc = flush_parts(c, m.c.d_model, M, md))) return rc;
     if (shallow_out) {
       Bracket br(c, CLS_OTHER);
@@ -1004,7 +1016,7 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
     }
     if ((rc = run_layers(c, which, ls, m.c.n_layers, B, M, cap, md, 0))) return rc;
   } else {
-    if ((rc = run_layers(c, which, 0, m.c.n_layers, B, M, cap, md, 0))) return rc;
+    if ((rc = run_layers(c, which, 0, m.c.n_layers, B, M, cap, md, 0, true))) return rc;
   }
   if ((rc = run_final(c, which, M, md, nullptr, z_out))) return rc;
   if (commit) {
@@ -1166,11 +1178,9 @@ int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, c
   for (int i = 0; i < K; ++i) {
     const float* xs = (i == 0) ? x_pending : x_draft + (size_t)(i - 1) * D;
     const int ldx = (i == 0) ? D : K * D;
-    { Bracket br(c, CLS_OTHER);
-      HIPCHK(c, launch_embed(s, c->bf16, xs, ldx, D, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, i == 0 ? pending_id : nullptr,
-                             c->h, d, B, nullptr)); }
+    HIPCHK(c, embed_first_norm(c, FARD_DRAFT, xs, ldx, i == 0 ? pending_id : nullptr, B, nullptr));
     const bool attn_mode = c->cfg.entropy_mode == FARD_ENT_ATTN;
-    if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0))) return rc;
+    if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0, true))) return rc;
     // pending partial planes of the last shallow layer: the entropy rows add them on the fly and the next norm
     // folds them into the stream; otherwise they are folded here
     const bool ent_folds = !attn_mode && ls < m.c.n_layers && ent_rows_in_regs_f32(c->h, d, d);
@@ -1222,8 +1232,9 @@ int spec_verify(fard_ctx* c, const float* x_pending, const int32_t* pending_id, 
       HIPCHK(c, launch_fill_i32(s, cid, -1, M));
       HIPCHK(c, launch_scatter_rows(s, pending_id, cid, c->maps.row_start, 1, 4, B, nullptr));
     }
-    HIPCHK(c, launch_embed(s, c->bf16, c->x_in, D, D, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, cid, c->h, m.c.d_model, M, md)); }
-  if ((rc = run_layers(c, FARD_TARGET, 0, m.c.n_layers, B, M, K + 1, md, 0))) return rc;
+  }
+  HIPCHK(c, embed_first_norm(c, FARD_TARGET, c->x_in, D, cid, M, md));
+  if ((rc = run_layers(c, FARD_TARGET, 0, m.c.n_layers, B, M, K + 1, md, 0, true))) return rc;
   if ((rc = run_final(c, FARD_TARGET, M, md, nullptr, c->z))) return rc;
   if (z_p) {
     Bracket br(c, CLS_OTHER);

@@ -39,6 +39,12 @@ hipError_t launch_embed(hipStream_t s, int is_bf16, const float* x, int ldx, int
                         const void* cond_table, const int* cond_id, float* h, int d, int M,
                         const int* m_dev);
 
+// launch_embed followed by the norm of the same rows (gain g, bias b; norm_type 0 LayerNorm, 1 RMSNorm) into u, in
+// one launch.
+hipError_t launch_embed_norm(hipStream_t s, int is_bf16, const float* x, int ldx, int D, const void* w_in, const float* b_in,
+                             const void* pos_table, const int* row_pos, const void* cond_table, const int* cond_id, float* h,
+                             int d, int M, const int* m_dev, int norm_type, float eps, const float* g, const float* b, void* u);
+
 // out_T[r, :] = norm(h[r, :]) with optional affine (g, b) and optional AdaLN modulation
 // (1 + scale[r, :]) / shift[r, :] read with row stride ldm.  norm_type 0 LayerNorm, 1 RMSNorm.
 // in_map (optional) gathers: output row r is computed from input row in_map[r].

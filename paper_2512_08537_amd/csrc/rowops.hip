@@ -966,6 +966,107 @@ __global__ __launch_bounds__(256) void add_parts_kernel(float* __restrict__ h, c
   }
 }
 
+template <typename T>
+__device__ __forceinline__ f32x4 load4f(const T* p);
+template <>
+__device__ __forceinline__ f32x4 load4f<float>(const float* p) { return *(const f32x4*)p; }
+template <>
+__device__ __forceinline__ f32x4 load4f<bf16>(const bf16* p) {
+  const bf16x4 t = *(const bf16x4*)p;
+  return f32x4{(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
+}
+
+// embed + the first norm of layer 0 in one launch: one workgroup per row computes h[r, :] as embed_kernel does,
+// keeps it in registers, writes it, and writes u[r, :] = norm(h[r, :]) g + b (what norm_kernel would).
+template <typename T, int VPT>
+__global__ __launch_bounds__(256) void embed_norm_kernel(const float* __restrict__ x, int ldx, int D, const T* __restrict__ w_in,
+                                                         const float* __restrict__ b_in, const T* __restrict__ pos_table,
+                                                         const int* __restrict__ row_pos, const T* __restrict__ cond_table,
+                                                         const int* __restrict__ cond_id, float* __restrict__ h, int d, int M,
+                                                         const int* m_dev, int norm_type, float eps, const float* __restrict__ g,
+                                                         const float* __restrict__ b, T* __restrict__ u) {
+  __shared__ float red[8];
+  const int Me = eff_rows(M, m_dev);
+  const int r = blockIdx.x;
+  if (r >= Me) return;
+  const int n4 = d >> 2;
+  const int id = cond_id ? cond_id[r] : -1;
+  const int pos = (pos_table && id < 0) ? row_pos[r] : 0;
+  f32x4 v[VPT];
+  float s = 0.f;
+  float xr[16];                                            // D <= 16 (checked on the host)
+#pragma unroll
+  for (int k = 0; k < 16; ++k) xr[k] = (k < D) ? x[(size_t)r * ldx + k] : 0.f;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c4 = threadIdx.x + i * 256;
+    v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (c4 < n4) {
+      if (id >= 0) {
+        v[i] = load4f<T>(cond_table + (size_t)id * d + c4 * 4);
+      } else {
+        // four columns at a time: all 16 weight loads of the group are issued before the first use
+        f32x4 w[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) w[k] = load4f<T>(w_in + (size_t)(k < D ? k : 0) * d + c4 * 4);
+        if (b_in) v[i] = ((const f32x4*)b_in)[c4];
+        if (pos_table) v[i] += load4f<T>(pos_table + (size_t)pos * d + c4 * 4);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[i] += w[k] * xr[k];
+      }
+      *(f32x4*)(h + (size_t)r * d + c4 * 4) = v[i];
+      s += v[i][0] + v[i][1] + v[i][2] + v[i][3];
+    }
+  }
+  float mean = 0.f;
+  if (norm_type == 0) mean = block_sum(s, red) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    if (threadIdx.x + i * 256 < n4) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float t = v[i][e] - mean; q += t * t; }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(block_sum(q, red) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int c4 = threadIdx.x + i * 256;
+    if (c4 >= n4) continue;
+    f32x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = (v[i][e] - mean) * rstd;
+    if (g) y *= ((const f32x4*)g)[c4];
+    if (b) y += ((const f32x4*)b)[c4];
+    store4<T>(u + (size_t)r * d + c4 * 4, y[0], y[1], y[2], y[3]);
+  }
+}
+
+hipError_t launch_embed_norm(hipStream_t s, int is_bf16, const float* x, int ldx, int D, const void* w_in, const float* b_in,
+                             const void* pos_table, const int* row_pos, const void* cond_table, const int* cond_id, float* h,
+                             int d, int M, const int* m_dev, int norm_type, float eps, const float* g, const float* b, void* u) {
+  if (M <= 0) return hipSuccess;
+  if (d % 4 != 0 || d > 256 * 4 * NORM_VPT) return hipErrorInvalidValue;
+#define FARD_EN(VPT)                                                                                                       \
+  do {                                                                                                                     \
+    if (is_bf16)                                                                                                           \
+      embed_norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(x, ldx, D, (const bf16*)w_in, b_in, (const bf16*)pos_table, row_pos,  \
+                                                     (const bf16*)cond_table, cond_id, h, d, M, m_dev, norm_type, eps, g, b, \
+                                                     (bf16*)u);                                                            \
+    else                                                                                                                   \
+      embed_norm_kernel<float, VPT><<<M, 256, 0, s>>>(x, ldx, D, (const float*)w_in, b_in, (const float*)pos_table, row_pos, \
+                                                      (const float*)cond_table, cond_id, h, d, M, m_dev, norm_type, eps, g, b, \
+                                                      (float*)u);                                                          \
+  } while (0)
+  const int n4 = d >> 2;
+  if (n4 <= 256) FARD_EN(1);
+  else if (n4 <= 512) FARD_EN(2);
+  else if (n4 <= 1024) FARD_EN(4);
+  else FARD_EN(8);
+#undef FARD_EN
+  return hipGetLastError();
+}
+
 hipError_t launch_add_parts(hipStream_t s, float* h, const float* parts, int n_parts, size_t part_stride, int d, int M,
                             const int* m_dev) {
   if (M <= 0 || n_parts <= 0) return hipSuccess;
