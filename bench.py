@@ -171,18 +171,31 @@ def main():
         g_ur = torch.rand((R, B, J), generator=gt, device=ctx.dev)
         torch.cuda.synchronize()                         # (torch filled these on its own stream)
         reps = max(1, min(5, args.steps))
-        for i in range(reps + 1):
-            if i == 1:
-                ctx.sync()
-                tg0 = time.perf_counter()
-            reset()
-            go = ctx.spec_generate(gi["pending"], g_eps, g_r, g_er, g_ur, tau)
-        ctx.sync()
-        tg = (time.perf_counter() - tg0) / reps
+
+        def gen_timed():
+            go = None
+            for i in range(reps + 2):                        # two untimed calls (with replay on: the recording ones)
+                if i == 2:
+                    ctx.sync()
+                    tg0 = time.perf_counter()
+                reset()
+                go = ctx.spec_generate(gi["pending"], g_eps, g_r, g_er, g_ur, tau, out=go)
+            ctx.sync()
+            return (time.perf_counter() - tg0) / reps, go
+
+        ctx.spec_graph_enable(False)
+        tg_eager, go = gen_timed()
+        tg, tg_graph = tg_eager, None
+        if not args.no_graph:
+            ctx.spec_graph_enable(True)
+            tg_graph, go = gen_timed()
+            tg = min(tg_eager, tg_graph)
         n_tok = float(go["n_tokens"].sum().item())
         gen_stats = {"rounds": R, "ms_per_round": round(tg / R * 1e3, 4), "tokens": n_tok,
                      "tokens_per_s": round(n_tok / tg, 1), "resample_tries_mean":
-                     round(float(go["tries"].float().sum().item()) / max(1.0, float((go["tries"] > 0).sum().item())), 2)}
+                     round(float(go["tries"].float().sum().item()) / max(1.0, float((go["tries"] > 0).sum().item())), 2),
+                     "ms_per_round_kernel_by_kernel": round(tg_eager / R * 1e3, 4),
+                     "ms_per_round_graph_replay": None if tg_graph is None else round(tg_graph / R * 1e3, 4)}
 
     # Prefill (the next row after the round itself): both caches rebuilt from a prefix of n_ctx known tokens per sample
     # (a class token and latents), timed on the stream; GEMM and attention time of the target's prefill from HIP events

@@ -217,7 +217,11 @@ int spec_round(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id,
  * Replays read the cache lengths on the device, so spec_kv_reset / spec_kv_load between calls are fine; the
  * host-side capacity rules (FARD_ECAPACITY) are checked on every call as usual.  The buffers the arguments
  * name must stay allocated while the graph is in use; their contents may change freely.
- * enable = 0 drops the graph.  Per-kernel timing (spec_profile_enable) switches replay off while it is on.
+ * spec_generate uses the same switch: the noise of each round is first copied to staging buffers inside the context
+ * (one small launch), so every round is the same set of launches; the first round of a new argument set (tokens,
+ * n_tokens, the scalars, B, R, J <= 64) is launched kernel by kernel, the second is recorded, all later rounds, also
+ * of later calls with the same arguments, are replays; the per-round records are copied out after each round.
+ * enable = 0 drops the graphs.  Per-kernel timing (spec_profile_enable) switches replay off while it is on.
  * Errors: FARD_ESTATE if the context runs on the default stream (it cannot be captured). */
 int spec_graph_enable(fard_ctx* ctx, int32_t enable);
 

@@ -337,16 +337,25 @@ class Context:
                                     _ptr(u_res), float(log_sigma), sp, sq, B, J, _ptr(x_next), _ptr(tries)))
         return x_next, tries
 
-    def spec_generate(self, x_first, eps, r, eps_res, u_res, tau, first_id=None, log_sigma=0.0, sigma_p=None, sigma_q=None):
-        """eps [R,S+1,B,K+1,D], r [R,B,K], eps_res [R,B,J,D], u_res [R,B,J] (device fp32)."""
+    def spec_generate(self, x_first, eps, r, eps_res, u_res, tau, first_id=None, log_sigma=0.0, sigma_p=None, sigma_q=None,
+                      out=None):
+        """eps [R,S+1,B,K+1,D], r [R,B,K], eps_res [R,B,J,D], u_res [R,B,J] (device fp32).  out: the dict of a
+        previous call with the same shapes (its buffers are reused; with spec_graph_enable that keeps the recorded
+        round valid from the first round on)."""
         t = self.torch
         R, B, K = r.shape
         J = u_res.shape[2]
         D = x_first.shape[1]
         sp, sq = self._sigmas(sigma_p, sigma_q)
-        o = dict(tokens=t.zeros((B, R * (K + 1), D), dtype=t.float32, device=self.dev),
-                 n_tokens=self.empty((B,), t.int32), H=self.empty((R, B, K), t.float32),
-                 n_keep=self.empty((R, B), t.int32), n_accept=self.empty((R, B), t.int32), tries=self.empty((R, B), t.int32))
+        if out is not None:
+            o = out
+            o["tokens"].zero_()
+        else:
+            o = dict(tokens=t.zeros((B, R * (K + 1), D), dtype=t.float32, device=self.dev),
+                     n_tokens=self.empty((B,), t.int32), H=self.empty((R, B, K), t.float32),
+                     n_keep=self.empty((R, B), t.int32), n_accept=self.empty((R, B), t.int32), tries=self.empty((R, B), t.int32))
+        if self.stream_ptr is not None:
+            t.cuda.current_stream().synchronize()        # torch zeroed `tokens` on its own stream
         self._chk(lib.spec_generate(self.h, _ptr(x_first), _ptr(first_id), _ptr(eps), _ptr(r), _ptr(eps_res), _ptr(u_res), float(tau),
                                     float(log_sigma), sp, sq, B, R, J, _ptr(o["tokens"]), _ptr(o["n_tokens"]), _ptr(o["H"]),
                                     _ptr(o["n_keep"]), _ptr(o["n_accept"]), _ptr(o["tries"])))

@@ -102,6 +102,31 @@ __global__ void ln_fold_kernel(const TS* __restrict__ w, const float* __restrict
   cs[n] = c;
   bf[n] = bb;
 }
+// Multi-round generation as graph replays: the noise of round t is copied to fixed staging buffers before the round's
+// graph, and the round's per-sample records are copied out after it.
+__global__ void gen_stage_in_kernel(const float* __restrict__ eps, const float* __restrict__ r, const float* __restrict__ eres,
+                                    const float* __restrict__ ures, size_t n_eps, size_t n_r, size_t n_eres, size_t n_ures,
+                                    float* __restrict__ d_eps, float* __restrict__ d_r, float* __restrict__ d_eres,
+                                    float* __restrict__ d_ures) {
+  const size_t total = n_eps + n_r + n_eres + n_ures;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    if (i < n_eps) d_eps[i] = eps[i];
+    else if (i < n_eps + n_r) d_r[i - n_eps] = r[i - n_eps];
+    else if (i < n_eps + n_r + n_eres) d_eres[i - n_eps - n_r] = eres[i - n_eps - n_r];
+    else d_ures[i - n_eps - n_r - n_eres] = ures[i - n_eps - n_r - n_eres];
+  }
+}
+__global__ void gen_stage_out_kernel(const float* __restrict__ s_H, const int* __restrict__ s_nk, const int* __restrict__ s_na,
+                                     const int* __restrict__ s_tr, int BK, int B, float* __restrict__ H, int* __restrict__ nk,
+                                     int* __restrict__ na, int* __restrict__ tr) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < BK) H[i] = s_H[i];
+  if (i < B) {
+    nk[i] = s_nk[i];
+    na[i] = s_na[i];
+    tr[i] = s_tr[i];
+  }
+}
 __global__ void temb_feat_kernel(float t, float t_scale, int half, float* out) {
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
   if (k < half) {
@@ -215,6 +240,9 @@ struct fard_ctx {
   int pend_n = 0;
   size_t pend_stride = 0;
   RoundGraph rgraph;
+  RoundGraph ggraph;                       // one round of spec_generate on the staging buffers below
+  float *s_eps = nullptr, *s_r = nullptr, *s_eres = nullptr, *s_ures = nullptr, *s_H = nullptr;
+  int *s_pid = nullptr, *s_nk = nullptr, *s_na = nullptr, *s_tr = nullptr;
   void* loss_tmp = nullptr;                // scratch of the training-side losses, grown on demand
   size_t loss_tmp_bytes = 0;
   uint8_t* acc_tmp = nullptr;
@@ -603,6 +631,7 @@ int load_head(fard_ctx* c, Loader& ld) {
   return FARD_OK;
 }
 
+constexpr int GEN_J_MAX = 64;            // resampling tries that the staged (graph) generation path holds
 constexpr int PART_MAX_SLICES = 8;      // K slices of a deferred residual update
 constexpr int PART_MAX_ROWS = 640;
 
@@ -664,6 +693,15 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<float>(c, &c->g_cu_x, (size_t)g.max_batch * D))) return rc;
   if ((rc = dalloc<int>(c, &c->g_cu_nq, g.max_batch))) return rc;
   if ((rc = dalloc<uint8_t>(c, &c->g_keep, bk))) return rc;
+  if ((rc = dalloc<float>(c, &c->s_eps, (size_t)(g.head.n_steps + 1) * g.max_batch * (g.K + 1) * D))) return rc;
+  if ((rc = dalloc<float>(c, &c->s_r, bk))) return rc;
+  if ((rc = dalloc<float>(c, &c->s_eres, (size_t)g.max_batch * GEN_J_MAX * D))) return rc;
+  if ((rc = dalloc<float>(c, &c->s_ures, (size_t)g.max_batch * GEN_J_MAX))) return rc;
+  if ((rc = dalloc<float>(c, &c->s_H, bk))) return rc;
+  if ((rc = dalloc<int>(c, &c->s_pid, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->s_nk, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->s_na, g.max_batch))) return rc;
+  if ((rc = dalloc<int>(c, &c->s_tr, g.max_batch))) return rc;
   if (c->bf16 && (rc = dalloc<float>(c, &c->parts, (size_t)PART_MAX_SLICES * std::min(M, PART_MAX_ROWS) * dmax))) return rc;
   return FARD_OK;
 }
@@ -910,6 +948,7 @@ int spec_round_destroy(fard_ctx* c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto& ev : c->prof.pool) { (void)hipEventDestroy(ev.first); (void)hipEventDestroy(ev.second); }
   c->rgraph.drop();
+  c->ggraph.drop();
   if (c->gemm_tmp) (void)hipFree(c->gemm_tmp);
   if (c->loss_tmp) (void)hipFree(c->loss_tmp);
   for (void* p : c->allocs) (void)hipFree(p);
@@ -1277,6 +1316,7 @@ int spec_graph_enable(fard_ctx* c, int32_t on) {
   if (check_ctx(c)) return FARD_EINVAL;
   if (on && c->stream == nullptr) return fail(c, FARD_ESTATE, "rounds on the default stream cannot be captured");
   c->rgraph.drop();
+  c->ggraph.drop();
   c->rgraph.on = on != 0;
   return FARD_OK;
 }
@@ -1370,6 +1410,92 @@ int spec_resample(fard_ctx* c, const float* mu_p, const float* mu_q, const float
   return FARD_OK;
 }
 
+// One round of generation on the staging buffers: round, closing token, draft catch-up.  The same launches for every
+// round, so that a recording of one round replays for all of them.
+static int generate_round_staged(fard_ctx* c, bool with_id, float tau, float lsf, float sp, float sq, int B, int J, float* tokens,
+                                 int tok_cap, int* n_tokens) {
+  const int K = c->cfg.K, D = c->cfg.target.d_latent, S = c->cfg.head.n_steps;
+  hipStream_t s = c->stream;
+  int rc = round_eager(c, c->g_next, with_id ? c->s_pid : nullptr, c->s_eps, c->s_r, tau, lsf, sp, sq, B, c->s_H, c->g_keep, c->s_nk,
+                       c->g_x, c->g_mu_q, c->s_na, c->g_lr, c->g_mu_p);
+  if (rc) return rc;
+  { Bracket br(c, CLS_OTHER);
+    HIPCHK(c, launch_round_finish(s, c->g_mu_p, c->g_mu_q, c->s_eps + (size_t)S * B * (K + 1) * D, c->s_na, c->s_nk, c->s_eres,
+                                  c->s_ures, c->g_x, B, K, D, J, lsf, sp, sq, c->g_next, c->s_tr, tokens, tok_cap, n_tokens));
+    HIPCHK(c, launch_catchup_pack(s, c->s_na, c->g_x, B, K, D, c->g_cu_nq, c->g_cu_x)); }
+  return spec_forward(c, FARD_DRAFT, c->g_cu_x, nullptr, c->g_cu_nq, 1, B, B, 1, c->z, nullptr, nullptr);
+}
+
+static int generate_staged(fard_ctx* c, const float* x_first, const int32_t* first_id, const float* eps, const float* r,
+                           const float* eps_res, const float* u_res, float tau, float lsf, float sp, float sq, int B, int R, int J,
+                           float* tokens, int32_t* n_tokens, float* H, int32_t* n_keep, int32_t* n_accept, int32_t* tries) {
+  const int K = c->cfg.K, D = c->cfg.target.d_latent, S = c->cfg.head.n_steps;
+  hipStream_t s = c->stream;
+  const size_t n_eps = (size_t)(S + 1) * B * (K + 1) * D, n_r = (size_t)B * K, n_eres = (size_t)B * J * D, n_ures = (size_t)B * J;
+  const int tok_cap = R * (K + 1);
+  RoundGraph& g = c->ggraph;
+  RoundKey key;
+  memset(&key, 0, sizeof(key));
+  key.ptr[0] = tokens; key.ptr[1] = n_tokens; key.ptr[2] = first_id ? c->s_pid : nullptr;
+  key.f[0] = tau; key.f[1] = lsf; key.f[2] = sp; key.f[3] = sq;
+  key.B = B; key.pad = J * 65536 + R;
+  if (!(g.have_key && memcmp(&key, &g.key, sizeof(key)) == 0)) {
+    g.drop();
+    g.key = key;
+    g.have_key = true;
+  }
+  HIPCHK(c, hipMemcpyAsync(c->g_next, x_first, (size_t)B * D * 4, hipMemcpyDeviceToDevice, s));
+  if (first_id) { copy_i32_kernel<<<(B + 255) / 256, 256, 0, s>>>(first_id, c->s_pid, B); HIPCHK(c, hipGetLastError()); }
+  bool ran_eager = false;
+  for (int t = 0; t < R; ++t) {
+    { Bracket br(c, CLS_OTHER);
+      const size_t total = n_eps + n_r + n_eres + n_ures;
+      gen_stage_in_kernel<<<(unsigned)std::min<size_t>((total + 255) / 256, 1024), 256, 0, s>>>(
+          eps + t * n_eps, r + t * n_r, eps_res + t * n_eres, u_res + t * n_ures, n_eps, n_r, n_eres, n_ures, c->s_eps, c->s_r,
+          c->s_eres, c->s_ures);
+      HIPCHK(c, hipGetLastError());
+      if (t == 1 && first_id) HIPCHK(c, launch_fill_i32(s, c->s_pid, -1, B)); }   // later pending tokens are latents
+    int rc = FARD_OK;
+    if (g.exec) {
+      HIPCHK(c, hipGraphLaunch(g.exec, s));
+      c->mdl[FARD_DRAFT].len_hi += K + 1;
+      c->mdl[FARD_TARGET].len_hi += K + 1;
+      c->mdl[FARD_DRAFT].written = c->mdl[FARD_TARGET].written = 0;
+    } else if (!ran_eager) {
+      // the first round of a new argument set is launched kernel by kernel (it validates, and every kernel has run once)
+      rc = generate_round_staged(c, first_id != nullptr, tau, lsf, sp, sq, B, J, tokens, tok_cap, n_tokens);
+      ran_eager = true;
+    } else {
+      const int hi0[2] = {c->mdl[0].len_hi, c->mdl[1].len_hi}, wr0[2] = {c->mdl[0].written, c->mdl[1].written};
+      HIPCHK(c, hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed));
+      rc = generate_round_staged(c, first_id != nullptr, tau, lsf, sp, sq, B, J, tokens, tok_cap, n_tokens);
+      hipGraph_t graph = nullptr;
+      hipError_t e = hipStreamEndCapture(s, &graph);
+      hipGraphExec_t exec = nullptr;
+      if (rc == FARD_OK && e == hipSuccess && graph) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+      if (rc == FARD_OK && e == hipSuccess && exec) e = hipGraphLaunch(exec, s);
+      if (rc != FARD_OK || e != hipSuccess || !exec) {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+        for (int w = 0; w < 2; ++w) { c->mdl[w].len_hi = hi0[w]; c->mdl[w].written = wr0[w]; }
+        c->pend_n = 0;
+        g.drop();
+        if (rc != FARD_OK) return rc;
+        return fail(c, FARD_EHIP, std::string("graph of a generation round: ") + hipGetErrorString(e));
+      }
+      g.graph = graph;
+      g.exec = exec;
+    }
+    if (rc) return rc;
+    { Bracket br(c, CLS_OTHER);
+      const int BK = B * K;
+      gen_stage_out_kernel<<<(BK + 255) / 256, 256, 0, s>>>(c->s_H, c->s_nk, c->s_na, c->s_tr, BK, B, H + (size_t)t * BK,
+                                                          n_keep + (size_t)t * B, n_accept + (size_t)t * B, tries + (size_t)t * B);
+      HIPCHK(c, hipGetLastError()); }
+  }
+  return FARD_OK;
+}
+
 int spec_generate(fard_ctx* c, const float* x_first, const int32_t* first_id, const float* eps, const float* r,
                   const float* eps_res, const float* u_res, float tau, float log_sigma_factor, float sigma_p, float sigma_q,
                   int32_t B, int32_t R, int32_t J, float* tokens, int32_t* n_tokens, float* H, int32_t* n_keep,
@@ -1393,6 +1519,9 @@ int spec_generate(fard_ctx* c, const float* x_first, const int32_t* first_id, co
   const int tok_cap = R * (K + 1);
   HIPCHK(c, launch_fill_i32(s, n_tokens, 0, B));
   uint8_t* keep = c->g_keep;
+  if (c->rgraph.on && !c->prof.on && J <= GEN_J_MAX)
+    return generate_staged(c, x_first, first_id, eps, r, eps_res, u_res, tau, log_sigma_factor, sigma_p, sigma_q, B, R, J, tokens,
+                           n_tokens, H, n_keep, n_accept, tries);
   for (int t = 0; t < R; ++t) {
     const float* eps_t = eps + (size_t)t * eps_round;
     int rc = round_eager(c, t == 0 ? x_first : c->g_next, t == 0 ? first_id : nullptr, eps_t, r + (size_t)t * B * K, tau,

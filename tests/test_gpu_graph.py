@@ -81,6 +81,48 @@ def test_graph_replays_equal_eager_rounds():
     ctx.close()
 
 
+def test_generation_rounds_as_graph_replays_equal_eager_generation():
+    """spec_generate with graph replay on: the first round of a new argument set is launched kernel by kernel, the
+    second is recorded, later ones and every round of a repeated call replay; all records and tokens must equal the
+    eager run bit for bit."""
+    import torch
+    from synth import gen
+    case = build_case(1, seed=3, affine=False, B=8, deep_gain=0.02)
+    rc = case.rc
+    ctx = _ctx(case)
+    gi = gpu_inputs(ctx, case)
+    B, K, D, S, R, J = case.B, rc.K, rc.target.d_latent, rc.head.n_steps, 6, 8
+    eps = ctx.dev_f32(np.stack([gen.noise(9, f"e{t}", (S + 1, B, K + 1, D)) for t in range(R)]))
+    r = ctx.dev_f32(np.stack([gen.uniforms(9, f"r{t}", (B, K)) for t in range(R)]))
+    er = ctx.dev_f32(np.stack([gen.noise(9, f"er{t}", (B, J, D)) for t in range(R)]))
+    ur = ctx.dev_f32(np.stack([gen.uniforms(9, f"ur{t}", (B, J)) for t in range(R)]))
+    ids = ctx.dev_i32(np.arange(B, dtype=np.int32) * 7 % 1000)
+    cal = _round(ctx, case, gi, ctx._round_bufs(B), -1.0, case.n_ctx)
+    tau = float(np.median(cal["H"]))
+
+    def run(out=None, first_id=None):
+        load_caches(ctx, case)
+        _reset(ctx, case, case.n_ctx)
+        o = ctx.spec_generate(gi["pending"], eps, r, er, ur, tau, first_id=first_id, out=out)
+        ctx.sync()
+        return o, {k: v.clone() for k, v in o.items()}
+
+    for first_id in (None, ids):
+        _, ref = run(first_id=first_id)
+        assert int(ref["n_tokens"].sum()) >= R * B
+        ctx.spec_graph_enable(True)
+        o, got = run(first_id=first_id)                              # round 0 eager, round 1 recorded, 2.. replayed
+        assert all(torch.equal(got[k], ref[k]) for k in ref), "first graph-mode call"
+        for i in range(2):
+            for k in ("H", "n_keep", "n_accept", "tries", "n_tokens"):
+                o[k].zero_()
+            torch.cuda.synchronize()
+            _, got = run(out=o, first_id=first_id)                   # same buffers: every round replays
+            assert all(torch.equal(got[k], ref[k]) for k in ref), f"repeated call {i}"
+        ctx.spec_graph_enable(False)
+    ctx.close()
+
+
 def test_graph_replay_keeps_the_capacity_rules():
     from paper_2512_08537_amd import binding
     case = build_case("mid-bf16", seed=4)
