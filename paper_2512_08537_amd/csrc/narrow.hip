@@ -12,10 +12,14 @@
 // (NT > 1 when many row slabs would otherwise re-read the activations too often); blockIdx.y walks the
 // row slabs.
 //
+// A norm that precedes the GEMM can be applied in the epilogue instead of by a launch of its own (LNF): the
+// operand is the raw rows as bf16, the weights carry the norm's gain, every wave sums its rows' statistics from the
+// activation fragments it feeds to the MFMAs, and the epilogue applies rstd, mean and the weights' column sums.
+//
 // Measured alternatives that lost and are not kept: 32-column tiles with K split over workgroups and fp32
-// atomics (the atomics cost 1-2 us per launch and grow with the split count); folding the preceding
-// norm into the operand load (fp32 rows read in MFMA fragment order touch 4x the cache lines of the bf16
-// operand, and recomputing row statistics in every workgroup hot-spots the L2 lines of those rows).
+// atomics (the atomics cost 1-2 us per launch and grow with the split count); normalising the operand while it
+// is loaded (fp32 rows read in MFMA fragment order touch 4x the cache lines of the bf16 operand, and a separate
+// pass over the rows for their statistics in every workgroup hot-spots the L2 lines of those rows).
 #include "gemm.h"
 
 namespace fard {
