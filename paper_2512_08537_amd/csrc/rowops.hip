@@ -120,6 +120,18 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+// both sums of a 256-thread workgroup in one round (two barriers)
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) { red[wave] = a; red[4 + wave] = b; }
+  __syncthreads();
+  a = red[0] + red[1] + red[2] + red[3];
+  b = red[4] + red[5] + red[6] + red[7];
+}
+
 // One workgroup per row.  The row is read once with 16-byte loads and stays in registers for the
 // statistics and the output pass (d <= 256 * 4 * NORM_VPT); everything a thread needs is requested
 // before the first reduction so that the loads overlap.
@@ -166,24 +178,36 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
       const int c4 = threadIdx.x + i * 256;
       if (c4 < n4) {
         for (int p = 0; p < n_parts; ++p) x[i] += *(const f32x4*)(parts + (size_t)p * part_stride + ro + c4 * 4);
-        if (h_wb != nullptr) *(f32x4*)(h_wb + ro + c4 * 4) = x[i];
       }
     }
   }
-#pragma unroll
-  for (int i = 0; i < VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
-  float mean = 0.f;
-  if (norm_type == 0) mean = block_sum(s, red) / (float)d;
+  // one reduction round for both moments, taken about a pivot (the row's first element) so that
+  // E[(x-p)^2] - E[x-p]^2 does not cancel for rows with a large mean
+  const float pivot = row[0];
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < VPT; ++i) {
     const int c4 = threadIdx.x + i * 256;
     if (c4 < n4) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { const float t = x[i][e] - mean; q += t * t; }
+      for (int e = 0; e < 4; ++e) { const float t = x[i][e] - pivot; s += t; q = fmaf(t, t, q); }
     }
   }
-  const float var = block_sum(q, red) / (float)d;
+  block_sum2(s, q, red);
+  if (n_parts > 0 && h_wb != nullptr) {
+    // the completed row goes back only now: every thread has read the pivot (element 0 of the old row) before the
+    // barriers of the reduction
+    const size_t ro = (size_t)(in_map ? in_map[r] : r) * d;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c4 = threadIdx.x + i * 256;
+      if (c4 < n4) *(f32x4*)(h_wb + ro + c4 * 4) = x[i];
+    }
+  }
+  const float m1 = s / (float)d, m2 = q / (float)d;
+  const float mean = (norm_type == 0) ? pivot + m1 : 0.f;
+  // RMS norm: E[x^2] = E[(x-p)^2] + 2 p E[x-p] + p^2
+  const float var = (norm_type == 0) ? fmaxf(m2 - m1 * m1, 0.f) : fmaxf(m2 + 2.f * pivot * m1 + pivot * pivot, 0.f);
   const float rstd = 1.0f / sqrtf(var + eps);
 #pragma unroll
   for (int i = 0; i < VPT; ++i) {
@@ -756,19 +780,20 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
     sc[i] = ok ? ((const f32x4*)scp)[c4] : z4;
     sh[i] = ok ? ((const f32x4*)shp)[c4] : z4;
   }
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < HO_VPT; ++i) s += x[i][0] + x[i][1] + x[i][2] + x[i][3];
-  const float mean = block_sum(s, red) / (float)w;
-  float q = 0.f;
+  // both moments in one reduction round, about a pivot (see norm_kernel)
+  const float pivot = row[0];
+  float s = 0.f, q = 0.f;
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) {
     if (threadIdx.x + i * 256 < n4) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { const float t = x[i][e] - mean; q += t * t; }
+      for (int e = 0; e < 4; ++e) { const float t = x[i][e] - pivot; s += t; q = fmaf(t, t, q); }
     }
   }
-  const float rstd = 1.0f / sqrtf(block_sum(q, red) / (float)w + 1e-6f);
+  block_sum2(s, q, red);
+  const float m1 = s / (float)w;
+  const float mean = pivot + m1;
+  const float rstd = 1.0f / sqrtf(fmaxf(q / (float)w - m1 * m1, 0.f) + 1e-6f);
   float acc[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
