@@ -780,6 +780,47 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
     sc[i] = ok ? ((const f32x4*)scp)[c4] : z4;
     sh[i] = ok ? ((const f32x4*)shp)[c4] : z4;
   }
+  // Operands of the later phases (output projection, sampler update, next step's input projection) are requested
+  // here, before the first barrier, when they fit in registers (bf16, D = 16, w <= 1024): the kernel then waits
+  // for memory once instead of once per phase.
+  constexpr bool CAN_PRE = sizeof(T) == 2;
+  const bool pre = CAN_PRE && D == 16 && w <= 1024;
+  const T* W = (const T*)a.w_out;
+  const T* w_in = (const T*)a.w_in;
+  bf16x8 wq[HO_VPT][4][2];
+  T wvn[4][16];
+  float bjn[4] = {0.f, 0.f, 0.f, 0.f};
+  float p_xt = 0.f, p_eps = 0.f, p_bout = 0.f;
+  size_t p_oi = 0;
+  if constexpr (CAN_PRE) {
+    if (pre) {
+#pragma unroll
+      for (int i = 0; i < HO_VPT; ++i) {
+        const int c4 = threadIdx.x + i * 256;
+        const int cc = (c4 < n4) ? c4 : 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int hq = 0; hq < 2; ++hq) wq[i][e][hq] = ((const bf16x8*)(W + (size_t)(cc * 4 + e) * 16))[hq];
+      }
+      if (threadIdx.x < 16) {
+        const int k = threadIdx.x;
+        p_bout = a.b_out[k];
+        p_xt = a.xt[(size_t)r * 16 + k];
+        p_oi = (size_t)(a.omap ? a.omap[r] : r) * 16 + k;
+        if (a.last || a.renoise) p_eps = a.eps_next[(size_t)(a.emap ? a.emap[r] : r) * 16 + k];
+      }
+      if (!a.last) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int c = (threadIdx.x + 256 * j < w) ? threadIdx.x + 256 * j : threadIdx.x;
+          bjn[j] = a.b_in[c];
+#pragma unroll
+          for (int k = 0; k < 16; ++k) wvn[j][k] = w_in[(size_t)k * w + c];
+        }
+      }
+    }
+  }
   // both moments in one reduction round, about a pivot (see norm_kernel)
   const float pivot = row[0];
   float s = 0.f, q = 0.f;
@@ -797,7 +838,6 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   float acc[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
-  const T* W = (const T*)a.w_out;
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) {
     const int c4 = threadIdx.x + i * 256;
@@ -806,7 +846,10 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
     for (int e = 0; e < 4; ++e) {
       const float y = (x[i][e] - mean) * rstd * (1.0f + sc[i][e]) + sh[i][e];
       const int c = c4 * 4 + e;
-      if (D == 16) {
+      if (CAN_PRE && pre) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) acc[k] += y * (float)wq[i][e][k >> 3][k & 7];
+      } else if (D == 16) {
         float wr[16];
         load_w16<T>(W + (size_t)c * 16, wr);
 #pragma unroll
@@ -827,17 +870,17 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   __syncthreads();
   if (threadIdx.x < D) {
     const int k = threadIdx.x;
-    const float v = part[0][k] + part[1][k] + part[2][k] + part[3][k] + a.b_out[k];
+    const float v = part[0][k] + part[1][k] + part[2][k] + part[3][k] + (pre ? p_bout : a.b_out[k]);
     const size_t xi = (size_t)r * D + k;
-    const size_t ei = (size_t)(a.emap ? a.emap[r] : r) * D + k;
-    const size_t oi = (size_t)(a.omap ? a.omap[r] : r) * D + k;
-    const float xt = a.xt[xi];
+    const size_t ei = pre ? 0 : (size_t)(a.emap ? a.emap[r] : r) * D + k;
+    const size_t oi = pre ? p_oi : (size_t)(a.omap ? a.omap[r] : r) * D + k;
+    const float xt = pre ? p_xt : a.xt[xi];
     const float x0 = xt - a.t * v;
     if (a.last) {
       a.mu[oi] = x0;
-      a.x[oi] = x0 + a.sigma * a.eps_next[ei];
+      a.x[oi] = x0 + a.sigma * (pre ? p_eps : a.eps_next[ei]);
     } else {
-      const float e = a.renoise ? a.eps_next[ei] : xt + (1.0f - a.t) * v;
+      const float e = a.renoise ? (pre ? p_eps : a.eps_next[ei]) : xt + (1.0f - a.t) * v;
       const float xn = (1.0f - a.t_next) * x0 + a.t_next * e;
       a.xt[xi] = xn;
       xs[k] = xn;
@@ -846,8 +889,17 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   if (a.last) return;
   __syncthreads();
   // input projection of the next step
-  const T* w_in = (const T*)a.w_in;
-  if (D <= 16) {
+  if (CAN_PRE && pre) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = threadIdx.x + 256 * j;
+      if (c >= w) continue;
+      float v = bjn[j];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) v += xs[k] * (float)wvn[j][k];
+      a.hh_next[(size_t)r * w + c] = v;
+    }
+  } else if (D <= 16) {
     // 4 columns per thread and pass, all 64 weight loads in flight together
     float xr[16];
 #pragma unroll
