@@ -133,8 +133,9 @@ int spec_kv_commit(fard_ctx* ctx, int32_t which, const int32_t* n_accept, int32_
  * draft; causal structure of Sec. 3.1).  Sample b owns n_q[b] consecutive rows; row j of a sample
  * sits at position cache_len[b] + j and attends to the cache and to rows 0..j.
  *   x_in     fp32 [M, D] latent rows         cond_id  int32 [M] or NULL; >= 0: the row is an id row
- *   n_q      device int32 [B], sum <= M      M <= max_batch * max(K+1, rows of a prefill pass)
- *   nq_max   host upper bound of n_q[b]; device values are clamped to it; bf16: nq_max * (H/H_kv) <= 64.
+ *   n_q      device int32 [B], sum <= M      M <= max(max_batch*(K+1), min(max_batch*max_ctx, 8192)) workspace rows
+ *   nq_max   host upper bound of n_q[b]; device values are clamped to it.  One attention workgroup holds
+ *            64 / (H/H_kv) rows of a sample (bf16); more rows per sample are taken in passes inside every layer.
  *            Capacity (cache_len + nq_max <= max_ctx) is checked against it on the host.
  *   commit   1: cache_len[b] += n_q[b]
  *   z_out    storage type [M, d_out]         shallow_out  fp32 [M, d] residual stream after layer
@@ -145,9 +146,10 @@ int spec_forward(fard_ctx* ctx, int32_t which, const float* x_in, const int32_t*
 
 /* Prefill: builds the KV cache of one model from a prefix of known tokens instead of loading it (the prefix that
  * Alg. 1 starts from; causal structure of Sec. 3.1).  Sample b's rows x[b, 0 .. n[b]-1, :] are appended at
- * positions cache_len[b] .. cache_len[b] + n[b] - 1; row j attends to the cache and to rows 0..j.  The prefix is
- * taken in passes of at most 64 / (n_heads / n_kv_heads) rows per sample (what one attention workgroup holds; 64 in
- * fp32), each a spec_forward with commit = 1, so the result is that of one causal forward over all rows.
+ * positions cache_len[b] .. cache_len[b] + n[b] - 1; row j attends to the cache and to rows 0..j.  Whole prefixes go
+ * through the layers at once while B of them fit into the workspace (8192 rows), else in passes of workspace / B rows
+ * per sample; inside a layer the attention takes 64 / (n_heads / n_kv_heads) rows of a sample at a time (what one
+ * attention workgroup holds).  The result is that of one causal forward over all rows.
  *   x        device fp32 [B, n_max, D] latent rows (rows at or beyond n[b] are not read)
  *   first_id device int32 [B] or NULL: >= 0 makes row 0 of the prefix an id row (class token); needs an id table
  *   n        HOST int32 [B], 0 <= n[b] <= n_max (copied before return)

@@ -50,6 +50,19 @@ __global__ void copy_i32_kernel(const int* src, int* dst, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = src[i];
 }
+// Attention passes over the rows of a forward with more rows per sample than one attention workgroup holds: pass p
+// takes rows [p cap, (p + 1) cap) of every sample.  start / cnt / len are [n_pass][B].
+__global__ void attn_pass_kernel(const int* __restrict__ row_start, const int* __restrict__ cache_len, int B, int cap, int n_pass,
+                                 int* __restrict__ start, int* __restrict__ cnt, int* __restrict__ len) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * n_pass) return;
+  const int p = i / B, b = i - p * B;
+  const int nq = row_start[b + 1] - row_start[b];
+  const int lo = min(p * cap, nq);
+  start[i] = row_start[b] + lo;
+  cnt[i] = min(max(nq - lo, 0), cap);
+  len[i] = cache_len[b] + lo;
+}
 // Prefill, one chunk: sample b contributes nq[b] = clamp(n[b] - c0, 0, chunk) rows.
 __global__ void prefill_chunk_kernel(const int* __restrict__ n, int c0, int chunk, int* __restrict__ nq, int B) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -220,6 +233,8 @@ struct fard_ctx {
   int m_max = 0;                           // rows of a round: max_batch * (K + 1)
   int m_rows = 0;                          // rows of the transformer workspace: max_batch * max(K + 1, prefill chunk)
   int *pf_n = nullptr, *pf_nq = nullptr;   // prefill: prefix lengths and the current chunk's row counts
+  int *ap_start = nullptr, *ap_cnt = nullptr, *ap_len = nullptr;   // attention passes [n_pass][B], ap_max entries each
+  int ap_max = 0;
   Model mdl[2];
   HeadW head;
   std::vector<void*> allocs;
@@ -635,6 +650,8 @@ constexpr int GEN_J_MAX = 64;            // resampling tries that the staged (gr
 constexpr int PART_MAX_SLICES = 8;      // K slices of a deferred residual update
 constexpr int PART_MAX_ROWS = 640;
 
+int cap_nq(const fard_ctx* c, int which);
+
 int alloc_workspace(fard_ctx* c) {
   const fard_round_cfg& g = c->cfg;
   const int M = c->m_max, MR = c->m_rows;
@@ -682,6 +699,11 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<int>(c, &c->emap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->omap, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->ent_blk, ENT_MAX_BLOCKS))) return rc;
+  // entries of the attention-pass arrays: n_pass * B <= rows / (rows of a pass) + B for any batch that fits
+  c->ap_max = c->m_rows / std::max(1, std::min(std::min(cap_nq(c, 0), cap_nq(c, 1)), c->m_rows)) + 2 * g.max_batch;
+  if ((rc = dalloc<int>(c, &c->ap_start, (size_t)c->ap_max))) return rc;
+  if ((rc = dalloc<int>(c, &c->ap_cnt, (size_t)c->ap_max))) return rc;
+  if ((rc = dalloc<int>(c, &c->ap_len, (size_t)c->ap_max))) return rc;
   if ((rc = dalloc<int>(c, &c->pf_n, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->pf_nq, g.max_batch))) return rc;
   const size_t bk = (size_t)g.max_batch * g.K;
@@ -776,9 +798,22 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
       HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE, t.rope_theta, c->maps.row_sample,
                                    c->maps.row_pos, M, m_dev));
     }
-    { Bracket br(c, CLS_ATTN);
+    const int acap = cap_nq(c, which);
+    if (nq_max <= acap) {
+      Bracket br(c, CLS_ATTN);
       HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, m.len, c->maps.row_start, B, nq_max, c->ao, HD,
-                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0)); }
+                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0));
+    } else {
+      // more rows per sample than one attention workgroup holds: passes of acap rows (c->ap_* hold their row ranges
+      // and first positions); each pass stores its own K / V rows before the next one reads them
+      const int n_pass = (nq_max + acap - 1) / acap;
+      for (int p = 0; p < n_pass; ++p) {
+        Bracket br(c, CLS_ATTN);
+        HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, c->ap_len + (size_t)p * B, c->ap_start + (size_t)p * B, B,
+                                   std::min(acap, nq_max - p * acap), c->ao, HD, (l + 1 == ent_layer) ? c->ent_heads : nullptr,
+                                   fused_append ? 1 : 0, c->ap_cnt + (size_t)p * B));
+      }
+    }
     // norm 2 without a launch of its own, when both GEMMs around it run in the narrow kernel: the output
     // projection also leaves the updated stream as bf16, and the up-projection (weights pre-scaled by the norm's
     // gain) sums the row statistics from its activation fragments and applies them in its epilogue
@@ -833,8 +868,13 @@ int cap_nq(const fard_ctx* c, int which) {
   const fard_tf_cfg& t = c->mdl[which].c;
   return c->bf16 ? 64 / (t.n_heads / t.n_kv_heads) : 1 << 20;
 }
-// Rows per sample that one prefill pass takes: what one attention workgroup holds, at most 64.
-int prefill_chunk(const fard_ctx* c, int which) { return std::min(std::min(cap_nq(c, which), 64), c->cfg.max_ctx); }
+// Rows of the transformer workspace: a round's rows, or up to PREFILL_ROWS rows of a prefill pass (whole prefixes when
+// they fit, so that the GEMMs of a prefill see thousands of rows whatever the attention kernel's own row limit is).
+constexpr int PREFILL_ROWS = 8192;
+int workspace_rows(const fard_round_cfg& g) {
+  const long all = (long)g.max_batch * g.max_ctx;
+  return (int)std::max<long>((long)g.max_batch * (g.K + 1), std::min<long>(all, PREFILL_ROWS));
+}
 
 // S sampler steps of the head over n rows of z (compact), noise / output rows through emap / omap.
 int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* eps, size_t eps_step_stride,
@@ -923,7 +963,7 @@ int spec_round_init(const fard_round_cfg* cfg, const fard_tensor* weights, int32
   if (c->bf16 && (hc.width % 64 != 0 || hc.d_cond % 64 != 0)) return bail(fail(c, FARD_ESHAPE, "bf16 head widths must be multiples of 64"));
   if (!(hc.sigma_last > 0.f)) return bail(fail(c, FARD_EINVAL, "sigma_last must be > 0"));
   c->m_max = cfg->max_batch * (cfg->K + 1);
-  c->m_rows = cfg->max_batch * std::max(cfg->K + 1, std::max(prefill_chunk(c, FARD_TARGET), prefill_chunk(c, FARD_DRAFT)));
+  c->m_rows = workspace_rows(*cfg);
 
   Loader ld;
   ld.c = c;
@@ -1029,7 +1069,9 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
   Model& m = c->mdl[which];
   if (cond_id && !m.cond) return fail(c, FARD_EINVAL, "cond_id given but the model has no id table");
   if (nq_max < 1) return fail(c, FARD_EINVAL, "nq_max < 1");
-  if (nq_max > cap_nq(c, which)) return fail(c, FARD_ESHAPE, "nq_max * (n_heads / n_kv_heads) > 64");
+  const int acap = cap_nq(c, which);
+  const int n_pass = (std::min(nq_max, M) + acap - 1) / acap;
+  if ((long)n_pass * B > c->ap_max) return fail(c, FARD_ESHAPE, "nq_max beyond the attention passes the workspace holds");
   const int cap = std::min(nq_max, M);
   if (m.len_hi + cap > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "cache_len + n_q may exceed max_ctx");
   if (m.c.pos == FARD_POS_LEARNED && m.len_hi + cap > m.c.max_pos) return fail(c, FARD_ECAPACITY, "position beyond the learned table");
@@ -1037,6 +1079,12 @@ int spec_forward(fard_ctx* c, int32_t which, const float* x_in, const int32_t* c
   { Bracket br(c, CLS_OTHER);
     HIPCHK(c, launch_build_rows(s, n_q, 0, B, c->cfg.K, m.c.d_latent, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, M, cap)); }
   const int* md = c->maps.m_total;
+  if (n_pass > 1) {
+    Bracket br(c, CLS_OTHER);
+    attn_pass_kernel<<<(B * n_pass + 255) / 256, 256, 0, s>>>(c->maps.row_start, m.len, B, acap, n_pass, c->ap_start, c->ap_cnt,
+                                                               c->ap_len);
+    HIPCHK(c, hipGetLastError());
+  }
   HIPCHK(c, embed_first_norm(c, which, x_in, m.c.d_latent, cond_id, M, md));
   const int ls = c->cfg.entropy_layer;
   const bool want_sh = (shallow_out || h_attn_out) && ls <= m.c.n_layers;
@@ -1086,7 +1134,8 @@ int spec_prefill(fard_ctx* c, int32_t which, const float* x, const int32_t* firs
   hipStream_t s = c->stream;
   HIPCHK(c, hipMemcpyAsync(c->pf_n, n, (size_t)B * 4, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipStreamSynchronize(s));      // the host array may go away after return
-  const int chunk = prefill_chunk(c, which), D = m.c.d_latent, ldz = m.d_out();
+  // rows per sample of one pass through the layers: whole prefixes when B of them fit into the workspace
+  const int chunk = std::max(1, std::min(c->m_rows / B, c->cfg.max_ctx)), D = m.c.d_latent, ldz = m.d_out();
   for (int c0 = 0; c0 < n_hi; c0 += chunk) {
     const int cap = std::min(chunk, n_hi - c0);
     int M = 0;

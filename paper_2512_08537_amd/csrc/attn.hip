@@ -26,8 +26,9 @@ namespace {
 template <int DH, int NQB>
 __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
                                                         const int* __restrict__ cache_len,
-                                                        const int* __restrict__ row_start, bf16* __restrict__ out,
-                                                        int ldo, float* __restrict__ ent_heads, int append) {
+                                                        const int* __restrict__ row_start, const int* __restrict__ row_cnt,
+                                                        bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads,
+                                                        int append) {
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   const int G = n_heads / Hk;
   const int b = blockIdx.x / Hk, hk = blockIdx.x - b * Hk;
   const int r0 = row_start[b];
-  const int nq = row_start[b + 1] - r0;
+  const int nq = row_cnt ? row_cnt[b] : row_start[b + 1] - r0;     // (row_cnt: a pass over part of the sample's rows)
   if (nq <= 0) return;
   const int p0 = cache_len[b];
   const int ncols = nq * G;                       // column c <-> (query head hk*G + c / nq, row c % nq)
@@ -270,12 +271,13 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
 // fp32 path: one wave per (row, head).
 __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
                                                       const int* __restrict__ cache_len,
-                                                      const int* __restrict__ row_start, int B, float* __restrict__ out,
+                                                      const int* __restrict__ row_start, const int* __restrict__ row_cnt,
+                                                      int B, float* __restrict__ out,
                                                       int ldo, float* __restrict__ ent_heads, int max_keys) {
   extern __shared__ float s_p[];                 // [max_keys] scores / probabilities
   const int head = blockIdx.x, b = blockIdx.z, j = blockIdx.y;
   const int r0 = row_start[b];
-  const int nq = row_start[b + 1] - r0;
+  const int nq = row_cnt ? row_cnt[b] : row_start[b + 1] - r0;
   if (j >= nq) return;
   const int Hk = kv.n_kv_heads, dh = kv.d_head;
   const int hk = (head * Hk) / n_heads;
@@ -316,14 +318,15 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 }  // namespace
 
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv, const int* cache_len,
-                            const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads, int append) {
+                            const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads, int append,
+                            const int* row_cnt) {
   if (B <= 0 || nq_max <= 0) return hipSuccess;
   if (!kv.is_bf16) {
     if (append) return hipErrorInvalidValue;
     dim3 grid(n_heads, nq_max, B);
     const size_t smem = (size_t)kv.ctx_pad * sizeof(float);
     if (smem > 64 * 1024) return hipErrorInvalidValue;
-    attn_f32_kernel<<<grid, 64, smem, s>>>((const float*)qkv, ld, n_heads, kv, cache_len, row_start, B, (float*)out,
+    attn_f32_kernel<<<grid, 64, smem, s>>>((const float*)qkv, ld, n_heads, kv, cache_len, row_start, row_cnt, B, (float*)out,
                                            ldo, ent_heads, kv.ctx_pad);
     return hipGetLastError();
   }
@@ -334,14 +337,14 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
   const bf16* q = (const bf16*)qkv;
   bf16* o = (bf16*)out;
   if (kv.d_head == 64) {
-    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
-    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
+    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
+    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
   } else if (kv.d_head == 128) {
-    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
-    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
+    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
+    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
   } else if (kv.d_head == 32) {
-    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
-    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, o, ldo, ent_heads, append);
+    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
+    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
   } else {
     return hipErrorInvalidValue;
   }

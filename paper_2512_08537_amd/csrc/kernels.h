@@ -88,9 +88,11 @@ hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v
 // out_T[r, g*dh + :].  ent_heads[r, g] (optional) receives the entropy of the attention row.
 // append != 0 (bf16 caches, no RoPE): the kernel itself stores the new rows' K and V at positions
 // cache_len[b] .. + n_q - 1 before it reads them, replacing a separate launch_rope_append.
+// row_cnt (optional): sample b contributes row_cnt[b] rows starting at row_start[b] (a pass over part of a sample's
+// rows; cache_len[b] is then the position of the first of them); without it the rows are row_start[b] .. row_start[b+1].
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv,
                             const int* cache_len, const int* row_start, int B, int nq_max,
-                            void* out, int ldo, float* ent_heads, int append);
+                            void* out, int ldo, float* ent_heads, int append, const int* row_cnt = nullptr);
 
 // Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
 // Up to ENT_SAMPLE_MODE_MIN_B samples: a wave per row, then one workgroup thresholds and compacts.  Above: a
