@@ -14,6 +14,7 @@ __global__ __launch_bounds__(256) void build_rows_kernel(const int* n_base, int 
                                                          const float* x_first, const float* x_rest,
                                                          float* x_out, int* aux_row, int m_max, int nq_cap) {
   __shared__ int s_scan[256];
+  __shared__ int s_len[256];
   __shared__ int s_carry;
   const int tid = threadIdx.x;
   if (tid == 0) s_carry = 0;
@@ -38,18 +39,39 @@ __global__ __launch_bounds__(256) void build_rows_kernel(const int* n_base, int 
     const int start = carry + s_scan[tid] - nq;
     if (b < B) {
       maps.row_start[b] = start < m_max ? start : m_max;
-      const int len = cache_len[b];
-      for (int j = 0; j < nq; ++j) {
-        const int r = start + j;
+      s_len[tid] = cache_len[b];
+    }
+    __syncthreads();
+    // the rows of these 256 samples, dealt to the threads: row -> sample by bisection of the inclusive scan
+    const int block_total = s_scan[255];
+    auto sample_of = [&](int rl, int& jj) {
+      int lo = 0, hi = 255;                        // smallest i with s_scan[i] > rl
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (s_scan[mid] > rl) hi = mid; else lo = mid + 1;
+      }
+      jj = rl - (lo ? s_scan[lo - 1] : 0);
+      return lo;
+    };
+    for (int rl = tid; rl < block_total; rl += 256) {
+      const int r = carry + rl;
+      if (r >= m_max) break;
+      int jj;
+      const int i = sample_of(rl, jj);
+      maps.row_sample[r] = base + i;
+      maps.row_j[r] = jj;
+      maps.row_pos[r] = s_len[i] + jj;
+      if (aux_row) aux_row[r] = (base + i) * (K + 1) + jj;
+    }
+    if (x_out) {
+      for (int e = tid; e < block_total * D; e += 256) {
+        const int rl = e / D, cc = e - rl * D;
+        const int r = carry + rl;
         if (r >= m_max) break;
-        maps.row_sample[r] = b;
-        maps.row_j[r] = j;
-        maps.row_pos[r] = len + j;
-        if (aux_row) aux_row[r] = b * (K + 1) + j;
-        if (x_out) {
-          const float* src = (j == 0) ? x_first + (size_t)b * D : x_rest + ((size_t)b * K + (j - 1)) * D;
-          for (int c = 0; c < D; ++c) x_out[(size_t)r * D + c] = src[c];
-        }
+        int jj;
+        const int i = sample_of(rl, jj);
+        const float* src = (jj == 0) ? x_first + (size_t)(base + i) * D : x_rest + ((size_t)(base + i) * K + (jj - 1)) * D;
+        x_out[(size_t)r * D + cc] = src[cc];
       }
     }
     __syncthreads();
