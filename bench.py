@@ -141,6 +141,21 @@ def main():
                 "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
                 "flops_per_byte": round(intensity, 1), "achieved_TFLOPs": round(g_tflops, 3),
                 "frac_mfma": round(g_tflops / peak, 5), "achieved_GBs": round(g_gbs, 1)}
+    # what this machine sustains on the two roofs (a 1 GiB streaming read, a register-only bf16 MFMA loop): `frac` stays
+    # against the published peaks, the probed ones are reported beside it
+    probe_buf = torch.empty(1 << 28, device="cuda", dtype=torch.float32)
+    probe_buf.zero_()
+    torch.cuda.synchronize()
+    rd_ms, rd_bytes = ctx.spec_peak_probe(0, probe_buf, reps=10)
+    mf_ms, mf_flop = ctx.spec_peak_probe(1, iters=4096, reps=5)
+    del probe_buf
+    probed_gbs = rd_bytes / (rd_ms * 1e-3) / 1e9
+    probed_tflops = mf_flop / (mf_ms * 1e-3) / 1e12
+    roofline["probed_peak"] = {"hbm_read_GBs": round(probed_gbs, 1), "mfma_bf16_TFLOPs": round(probed_tflops, 1)}
+    if hbm_bound:
+        roofline["frac_of_probed"] = round(g_gbs / probed_gbs, 5)
+    elif rc.dtype == 1:
+        roofline["frac_of_probed"] = round(g_tflops / probed_tflops, 5)
     # attention: algorithmic K/V bytes of the verify forward + the K draft steps
     t, d = rc.target, rc.draft
     esz = 2 if rc.dtype == 1 else 4
@@ -155,6 +170,7 @@ def main():
                for k, v in prof.items()}
     kernels["attention"]["achieved_GBs"] = round(att_gbs, 1)
     kernels["attention"]["frac_hbm"] = round(att_gbs / PEAK_HBM_GBS, 5)
+    kernels["attention"]["frac_hbm_probed"] = round(att_gbs / probed_gbs, 5)
 
     # Steps 1-5 over several rounds without a host synchronisation (spec_generate): tokens per second including the
     # closing token of every round; as many rounds as the cache capacity bound allows from n_ctx, at most 16

@@ -302,6 +302,18 @@ int spec_entropy_loss(fard_ctx* ctx, const void* q, const void* k, int32_t B, in
 int spec_smooth_l1(fard_ctx* ctx, const void* pred, const void* target, int64_t n, float beta, float* loss,
                    float* dpred);
 
+/* Peak probes for the roofline of Sec. 3's round (no operation of the method; measurement only): what this GPU
+ * sustains on the two resources the kernels are priced against, timed with HIP events on the context's stream.
+ *   kind 0: streaming read of buf (device, 16-byte aligned, bytes a positive multiple of 16; read only), 16 B per
+ *           lane per load over 2048 workgroups; units_per_launch = bytes.
+ *   kind 1: register-only loop of bf16 32x32x16 MFMAs, 4 * iters per wave over 2048 workgroups of four waves;
+ *           units_per_launch = flop.  buf and bytes are ignored.
+ * One warm-up launch, then reps timed launches; *ms_per_launch (host) is their average, *units_per_launch (host)
+ * the bytes or flop of one launch.  Blocks the host until done; allocates a few KB inside the context on first
+ * use (not for capture). */
+int spec_peak_probe(fard_ctx* ctx, int32_t kind, const void* buf, int64_t bytes, int32_t iters, int32_t reps,
+                    float* ms_per_launch, double* units_per_launch);
+
 /* Per-kernel timing with HIP events on the context's stream.  enable = 1 brackets every launch of
  * the named kernel class between two events; spec_profile_read synchronises and returns the
  * accumulated time (ms) and launch count since enable, then clears them.

@@ -74,6 +74,7 @@ _SIGS = {
     "spec_entropy_loss": [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "spec_smooth_l1": [_vp, _vp, _vp, C.c_int64, _f32, _vp, _vp],
     "spec_prefill": [_vp, _i32, _vp, _vp, C.POINTER(C.c_int32), _i32, _i32, _vp],
+    "spec_peak_probe": [_vp, _i32, _vp, C.c_int64, _i32, _i32, C.POINTER(C.c_float), C.POINTER(C.c_double)],
     "spec_profile_enable": [_vp, _i32],
     "spec_profile_read": [_vp, _i32, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_double),
                           C.POINTER(C.c_double)],
@@ -406,6 +407,13 @@ class Context:
 
     def spec_graph_enable(self, on: bool):
         self._chk(lib.spec_graph_enable(self.h, 1 if on else 0))
+
+    def spec_peak_probe(self, kind: int, buf=None, iters: int = 0, reps: int = 10):
+        """kind 0: streaming read of the device tensor buf; kind 1: MFMA loop.  Returns (ms per launch, bytes or flop per launch)."""
+        ms, units = C.c_float(), C.c_double()
+        nbytes = 0 if buf is None else buf.numel() * buf.element_size()
+        self._chk(lib.spec_peak_probe(self.h, kind, _ptr(buf), nbytes, iters, reps, C.byref(ms), C.byref(units)))
+        return ms.value, units.value
 
     def spec_profile_enable(self, on: bool):
         self._chk(lib.spec_profile_enable(self.h, int(on)))

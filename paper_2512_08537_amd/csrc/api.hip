@@ -1684,6 +1684,41 @@ int spec_gemm_norm(fard_ctx* c, const void* x, const void* W, const float* g, co
   return FARD_OK;
 }
 
+int spec_peak_probe(fard_ctx* c, int32_t kind, const void* buf, int64_t bytes, int32_t iters, int32_t reps, float* ms_per_launch,
+                    double* units_per_launch) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (kind != 0 && kind != 1) return fail(c, FARD_EINVAL, "kind must be 0 (read) or 1 (MFMA)");
+  if (reps < 1 || reps > 1000) return fail(c, FARD_EINVAL, "1 <= reps <= 1000 required");
+  if (!ms_per_launch || !units_per_launch) return fail(c, FARD_EINVAL, "null argument");
+  if (kind == 0 && (!buf || bytes < 16 || bytes % 16 != 0 || ((uintptr_t)buf & 15))) return fail(c, FARD_ESHAPE, "buf: 16-byte aligned, bytes a positive multiple of 16");
+  if (kind == 1 && (iters < 1 || iters > (1 << 20))) return fail(c, FARD_EINVAL, "1 <= iters <= 2^20 required");
+  const int blocks = 2048;  // eight workgroups of four waves per compute unit
+  int rc = loss_scratch(c, probe_sink_bytes(kind, blocks));
+  if (rc) return rc;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  HIPCHK(c, hipEventCreate(&e0));
+  if (hipEventCreate(&e1) != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    return fail(c, FARD_EHIP, "hipEventCreate failed");
+  }
+  hipError_t err = hipSuccess;
+  for (int r = -1; r < reps && err == hipSuccess; ++r) {  // launch -1 warms up
+    if (r == 0) err = hipEventRecord(e0, c->stream);
+    if (err == hipSuccess) err = kind == 0 ? launch_probe_read(c->stream, buf, (long)bytes, blocks, c->loss_tmp) : launch_probe_mfma(c->stream, iters, blocks, c->loss_tmp);
+  }
+  if (err == hipSuccess) err = hipEventRecord(e1, c->stream);
+  if (err == hipSuccess) err = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (err == hipSuccess) err = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (err != hipSuccess) return fail(c, FARD_EHIP, hipGetErrorString(err));
+  *ms_per_launch = ms / reps;
+  // one 32x32x16 MFMA is 2*32*32*16 flop; four per iteration per wave, four waves per workgroup
+  *units_per_launch = kind == 0 ? (double)bytes : (double)blocks * 4.0 * 4.0 * (double)iters * 32768.0;
+  return FARD_OK;
+}
+
 int spec_profile_enable(fard_ctx* c, int32_t enable) {
   if (check_ctx(c)) return FARD_EINVAL;
   HIPCHK(c, hipStreamSynchronize(c->stream));

@@ -189,4 +189,9 @@ hipError_t launch_entropy_loss(hipStream_t s, const void* q, const void* k, int 
 hipError_t launch_smooth_l1(hipStream_t s, int is_bf16, const void* pred, const void* target, long n, float beta, float* partial,
                             int n_part, float* loss, float* dpred);
 
+// Peak probes (a streaming read, a register-only MFMA loop); sink: probe_sink_bytes(kind, blocks) bytes of scratch.
+size_t probe_sink_bytes(int kind, int blocks);
+hipError_t launch_probe_read(hipStream_t s, const void* buf, long bytes, int blocks, void* sink);
+hipError_t launch_probe_mfma(hipStream_t s, int iters, int blocks, void* sink);
+
 }  // namespace fard

@@ -4,6 +4,7 @@
   python -m paper_2512_08537_amd.kernel_bench entropy     # entropy pre-filter: config shapes + 2^20-row shape
   python -m paper_2512_08537_amd.kernel_bench narrow      # narrow-tile GEMM launches (time them with rocprofv3 --kernel-trace)
   python -m paper_2512_08537_amd.kernel_bench losses      # attention-entropy loss + gradients at training shapes
+  python -m paper_2512_08537_amd.kernel_bench peaks       # probed peaks: streaming read GB/s, bf16 MFMA TFLOP/s
   python -m paper_2512_08537_amd.kernel_bench copy        # 256 MiB copy: calibration of the HBM traffic counters
 
 Prints one JSON line per measurement: algorithmic bytes / HIP-event time on the library's stream.
@@ -88,6 +89,26 @@ def copy():
     print(json.dumps({"kernel": "torch copy_", "bytes_read": n * 4, "bytes_written": n * 4, "launches": 5}), flush=True)
 
 
+def peaks():
+    """What the box sustains on the two roofs: a streaming read over several sizes, a register-only bf16 MFMA loop."""
+    import torch
+    from tests.harness import build_case, make_ctx
+    ctx = make_ctx(build_case("ln-gelu-bf16", seed=0))
+    for mib in (64, 256, 1024, 4096):
+        buf = torch.zeros(mib << 18, device="cuda", dtype=torch.float32)
+        torch.cuda.synchronize()
+        ms, nbytes = ctx.spec_peak_probe(0, buf, reps=10)
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        print(json.dumps({"probe": "streaming read", "MiB": mib, "us": round(ms * 1e3, 2), "GBs": round(gbs, 1),
+                          "frac_of_published_hbm": round(gbs / PEAK_HBM_GBS, 4)}), flush=True)
+        del buf
+    for iters in (1024, 4096, 16384):
+        ms, flop = ctx.spec_peak_probe(1, iters=iters, reps=5)
+        tf = flop / (ms * 1e-3) / 1e12
+        print(json.dumps({"probe": "bf16 mfma 32x32x16", "iters": iters, "us": round(ms * 1e3, 2), "TFLOPs": round(tf, 1),
+                          "frac_of_published_bf16": round(tf / 2500.0, 4)}), flush=True)
+
+
 def losses():
     """The attention-entropy loss with both gradients at the draft's training shapes (batch x heads x sequence x head
     dim); flops = score tiles (forward, and once more per gradient) + the two second products, causal half only."""
@@ -119,4 +140,4 @@ def losses():
 
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "entropy"
-    {"entropy": entropy, "narrow": narrow, "copy": copy, "losses": losses}[what]()
+    {"entropy": entropy, "narrow": narrow, "copy": copy, "losses": losses, "peaks": peaks}[what]()

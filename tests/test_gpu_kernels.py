@@ -376,3 +376,27 @@ def test_accept_matches_oracle_on_identical_inputs(ctx_bf16):
     ctx.sync()
     assert np.array_equal(n_acc.cpu().numpy(), n_keep)
     assert np.abs(lr.cpu().numpy()).max() == 0.0
+
+
+def test_peak_probes_report_physical_rates(ctx_bf16):
+    """The probes time real work: a read of a buffer far larger than every cache stays under the published HBM peak,
+    the MFMA loop under the published bf16 peak, and both are within an order of magnitude of them."""
+    import torch
+    ctx, _ = ctx_bf16
+    from paper_2512_08537_amd.binding import FardError
+    buf = torch.zeros(1 << 28, device="cuda", dtype=torch.float32)      # 1 GiB
+    torch.cuda.synchronize()
+    ms, nbytes = ctx.spec_peak_probe(0, buf, reps=5)
+    assert nbytes == float(1 << 30) and ms > 0
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    assert 800.0 < gbs < 8000.0 * 1.02, gbs
+    ms, flop = ctx.spec_peak_probe(1, iters=2048, reps=3)
+    assert flop == 2048.0 * 16 * 2048 * 32768 and ms > 0
+    tf = flop / (ms * 1e-3) / 1e12
+    assert 250.0 < tf < 2500.0 * 1.02, tf
+    with pytest.raises(FardError):
+        ctx.spec_peak_probe(0, buf[1:9], reps=1)                   # 32 bytes at a 4-byte offset: misaligned
+    with pytest.raises(FardError):
+        ctx.spec_peak_probe(1, iters=0, reps=1)
+    with pytest.raises(FardError):
+        ctx.spec_peak_probe(2, buf, reps=1)
