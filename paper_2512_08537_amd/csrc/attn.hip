@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
         s[e] = (key <= lim) ? s[e] * scale : -INFINITY;
         bmax = fmaxf(bmax, s[e]);
       }
-      bmax = fmaxf(bmax, __shfl_xor(bmax, 32, WAVE));
+      bmax = xor32_max(bmax);
       const float m_new = fmaxf(m_run[qb], bmax);
       float psum = 0.f, asum = 0.f;
       bf16x8 pf[2];
@@ -157,8 +157,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
           asum += (s[e] == -INFINITY) ? 0.f : p * t;
           pf[e >> 3][e & 7] = (bf16)p;
         }
-        psum += __shfl_xor(psum, 32, WAVE);
-        asum += __shfl_xor(asum, 32, WAVE);
+        psum = xor32_sum(psum);
+        asum = xor32_sum(asum);
         float corr = 1.f;
         if (m_run[qb] != -INFINITY) {
           const float dl = m_run[qb] - m_new;

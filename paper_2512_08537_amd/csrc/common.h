@@ -37,16 +37,71 @@ __device__ __forceinline__ float apply_act(float x, int act) {
   return act == ACT_GELU ? gelu_erf(x) : (act == ACT_SILU ? silu(x) : x);
 }
 
-// butterfly reductions over the 64 lanes of a wavefront
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+// Reductions over the 64 lanes of a wavefront without a trip through the LDS crossbar: four data-parallel-primitive
+// steps make every row of 16 lanes uniform (neighbour, neighbouring pair, mirrored half row, mirrored row), then the
+// four row values are read as scalars.  All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+constexpr int DPP_SWAP1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int DPP_SWAP2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141; // lane i of a group of 8 reads lane 7 - i
+constexpr int DPP_MIRROR = 0x140;      // lane i of a row of 16 reads lane 15 - i
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<DPP_SWAP1>(v);
+  v += dpp_move<DPP_SWAP2>(v);
+  v += dpp_move<DPP_HALF_MIRROR>(v);
+  v += dpp_move<DPP_MIRROR>(v);
   return v;
 }
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_move<DPP_SWAP1>(v));
+  v = fmaxf(v, dpp_move<DPP_SWAP2>(v));
+  v = fmaxf(v, dpp_move<DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_move<DPP_MIRROR>(v));
   return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
+}
+__device__ __forceinline__ float wave_max(float v) {
+  v = row16_max(v);
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
+}
+// The same over each half of the wave (lanes 0-31, lanes 32-63): every lane gets its own half's result.
+__device__ __forceinline__ float half_sum(float v) {
+  v = row16_sum(v);
+  const float lo = lane_value(v, 0) + lane_value(v, 16), hi = lane_value(v, 32) + lane_value(v, 48);
+  return (threadIdx.x & 32) ? hi : lo;
+}
+__device__ __forceinline__ float half_max(float v) {
+  v = row16_max(v);
+  const float lo = fmaxf(lane_value(v, 0), lane_value(v, 16)), hi = fmaxf(lane_value(v, 32), lane_value(v, 48));
+  return (threadIdx.x & 32) ? hi : lo;
+}
+// Exchanges between the halves of the wave (lanes l and l ^ 32) and between neighbouring rows of 16 (l and l ^ 16)
+// by one register swap each: after swapping a value with itself, one result holds the lower partner's value in
+// both places and the other the upper partner's.
+__device__ __forceinline__ float other_half(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+  return __int_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float xor32_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+  return __int_as_float(r[0]) + __int_as_float(r[1]);
+}
+__device__ __forceinline__ float xor32_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+  return fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+}
+__device__ __forceinline__ float xor16_sum(float v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(v), __float_as_int(v), false, false);
+  return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
 // effective row count: host upper bound clipped by an optional device-side count

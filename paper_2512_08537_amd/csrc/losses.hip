@@ -127,9 +127,9 @@ __global__ __launch_bounds__(256) void ent_stats_kernel(const bf16* __restrict__
     }
   }
   Stat o;
-  o.m = __shfl_xor(st.m, 32, WAVE);
-  o.l = __shfl_xor(st.l, 32, WAVE);
-  o.a = __shfl_xor(st.a, 32, WAVE);
+  o.m = other_half(st.m);
+  o.l = other_half(st.l);
+  o.a = other_half(st.a);
   stat_merge(st, o);
   if (hh == 0) {
     const float ll = __logf(st.l);

@@ -221,10 +221,8 @@ __global__ __launch_bounds__(256, (LNF && NS == 8) ? 2 : 1) void gemm_narrow_ker
   if constexpr (LNF) {
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-      s1[i] += __shfl_xor(s1[i], 16, WAVE);
-      s1[i] += __shfl_xor(s1[i], 32, WAVE);
-      s2[i] += __shfl_xor(s2[i], 16, WAVE);
-      s2[i] += __shfl_xor(s2[i], 32, WAVE);
+      s1[i] = xor32_sum(xor16_sum(s1[i]));
+      s2[i] = xor32_sum(xor16_sum(s2[i]));
       if (lane < 16) {
         stat[(kw * 16 * MT + 16 * i + lane) * 2] = s1[i];
         stat[(kw * 16 * MT + 16 * i + lane) * 2 + 1] = s2[i];

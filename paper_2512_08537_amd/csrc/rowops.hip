@@ -428,6 +428,55 @@ __device__ __forceinline__ float ent_row_regs(const typename EntVec<T>::type (&v
   return __logf(l) - LN2 * a / l;
 }
 
+// Half a wave per row: lane l32 of the half holds pieces l32, l32 + 32, ... (up to ENT_NCH2), so that the two halves
+// of a wave fold two rows at once and share the reductions' instructions.
+constexpr int ENT_NCH2 = 8;
+template <typename T>
+__device__ __forceinline__ void ent_fetch_half(const T* __restrict__ row, int nvec, int l32,
+                                               typename EntVec<T>::type (&v)[ENT_NCH2]) {
+  using Vec = typename EntVec<T>::type;
+  const Vec* rv = (const Vec*)row;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH2; ++j) {
+    if (j * 32 < nvec) {                          // the same for every lane
+      const int c = j * 32 + l32;
+      v[j] = rv[c < nvec ? c : nvec - 1];
+    }
+  }
+}
+template <typename T>
+__device__ __forceinline__ float ent_row_half(const typename EntVec<T>::type (&v)[ENT_NCH2], int nvec, int l32) {
+  constexpr int VE = 16 / sizeof(T);
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH2; ++j) {
+    if (j * 32 < nvec) {
+      if (j * 32 + l32 < nvec) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) mx = fmaxf(mx, (float)v[j][i]);
+      }
+    }
+  }
+  const float m2 = half_max(mx) * LOG2E;
+  float l = 0.f, a = 0.f;
+#pragma unroll
+  for (int j = 0; j < ENT_NCH2; ++j) {
+    if (j * 32 < nvec) {
+      if (j * 32 + l32 < nvec) {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) {
+          const float t = fmaf((float)v[j][i], LOG2E, -m2), e = __builtin_amdgcn_exp2f(t);
+          l += e;
+          a = fmaf(e, t, a);
+        }
+      }
+    }
+  }
+  l = half_sum(l);
+  a = half_sum(a);
+  return __logf(l) - LN2 * a / l;
+}
+
 template <typename T>
 __device__ __forceinline__ float row_entropy_wave(const T* __restrict__ row, int L, int lane) {
   Mla s{-INFINITY, 0.f, 0.f};
@@ -520,16 +569,17 @@ __global__ __launch_bounds__(256) void prefilter_tail_kernel(const float* __rest
   if (tid == 0) *n_surv = carry;
 }
 
-// Large batches: one wave per sample walks its K rows and applies the prefix rule itself; workgroup
-// `blockIdx.x` owns the samples [blockIdx.x * spb, (blockIdx.x + 1) * spb) and records how many drafts they
-// kept.  PIPE: every row is at most ENT_NCH * 64 aligned 16-byte pieces, and the loads of the wave's next row
-// are issued before the current row is folded.
+// Large batches: a wave (PIPE: half a wave) per sample walks its K rows and applies the prefix rule itself;
+// workgroup `blockIdx.x` owns the samples [blockIdx.x * spb, (blockIdx.x + 1) * spb) and records how many drafts
+// they kept.  PIPE: every row is at most ENT_NCH2 * 32 aligned 16-byte pieces; the eight half waves of the
+// workgroup take the samples b0 + slot, b0 + slot + 8, ..., and the loads of a half's next row are issued before its
+// current row is folded (two register sets, taking turns).
 template <typename T, bool PIPE>
 __global__ __launch_bounds__(256) void entropy_samples_kernel(const T* __restrict__ feat, int B, int K, int L,
                                                               float tau, int spb, float* __restrict__ H,
                                                               uint8_t* __restrict__ keep, int* __restrict__ n_keep,
                                                               int* __restrict__ blk_cnt) {
-  __shared__ int s_cnt[4];
+  __shared__ int s_cnt[8];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b0 = blockIdx.x * spb, b1 = min(B, b0 + spb);
   int total = 0;
@@ -537,35 +587,42 @@ __global__ __launch_bounds__(256) void entropy_samples_kernel(const T* __restric
     constexpr int VE = 16 / sizeof(T);
     using Vec = typename EntVec<T>::type;
     const int nvec = L / VE;
-    const int nb = (b1 - b0 - wave + 3) / 4;       // samples of this wave: b0 + wave + 4 j
+    const int l32 = lane & 31, slot = wave * 2 + (lane >> 5);
+    const int nb = (b1 - b0 - wave * 2 + 7) / 8;   // samples of the wave's first half: never fewer than the second's
     const int nq = nb > 0 ? nb * K : 0;
-    Vec cur[ENT_NCH], nxt[ENT_NCH];
-    if (nq > 0) ent_fetch<T>(feat + (size_t)(b0 + wave) * K * L, 0, nvec, lane, cur);
+    Vec va[ENT_NCH2], vb[ENT_NCH2];
     bool alive = true;
-    int cnt = 0, i = 0, b = b0 + wave;
-    for (int q = 0; q < nq; ++q) {
-      const size_t r = (size_t)b * K + i;
-      const int in = (i + 1 == K) ? 0 : i + 1, bn = (i + 1 == K) ? b + 4 : b;
-      if (q + 1 < nq) ent_fetch<T>(feat + ((size_t)bn * K + in) * L, 0, nvec, lane, nxt);
+    int cnt = 0, i = 0, b = b0 + slot;
+    // a half without a sample left reads the workgroup's last sample again and writes nothing
+    auto row_of = [&](int bb, int ii) { return feat + ((size_t)min(bb, b1 - 1) * K + ii) * L; };
+    auto step = [&](Vec (&cur)[ENT_NCH2], Vec (&nxt)[ENT_NCH2], bool more) {
+      const int in = (i + 1 == K) ? 0 : i + 1, bn = (i + 1 == K) ? b + 8 : b;
+      if (more) ent_fetch_half<T>(row_of(bn, in), nvec, l32, nxt);
       __builtin_amdgcn_sched_barrier(0);
-      const float h = ent_row_regs<T>(cur, nvec, lane);
+      const float h = ent_row_half<T>(cur, nvec, l32);
+      const bool live = b < b1;
+      const size_t r = (size_t)b * K + i;
       alive = alive && !(h < tau);
       cnt += alive ? 1 : 0;
-      if (lane == 0) {
+      if (l32 == 0 && live) {
         H[r] = h;
         keep[r] = alive ? 1 : 0;
       }
       if (in == 0) {
-        if (lane == 0) n_keep[b] = cnt;
-        total += cnt;
+        if (l32 == 0 && live) n_keep[b] = cnt;
+        total += live ? cnt : 0;
         cnt = 0;
         alive = true;
       }
-#pragma unroll
-      for (int j = 0; j < ENT_NCH; ++j) cur[j] = nxt[j];
       i = in;
       b = bn;
+    };
+    if (nq > 0) ent_fetch_half<T>(row_of(b, 0), nvec, l32, va);
+    for (int q = 0; q < nq; q += 2) {
+      step(va, vb, q + 1 < nq);
+      if (q + 1 < nq) step(vb, va, q + 2 < nq);
     }
+    if (l32 == 0) s_cnt[slot] = total;
   } else {
     for (int b = b0 + wave; b < b1; b += 4) {
       bool alive = true;
@@ -583,10 +640,14 @@ __global__ __launch_bounds__(256) void entropy_samples_kernel(const T* __restric
       if (lane == 0) n_keep[b] = cnt;
       total += cnt;
     }
+    if ((lane & 31) == 0) s_cnt[wave * 2 + (lane >> 5)] = lane == 0 ? total : 0;
   }
-  if (lane == 0) s_cnt[wave] = total;
   __syncthreads();
-  if (threadIdx.x == 0) blk_cnt[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < 8; ++w) t += s_cnt[w];
+    blk_cnt[blockIdx.x] = t;
+  }
 }
 
 // Second pass of the large-batch path: workgroup i sums the counts of the workgroups before it, then lists
@@ -1225,10 +1286,10 @@ static void launch_entropy_prefilter_t(hipStream_t s, const T* feat, int B, int 
     return;
   }
   int spb = (B + ENT_MAX_BLOCKS - 1) / ENT_MAX_BLOCKS;
-  spb = (spb + 3) & ~3;
+  spb = (spb + 7) & ~7;
   const unsigned blocks = (unsigned)((B + spb - 1) / spb);
   constexpr int VE = 16 / (int)sizeof(T);
-  const bool pipe = (((uintptr_t)feat) & 15) == 0 && L % VE == 0 && L >= VE && L / VE <= ENT_NCH * WAVE;
+  const bool pipe = (((uintptr_t)feat) & 15) == 0 && L % VE == 0 && L >= VE && L / VE <= ENT_NCH2 * 32;
   if (pipe)
     entropy_samples_kernel<T, true><<<blocks, 256, 0, s>>>(feat, B, K, L, tau, spb, H, keep, n_keep, blk_cnt);
   else

@@ -209,7 +209,8 @@ def _check_prefilter(ctx, feat, tau, dtype_tol=1e-3):
 
 
 @pytest.mark.parametrize("B,K,L", [(1, 4, 256), (32, 8, 1024), (64, 8, 1280), (8, 8, 2048), (3, 5, 130), (2, 1, 1),
-                                   (7, 3, 9), (1024, 2, 72), (1025, 3, 136), (9001, 2, 40), (2500, 4, 257)])
+                                   (7, 3, 9), (1024, 2, 72), (1025, 3, 136), (9001, 2, 40), (2500, 4, 257),
+                                   (1500, 8, 1280), (1100, 3, 2048), (4100, 1, 8), (1030, 2, 2056)])
 def test_prefilter_shapes(ctx_bf16, B, K, L):
     ctx, _ = ctx_bf16
     feat = gen.normal(5, f"feat{B}{K}{L}", (B, K, L), 2.0, DT_BF16)
