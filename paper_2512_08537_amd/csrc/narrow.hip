@@ -276,7 +276,8 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
     else FARD_NR(1, 1, 8, false);
   } else if (steps <= 8 && a.N % 64 == 0) {
     // several row slabs: 64 columns per workgroup quarter the re-reads of the activations (measured best at
-    // 288 rows for N = 1024 .. 4096)
+    // 288 rows for N = 1024 .. 4096; slabs of 48, 64 or 96 rows re-read the weights less often but lengthen every
+    // workgroup's chain of load, MFMAs and epilogue: a round is 9-17 % slower with them)
     FARD_NR(2, 4, 8, true);
   } else if (steps <= 12) {
     if (steps <= 8) FARD_NR(2, 2, 8, true);
