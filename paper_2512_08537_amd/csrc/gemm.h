@@ -52,10 +52,6 @@ hipError_t launch_gemm_f32(hipStream_t s, const GemmArgs& a);
 bool narrow_supported(const GemmArgs& a);
 hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a);
 
-// Tuning hook: force the wave tile (wn in {1,2}), the K-split inside the workgroup (kw in {1,4}) and the
-// K split across workgroups of every following bf16 launch; wn = 0 restores the built-in choice.
-void gemm_force_cfg(int wn, int kw, int splits, int kc = 256);
-
 // Re-lay a row-major [K, N] matrix (src_is_bf16: bf16 else fp32; leading dimension ld) into MFMA
 // fragment order.  Destination n-block index = nb_offset + nb * nb_stride (lets two matrices be
 // interleaved block by block for the SwiGLU epilogue).

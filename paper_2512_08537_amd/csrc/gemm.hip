@@ -282,16 +282,14 @@ hipError_t launch_cfg(hipStream_t s, const GemmArgs& a, int splits) {
 }
 
 // ------------------------------------------------------------------------ skinny variants (M <= a few hundred)
-// For the skinny GEMMs of a round (2-50 MB of weights each) a launch is one memory round trip long
-// if, and only if, every load it needs is in flight from the first cycle.  Two kernels do that:
-//  * gemm_bf16_res_kernel (64 < M): the whole activation panel of the workgroup (64 rows x its K range,
-//    in passes of up to ~1100 k) goes HBM/L2 -> LDS by the direct-to-LDS loads of gfx950
-//    (global_load_lds_dwordx4: no registers, 1 KiB per wave instruction) while the first P k-steps of every
-//    wave's weight stream are requested; one wait, one barrier, then an MFMA loop without barriers whose
-//    LDS fragment reads run two steps ahead of the MFMAs.
-//  * gemm_bf16_direct_kernel (M <= 64): the 4 waves split K; each wave needs only its own k-slices of the
-//    activations, so it loads them straight into registers as MFMA A fragments: no LDS before the MFMAs.
-// Both finish through lds_epilogue: partial tiles meet in LDS, then all 256 threads read them back
+// For the GEMMs of a few hundred rows (2-50 MB of weights each) a launch is one memory round trip long
+// if, and only if, every load it needs is in flight from the first cycle:
+// gemm_bf16_res_kernel (64 < M): the whole activation panel of the workgroup (64 rows x its K range,
+// in passes of up to ~1100 k) goes HBM/L2 -> LDS by the direct-to-LDS loads of gfx950
+// (global_load_lds_dwordx4: no registers, 1 KiB per wave instruction) while the first P k-steps of every
+// wave's weight stream are requested; one wait, one barrier, then an MFMA loop without barriers whose
+// LDS fragment reads run two steps ahead of the MFMAs.
+// It finishes through lds_epilogue: partial tiles meet in LDS, then all 256 threads read them back
 // row-contiguous and write 8-16 bytes per lane (full cache lines) instead of 2-byte scattered stores.
 constexpr int RU = 1056;              // bytes between activation units in LDS (1 KiB unit + 32 B: conflict-free reads)
 
@@ -499,80 +497,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_res_kernel(GemmArgs a, int n_ti
   lds_epilogue<WM, WN, KW, NWN>(a, acc, (float*)lds_raw, m0, M, nt * NWN * WN * 32, kw, nw, sp == 0, splits > 1);
 }
 
-// M <= 64: 4 waves split K (interleaved k-steps), activations as A fragments straight from global memory.
-template <int WM, int WN, int P>
-__global__ __launch_bounds__(256) void gemm_bf16_direct_kernel(GemmArgs a, int n_tiles, int splits, int steps_per_split) {
-  constexpr int KW = 4;
-  extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-  const int id = blockIdx.x;
-  if (id >= n_tiles * splits) return;
-  const int nt = id % n_tiles, sp = id / n_tiles;
-  const int M = eff_rows(a.M, a.m_dev);
-  if (M <= 0) return;
-  const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
-  const int nblocks = a.N >> 5;
-  const int kb16 = a.K >> 4;
-  const int nb0 = nt * WN;
-  const int s_begin = sp * steps_per_split;
-  int n_steps = kb16 - s_begin;
-  if (n_steps > steps_per_split) n_steps = steps_per_split;
-  // this wave takes k-steps kw, kw + 4, kw + 8, ... of the workgroup's range
-  const int my_steps = (n_steps - kw + KW - 1) / KW;
-
-  const bf16* __restrict__ A = (const bf16*)a.A;
-  const bf16x8* __restrict__ Wp = (const bf16x8*)a.W;
-  f32x16 acc[WM][WN];
-#pragma unroll
-  for (int i = 0; i < WM; ++i)
-#pragma unroll
-    for (int j = 0; j < WN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-  bf16x8 zero8;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) zero8[e] = (bf16)0.f;
-
-  const bf16x8* bbase[WN];
-#pragma unroll
-  for (int j = 0; j < WN; ++j) {
-    const int nb = (nb0 + j < nblocks) ? nb0 + j : 0;
-    bbase[j] = Wp + ((size_t)nb * kb16 + s_begin) * 64 + lane;
-  }
-  const bf16* abase[WM];
-#pragma unroll
-  for (int i = 0; i < WM; ++i) {
-    int row = 32 * i + (lane & 31);
-    row = row < M ? row : M - 1;
-    abase[i] = A + (size_t)row * a.lda + (size_t)s_begin * 16 + (lane >> 5) * 8;
-  }
-  bf16x8 breg[P][WN], areg[P][WM];
-  auto load_ab = [&](int t, int p) {                       // t-th step of this wave
-    int s = kw + t * KW;
-    s = s < n_steps ? s : n_steps - 1;                     // past the end: re-read, zeroed at use
-#pragma unroll
-    for (int j = 0; j < WN; ++j) breg[p][j] = bbase[j][(size_t)s * 64];
-#pragma unroll
-    for (int i = 0; i < WM; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 16);
-  };
-#pragma unroll
-  for (int p = 0; p < P; ++p) load_ab(p, p);
-  __builtin_amdgcn_sched_barrier(0);                       // keep all P steps of loads ahead of the first MFMA
-  for (int t0 = 0; t0 < my_steps; t0 += P) {
-#pragma unroll
-    for (int g = 0; g < P; ++g) {
-      const bool live = (t0 + g) < my_steps;
-#pragma unroll
-      for (int j = 0; j < WN; ++j)
-#pragma unroll
-        for (int i = 0; i < WM; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(live ? areg[g][i] : zero8, breg[g][j], acc[i][j], 0, 0, 0);
-      load_ab(t0 + g + P, g);
-      __builtin_amdgcn_sched_barrier(0);                   // the refill stays P steps ahead of its use
-    }
-  }
-  lds_epilogue<WM, WN, KW, 1>(a, acc, (float*)lds_raw, 0, M, nt * WN * 32, kw, 0, sp == 0, splits > 1);
-}
-
 constexpr int RES_LDS_BUDGET = 150 * 1024;
 
 template <int WM, int WN, int KW, int P>
@@ -604,54 +528,11 @@ hipError_t launch_res(hipStream_t s, const GemmArgs& a, int splits) {
   return hipGetLastError();
 }
 
-template <int WM, int WN, int P>
-hipError_t launch_direct(hipStream_t s, const GemmArgs& a, int splits) {
-  const int BN = 32 * WN;
-  const int n_tiles = (a.N + BN - 1) / BN;
-  const int total_steps = a.K / 16;
-  if (splits < 1) splits = 1;
-  int sps = (total_steps + splits - 1) / splits;
-  sps = ((sps + 3) / 4) * 4;                               // whole groups of 4 k-steps (one per wave)
-  splits = (total_steps + sps - 1) / sps;
-  const size_t lds = (size_t)4 * 32 * WM * (BN + 4) * 4;
-  gemm_bf16_direct_kernel<WM, WN, P><<<n_tiles * splits, 256, lds, s>>>(a, n_tiles, splits, sps);
-  return hipGetLastError();
-}
-
 // Tile choice.  The chip has 256 CUs; these GEMMs rarely have that many 128-column tiles, so narrow
 // tiles (waves splitting K inside the workgroup) and K splits across workgroups are used until the
 // grid covers it.  EPI_SWIGLU needs both column blocks of a pair in one wave (WN = 2).
-int g_force_wn = 0, g_force_kw = 0, g_force_splits = 0, g_force_kc = 256;   // tuning hook (gemm_force_cfg); 0 = heuristic
-
 template <int WM>
 hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
-  if (g_force_wn) {
-    const int sp = g_force_splits ? g_force_splits : 1;
-    if (g_force_kc == 0) {
-      if constexpr (WM == 2) {
-        if (g_force_wn == 1 && g_force_kw == 2) return launch_res<2, 1, 2, 16>(s, a, sp);
-        if (g_force_wn == 2 && g_force_kw == 2) return launch_res<2, 2, 2, 16>(s, a, sp);
-        if (g_force_wn == 2 && g_force_kw == 1) return launch_res<2, 2, 1, 16>(s, a, sp);
-        return launch_res<2, 1, 1, 16>(s, a, sp);
-      }
-    }
-    if (g_force_kc == 1) {
-      if constexpr (WM <= 2) {
-        if (g_force_wn == 2) return launch_direct<WM, 2, 16>(s, a, sp);
-        return launch_direct<WM, 1, 16>(s, a, sp);
-      }
-    }
-    if (g_force_kc == 512) {
-      if (g_force_wn == 2 && g_force_kw == 1) return launch_cfg<WM, 2, 1, 8, 512>(s, a, sp);
-      if (g_force_wn == 1 && g_force_kw == 1) return launch_cfg<WM, 1, 1, 16, 512>(s, a, sp);
-      if (g_force_wn == 2 && g_force_kw == 4) return launch_cfg<WM, 2, 4, 8, 512>(s, a, sp);
-      return launch_cfg<WM, 1, 4, 8, 512>(s, a, sp);
-    }
-    if (g_force_wn == 2 && g_force_kw == 1) return launch_cfg<WM, 2, 1, 8, 256>(s, a, sp);
-    if (g_force_wn == 1 && g_force_kw == 1) return launch_cfg<WM, 1, 1, 16, 256>(s, a, sp);
-    if (g_force_wn == 2 && g_force_kw == 4) return launch_cfg<WM, 2, 4, 8, 256>(s, a, sp);
-    return launch_cfg<WM, 1, 4, 8, 256>(s, a, sp);
-  }
   const bool resid = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
   if constexpr (WM == 3) {
     // a few hundred rows, full-K epilogue: the resident-activation kernel on 64-row tiles, sized so that the
@@ -738,14 +619,12 @@ __global__ void pack_weight_kernel(const TS* __restrict__ src, int ld, int K, in
 
 }  // namespace
 
-void gemm_force_cfg(int wn, int kw, int splits, int kc) { g_force_wn = wn; g_force_kw = kw; g_force_splits = splits; g_force_kc = kc; }
-
 hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a) {
   if (a.M <= 0) return hipSuccess;
   if (a.K % 64 != 0 || a.N % 32 != 0 || a.lda % 8 != 0) return hipErrorInvalidValue;
   if (a.epi == EPI_SWIGLU && a.N % 64 != 0) return hipErrorInvalidValue;
   if (a.M <= 32) return launch_wm<1>(s, a);
-  if (a.M <= 64 || (g_force_wn && g_force_kc == 0)) return launch_wm<2>(s, a);
+  if (a.M <= 64) return launch_wm<2>(s, a);
   return launch_wm<3>(s, a);
 }
 

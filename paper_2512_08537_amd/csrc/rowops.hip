@@ -812,7 +812,7 @@ __global__ __launch_bounds__(256) void head_prep_kernel(const float* __restrict_
     hh[(size_t)r * w + c] = in_proj<T>(b_in[c], xr, xscale, D, w_in, w, c);
     for (int k = 0; k < S; ++k) sc[((size_t)k * n + r) * w + c] = from_f32<T>(silu(czv + temb[(size_t)k * w + c]));
   }
-  if (xt_out && blockIdx.x == 0 && threadIdx.x < D) xt_out[(size_t)r * D + threadIdx.x] = xr[threadIdx.x] * xscale;
+  if (xt_out && blockIdx.x == 0 && (int)threadIdx.x < D) xt_out[(size_t)r * D + threadIdx.x] = xr[threadIdx.x] * xscale;
 }
 
 // One workgroup per row: final AdaLN, output projection to D <= 16 components, sampler update, and (when
@@ -896,7 +896,7 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
       if (!a.last) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int c = (threadIdx.x + 256 * j < w) ? threadIdx.x + 256 * j : threadIdx.x;
+          const int c = ((int)threadIdx.x + 256 * j < w) ? (int)threadIdx.x + 256 * j : (int)threadIdx.x;
           bjn[j] = a.b_in[c];
 #pragma unroll
           for (int k = 0; k < 16; ++k) wvn[j][k] = w_in[(size_t)k * w + c];
@@ -909,7 +909,7 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   float s = 0.f, q = 0.f;
 #pragma unroll
   for (int i = 0; i < HO_VPT; ++i) {
-    if (threadIdx.x + i * 256 < n4) {
+    if ((int)threadIdx.x + i * 256 < n4) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) { const float t = x[i][e] - pivot; s += t; q = fmaf(t, t, q); }
     }
@@ -951,7 +951,7 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
     for (int k = 0; k < 16; ++k) part[wave][k] = acc[k];
   }
   __syncthreads();
-  if (threadIdx.x < D) {
+  if ((int)threadIdx.x < D) {
     const int k = threadIdx.x;
     const float v = part[0][k] + part[1][k] + part[2][k] + part[3][k] + (pre ? p_bout : a.b_out[k]);
     const size_t xi = (size_t)r * D + k;
@@ -1183,7 +1183,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const float* __restrict
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < VPT; ++i) {
-    if (threadIdx.x + i * 256 < n4) {
+    if ((int)threadIdx.x + i * 256 < n4) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) { const float t = v[i][e] - mean; q += t * t; }
     }
