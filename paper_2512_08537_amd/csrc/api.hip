@@ -805,14 +805,15 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
                                  (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0));
     } else {
       // more rows per sample than one attention workgroup holds: passes of acap rows (c->ap_* hold their row ranges
-      // and first positions); each pass stores its own K / V rows before the next one reads them
+      // and first positions), all in one launch once every row's K / V is in the cache
       const int n_pass = (nq_max + acap - 1) / acap;
-      for (int p = 0; p < n_pass; ++p) {
-        Bracket br(c, CLS_ATTN);
-        HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, c->ap_len + (size_t)p * B, c->ap_start + (size_t)p * B, B,
-                                   std::min(acap, nq_max - p * acap), c->ao, HD, (l + 1 == ent_layer) ? c->ent_heads : nullptr,
-                                   fused_append ? 1 : 0, c->ap_cnt + (size_t)p * B));
+      if (fused_append) {
+        Bracket br(c, CLS_OTHER);
+        HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, 0, t.rope_theta, c->maps.row_sample, c->maps.row_pos, M, m_dev));
       }
+      Bracket br(c, CLS_ATTN);
+      HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, c->ap_len, c->ap_start, B, acap, c->ao, HD,
+                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, 0, c->ap_cnt, n_pass));
     }
     // norm 2 without a launch of its own, when both GEMMs around it run in the narrow kernel: the output
     // projection also leaves the updated stream as bf16, and the up-projection (weights pre-scaled by the norm's

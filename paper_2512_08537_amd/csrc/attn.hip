@@ -28,7 +28,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
                                                         const int* __restrict__ cache_len,
                                                         const int* __restrict__ row_start, const int* __restrict__ row_cnt,
                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads,
-                                                        int append) {
+                                                        int append, int pass_stride) {
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
@@ -41,6 +41,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
   const int Hk = kv.n_kv_heads;
   const int G = n_heads / Hk;
   const int b = blockIdx.x / Hk, hk = blockIdx.x - b * Hk;
+  // several passes in one launch (blockIdx.y; the longest, i.e. last, pass is dispatched first): the per-sample
+  // arrays of pass p start p * pass_stride entries in
+  const int pass_off = ((int)gridDim.y - 1 - (int)blockIdx.y) * pass_stride;
+  cache_len += pass_off;
+  row_start += pass_off;
+  if (row_cnt) row_cnt += pass_off;
   const int r0 = row_start[b];
   const int nq = row_cnt ? row_cnt[b] : row_start[b + 1] - r0;     // (row_cnt: a pass over part of the sample's rows)
   if (nq <= 0) return;
@@ -273,9 +279,13 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
                                                       const int* __restrict__ cache_len,
                                                       const int* __restrict__ row_start, const int* __restrict__ row_cnt,
                                                       int B, float* __restrict__ out,
-                                                      int ldo, float* __restrict__ ent_heads, int max_keys) {
+                                                      int ldo, float* __restrict__ ent_heads, int max_keys, int pass_stride) {
   extern __shared__ float s_p[];                 // [max_keys] scores / probabilities
-  const int head = blockIdx.x, b = blockIdx.z, j = blockIdx.y;
+  const int head = blockIdx.x, b = blockIdx.z % B, j = blockIdx.y;
+  const int pass_off = ((int)blockIdx.z / B) * pass_stride;       // passes of one launch: blockIdx.z = pass * B + b
+  cache_len += pass_off;
+  row_start += pass_off;
+  if (row_cnt) row_cnt += pass_off;
   const int r0 = row_start[b];
   const int nq = row_cnt ? row_cnt[b] : row_start[b + 1] - r0;
   if (j >= nq) return;
@@ -319,32 +329,35 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv, const int* cache_len,
                             const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads, int append,
-                            const int* row_cnt) {
-  if (B <= 0 || nq_max <= 0) return hipSuccess;
+                            const int* row_cnt, int n_pass) {
+  if (B <= 0 || nq_max <= 0 || n_pass <= 0) return hipSuccess;
+  // several passes at once read rows that an earlier pass of the same launch would have had to store
+  if (n_pass > 1 && (append || row_cnt == nullptr || n_pass > 65535 || (long)B * n_pass > 65535)) return hipErrorInvalidValue;
   if (!kv.is_bf16) {
     if (append) return hipErrorInvalidValue;
-    dim3 grid(n_heads, nq_max, B);
+    dim3 grid(n_heads, nq_max, B * n_pass);
     const size_t smem = (size_t)kv.ctx_pad * sizeof(float);
     if (smem > 64 * 1024) return hipErrorInvalidValue;
     attn_f32_kernel<<<grid, 64, smem, s>>>((const float*)qkv, ld, n_heads, kv, cache_len, row_start, row_cnt, B, (float*)out,
-                                           ldo, ent_heads, kv.ctx_pad);
+                                           ldo, ent_heads, kv.ctx_pad, B);
     return hipGetLastError();
   }
   const int G = n_heads / kv.n_kv_heads;
   const int cols = G * nq_max;
   if (cols > 64 || n_heads % kv.n_kv_heads != 0) return hipErrorInvalidValue;
-  const int grid = B * kv.n_kv_heads;
+  const dim3 grid(B * kv.n_kv_heads, n_pass);
+  const int ps = B;
   const bf16* q = (const bf16*)qkv;
   bf16* o = (bf16*)out;
   if (kv.d_head == 64) {
-    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
-    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
+    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
+    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
   } else if (kv.d_head == 128) {
-    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
-    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
+    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
+    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
   } else if (kv.d_head == 32) {
-    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
-    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append);
+    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
+    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
   } else {
     return hipErrorInvalidValue;
   }

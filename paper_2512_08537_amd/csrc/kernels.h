@@ -90,9 +90,12 @@ hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v
 // cache_len[b] .. + n_q - 1 before it reads them, replacing a separate launch_rope_append.
 // row_cnt (optional): sample b contributes row_cnt[b] rows starting at row_start[b] (a pass over part of a sample's
 // rows; cache_len[b] is then the position of the first of them); without it the rows are row_start[b] .. row_start[b+1].
+// n_pass > 1: that many passes in one launch; pass p reads entries [p * B, (p + 1) * B) of cache_len, row_start and
+// row_cnt.  The K / V rows of all passes must be in the cache already (append == 0).
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv,
                             const int* cache_len, const int* row_start, int B, int nq_max,
-                            void* out, int ldo, float* ent_heads, int append, const int* row_cnt = nullptr);
+                            void* out, int ldo, float* ent_heads, int append, const int* row_cnt = nullptr,
+                            int n_pass = 1);
 
 // Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
 // Up to ENT_SAMPLE_MODE_MIN_B samples: a wave per row, then one workgroup thresholds and compacts.  Above: a
