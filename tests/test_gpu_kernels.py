@@ -33,6 +33,8 @@ def ctx_f32():
                                    (97, 128, 160), (288, 1024, 1024), (72, 512, 2048), (200, 2048, 320),
                                    (288, 1024, 3072), (130, 768, 4096), (576, 1280, 3840), (65, 256, 64),
                                    (2304, 1280, 3840), (500, 256, 12288),
+                                   # enough 256-column panels and rows for the 128-row tile: ragged rows, ragged last panel
+                                   (3900, 128, 7680), (3850, 192, 7712),
                                    # a thousand rows and more (prefill passes): ragged rows, few and ragged column
                                    # blocks
                                    (1025, 64, 32), (1100, 256, 96), (1300, 320, 160), (2048, 1024, 1024),

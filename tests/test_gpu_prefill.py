@@ -137,3 +137,34 @@ def test_prefill_config1_full_size_sampled_samples():
             print(f"which={which} sample {b}: {e:.2e}")
             assert e < 2e-2
     ctx.close()
+
+
+def test_prefill_of_thousands_of_rows_through_wide_layers():
+    """8 x 1024 rows through a 3840-wide layer: every GEMM of the layer (store, residual and SwiGLU epilogues) has
+    enough 256-column panels and 128-row tiles to take the streaming kernel's 128-row variant with XCD groups along M,
+    and the attention runs 86 passes of 12 rows (5 query heads per kv head) in one launch.  Sampled samples against the
+    oracle's single causal forward."""
+    from synth.configs import (RoundCfg, TfCfg, HeadCfg, ACT_SWIGLU, NORM_RMS, POS_ROPE)
+    tgt = TfCfg(n_layers=1, d_model=3840, n_heads=30, n_kv_heads=6, d_head=128, d_ff=2048,
+                act=ACT_SWIGLU, norm=NORM_RMS, pos=POS_ROPE, has_bias=0, norm_eps=1e-6)
+    drf = TfCfg(n_layers=1, d_model=256, n_heads=2, n_kv_heads=1, d_head=128, d_ff=192,
+                act=ACT_SWIGLU, norm=NORM_RMS, pos=POS_ROPE, has_bias=0, norm_eps=1e-6, d_out=3840)
+    rc = RoundCfg(name="wide-rows", target=tgt, draft=drf, head=HeadCfg(1, 128, 3840, n_steps=1), K=4, max_batch=8,
+                  max_ctx=1024, entropy_layer=1, batch=8, n_ctx=1)
+    case = build_case(rc, seed=43)
+    ctx = make_ctx(case)
+    B, D, n_max = 8, tgt.d_latent, 1024
+    rng = np.random.default_rng(9)
+    n = np.array([1024, 1024, 1000, 1024, 777, 1024, 1024, 1023], np.int32)
+    x = gen.bf16_round(rng.normal(size=(B, n_max, D)).astype(np.float32))
+    ctx.spec_kv_reset(0, None)
+    z_last = ctx.spec_prefill(0, ctx.dev_f32(x), n)
+    ctx.sync()
+    assert np.array_equal(ctx.spec_kv_lengths(0, B), n)
+    samples = [0, 2, 7]
+    _, zo = _oracle_prefill(case, 0, x, None, n, samples=samples)
+    zg = z_last.float().cpu().numpy()
+    e = rel_inf(zg[samples], np.stack([zo[b] for b in samples]))
+    print(f"wide rows: last-row features {e:.2e}")
+    assert e < TOL[DT_BF16]
+    ctx.close()
