@@ -262,11 +262,20 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, i
   T* row = qkv + (size_t)r * ld;
   const int n_rot_heads = n_heads + Hk;         // q heads then k heads are rotated
   if (rope) {
+    // the angle depends on the row's position and on the pair index c only; a thread whose elements all share one c
+    // (the workgroup size is a multiple of half the head dim) takes its sine and cosine once
+    const bool one_c = (blockDim.x % half) == 0;
+    float sn = 0.f, cs = 1.f;
+    if (one_c) {
+      const float inv = powf(theta, -2.0f * (float)(threadIdx.x % half) / (float)dh);
+      sincosf((float)pos * inv, &sn, &cs);
+    }
     for (int idx = threadIdx.x; idx < n_rot_heads * half; idx += blockDim.x) {
       const int hd = idx / half, c = idx - hd * half;
-      const float inv = powf(theta, -2.0f * (float)c / (float)dh);
-      float sn, cs;
-      sincosf((float)pos * inv, &sn, &cs);
+      if (!one_c) {
+        const float inv = powf(theta, -2.0f * (float)c / (float)dh);
+        sincosf((float)pos * inv, &sn, &cs);
+      }
       T* p = row + (size_t)hd * dh;
       const float a = to_f32(p[c]), bb = to_f32(p[c + half]);
       p[c] = from_f32<T>(a * cs - bb * sn);
