@@ -64,14 +64,43 @@ __global__ __launch_bounds__(256) void build_rows_kernel(const int* n_base, int 
       if (aux_row) aux_row[r] = (base + i) * (K + 1) + jj;
     }
     if (x_out) {
-      for (int e = tid; e < block_total * D; e += 256) {
-        const int rl = e / D, cc = e - rl * D;
-        const int r = carry + rl;
-        if (r >= m_max) break;
-        int jj;
-        const int i = sample_of(rl, jj);
-        const float* src = (jj == 0) ? x_first + (size_t)(base + i) * D : x_rest + ((size_t)(base + i) * K + (jj - 1)) * D;
-        x_out[(size_t)r * D + cc] = src[cc];
+      const bool vec4 = (D & 3) == 0 && ((((uintptr_t)x_first) | ((uintptr_t)x_rest) | ((uintptr_t)x_out)) & 15) == 0;
+      if (vec4) {
+        // 16-byte pieces, four of a thread's loads in flight at once (the rows are a few dozen bytes each)
+        const int D4 = D >> 2, n4 = block_total * D4;
+        for (int e0 = tid; e0 < n4; e0 += 4 * 256) {
+          f32x4 v[4];
+          size_t dst[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int e = e0 + u * 256;
+            dst[u] = (size_t)-1;
+            if (e < n4) {
+              const int rl = e / D4, cc = e - rl * D4;
+              const int r = carry + rl;
+              if (r < m_max) {
+                int jj;
+                const int i = sample_of(rl, jj);
+                const float* src = (jj == 0) ? x_first + (size_t)(base + i) * D : x_rest + ((size_t)(base + i) * K + (jj - 1)) * D;
+                v[u] = *(const f32x4*)(src + 4 * cc);
+                dst[u] = (size_t)r * D + 4 * cc;
+              }
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (dst[u] != (size_t)-1) *(f32x4*)(x_out + dst[u]) = v[u];
+        }
+      } else {
+        for (int e = tid; e < block_total * D; e += 256) {
+          const int rl = e / D, cc = e - rl * D;
+          const int r = carry + rl;
+          if (r >= m_max) break;
+          int jj;
+          const int i = sample_of(rl, jj);
+          const float* src = (jj == 0) ? x_first + (size_t)(base + i) * D : x_rest + ((size_t)(base + i) * K + (jj - 1)) * D;
+          x_out[(size_t)r * D + cc] = src[cc];
+        }
       }
     }
     __syncthreads();
