@@ -60,7 +60,8 @@ def main():
 
     import torch
     from paper_2512_08537_amd import binding
-    from tests.harness import build_case, make_ctx, gpu_inputs, run_oracle_round, load_caches
+    from synth.cases import build_case
+    from paper_2512_08537_amd.workload import make_ctx, gpu_inputs
 
     t0 = time.time()
     shared = args.config == 4                          # 44 GB of distinct synthetic cache would not fit the host
@@ -264,6 +265,7 @@ def main():
     if not args.no_cpu:
         cores = len(os.sched_getaffinity(0))
         idx = sorted(set(np.linspace(0, B - 1, min(args.cpu_samples, B)).astype(int).tolist()))
+        from oracle.run_case import run_oracle_round      # the oracle: this leg only
         tc0 = time.perf_counter()
         o = run_oracle_round(case, tau, samples=idx)
         tcpu = time.perf_counter() - tc0

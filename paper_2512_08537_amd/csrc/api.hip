@@ -252,6 +252,7 @@ struct fard_ctx {
   uint8_t* g_keep = nullptr;
   // deferred residual update: K-slice partial sums of the last down-projection, folded in by the next norm
   float* parts = nullptr;
+  size_t parts_cap = 0;                    // floats that parts holds
   int pend_n = 0;
   size_t pend_stride = 0;
   RoundGraph rgraph;
@@ -724,7 +725,11 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<int>(c, &c->s_nk, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->s_na, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->s_tr, g.max_batch))) return rc;
-  if (c->bf16 && (rc = dalloc<float>(c, &c->parts, (size_t)PART_MAX_SLICES * std::min(M, PART_MAX_ROWS) * dmax))) return rc;
+  // planes for any forward the workspace admits (a prefill pass has more rows than a round), up to the row limit
+  if (c->bf16) {
+    c->parts_cap = (size_t)PART_MAX_SLICES * std::min(std::max(M, MR), PART_MAX_ROWS) * dmax;
+    if ((rc = dalloc<float>(c, &c->parts, c->parts_cap))) return rc;
+  }
   return FARD_OK;
 }
 
@@ -744,7 +749,7 @@ KvGeom kv_geom(fard_ctx* c, Model& m, int layer) {
 // the next norm (or flush_parts) adds them to the residual stream.
 bool parts_eligible(const fard_ctx* c, int M, int N, int K) {
   return c->bf16 && c->parts != nullptr && M <= PART_MAX_ROWS && K > 2048 && (K + 1023) / 1024 <= PART_MAX_SLICES && N <= 8192 &&
-         N % 32 == 0 && K % 64 == 0;
+         N % 32 == 0 && K % 64 == 0 && (size_t)((K + 1023) / 1024) * M * N <= c->parts_cap;
 }
 
 hipError_t gemm_parts(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
@@ -754,6 +759,7 @@ hipError_t gemm_parts(fard_ctx* c, const void* A, int lda, const void* W, const 
   a.M = M; a.N = N; a.K = K; a.m_dev = m_dev; a.act = ACT_NONE; a.epi = EPI_PARTIAL;
   a.k_slices = (K + 1023) / 1024;
   a.part_stride = (size_t)M * N;
+  if ((size_t)a.k_slices * a.part_stride > c->parts_cap) return hipErrorInvalidValue;   // never launch past the planes
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * N * 4;
   Bracket br(c, CLS_GEMM, fl, by);

@@ -26,7 +26,8 @@ PEAK_HBM_GBS = 8000.0
 
 def entropy():
     import torch
-    from tests.harness import build_case, make_ctx
+    from synth.cases import build_case
+    from .workload import make_ctx
     case = build_case("ln-gelu-bf16", seed=0)
     ctx = make_ctx(case)
     # (B, K, L): configs[0..4] feature shapes, then the scaled shape that shows the asymptotic bandwidth
@@ -57,7 +58,8 @@ def narrow():
     """Launches the narrow-tile GEMM at the shapes of a configs[1] round; kernel durations are read from a
     rocprofv3 kernel trace of this run (the host loop here is slower than the kernels)."""
     import torch
-    from tests.harness import build_case, make_ctx
+    from synth.cases import build_case
+    from .workload import make_ctx
     case = build_case("ln-gelu-bf16", seed=0)
     ctx = make_ctx(case)
     dev = ctx.dev
@@ -92,7 +94,8 @@ def copy():
 def peaks():
     """What the box sustains on the two roofs: a streaming read over several sizes, a register-only bf16 MFMA loop."""
     import torch
-    from tests.harness import build_case, make_ctx
+    from synth.cases import build_case
+    from .workload import make_ctx
     ctx = make_ctx(build_case("ln-gelu-bf16", seed=0))
     for mib in (64, 256, 1024, 4096):
         buf = torch.zeros(mib << 18, device="cuda", dtype=torch.float32)
@@ -113,7 +116,8 @@ def losses():
     """The attention-entropy loss with both gradients at the draft's training shapes (batch x heads x sequence x head
     dim); flops = score tiles (forward, and once more per gradient) + the two second products, causal half only."""
     import torch
-    from tests.harness import build_case, make_ctx
+    from synth.cases import build_case
+    from .workload import make_ctx
     case = build_case("ln-gelu-bf16", seed=0)
     ctx = make_ctx(case)
     for (B, H, Hkv, R, dh) in [(32, 16, 16, 256, 64), (64, 20, 20, 256, 64), (8, 16, 16, 1024, 64), (8, 40, 8, 1024, 128)]:

@@ -1,10 +1,9 @@
-"""Shared set-up for the parity tests, smoke() and bench.py: seeded cases, one GPU round through the
-C-ABI binding, and the same round through the CPU oracle.  The two sides only share `synth`."""
+"""Shared imports of the parity tests: seeded cases (synth.cases), the HIP library's side
+(paper_2512_08537_amd.workload) and the CPU oracle's side (oracle.run_case).  The two sides only share `synth`."""
 from __future__ import annotations
 
 import os
 import sys
-from dataclasses import dataclass, field
 
 import numpy as np
 
@@ -12,134 +11,33 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-from synth import gen                       # noqa: E402
-from synth.configs import RoundCfg, reduced, config, clone   # noqa: E402
+from synth.cases import Case, build_case                                         # noqa: E402,F401
+from oracle.run_case import oracle_caches, run_oracle_round                      # noqa: E402,F401
 
 
-@dataclass
-class Case:
-    rc: RoundCfg
-    W: dict
-    cache_t: list          # per target layer (k, v) numpy [B, Hkv, n_ctx, dh]
-    cache_d: list
-    inp: dict
-    B: int
-    n_ctx: int
-    seed: int
-    shared_layers: bool = True
+def make_ctx(case, stream=None):
+    from paper_2512_08537_amd import workload
+    return workload.make_ctx(case, stream=stream)
 
 
-def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_draft=False, cache_layers_shared=False,
-               std_overrides=None, peaky=False, deep_gain=1.0) -> Case:
-    rc = kind if isinstance(kind, RoundCfg) else (config(kind) if isinstance(kind, int) else reduced(kind))
-    rc = clone(rc)
-    if same_draft:
-        rc.draft = clone(rc).target
-    B = rc.batch if B is None else B
-    n_ctx = rc.n_ctx if n_ctx is None else n_ctx
-    if peaky:
-        # QKV weights scaled so that attention scores have a standard deviation near 2: the softmax
-        # is far from uniform (a wrong K/Q layout shows) yet bf16 rounding of q, k stays within the bar
-        std_overrides = dict(std_overrides or {})
-        std_overrides["wqkv"] = 1.4 / np.sqrt(min(rc.target.d_model, rc.draft.d_model))
-    if w_std is None:
-        w_std = 0.02                                       # the workload recipe: N(0, 0.02)
-    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
-                       deep_from=rc.draft.n_layers, deep_gain=deep_gain)
-    same_shape = (rc.draft.d_model, rc.draft.n_heads, rc.draft.n_kv_heads, rc.draft.d_ff) == \
-                 (rc.target.d_model, rc.target.n_heads, rc.target.n_kv_heads, rc.target.d_ff)
-    if same_shape:
-        W.update(gen.truncated_draft(W, rc.target, rc.draft))
-    else:
-        W.update(gen.tf_weights(rc.draft, seed, "draft", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides))
-    W.update(gen.head_weights(rc.head, seed, rc.dtype, w_std=w_std, affine=affine))
-    cache_t, cache_d = [], []
-    for l in range(rc.target.n_layers):
-        src = 0 if cache_layers_shared else l
-        cache_t.append(gen.kv_cache(rc.target, seed, "target", src, B, n_ctx, rc.dtype) if (l == 0 or not cache_layers_shared)
-                       else cache_t[0])
-    for l in range(rc.draft.n_layers):
-        if same_shape:
-            cache_d.append(cache_t[l])
-        else:
-            cache_d.append(gen.kv_cache(rc.draft, seed, "draft", l, B, n_ctx, rc.dtype))
-    inp = gen.round_inputs(rc, seed, B)
-    return Case(rc, W, cache_t, cache_d, inp, B, n_ctx, seed, same_shape)
+def load_caches(ctx, case):
+    from paper_2512_08537_amd import workload
+    return workload.load_caches(ctx, case)
 
 
-# ------------------------------------------------------------------------------ GPU side
-def make_ctx(case: Case, stream=None):
-    from paper_2512_08537_amd import binding
-    ctx = binding.Context(case.rc, case.W, stream=stream)
-    load_caches(ctx, case)
-    return ctx
+def gpu_inputs(ctx, case):
+    from paper_2512_08537_amd import workload
+    return workload.gpu_inputs(ctx, case)
 
 
-def load_caches(ctx, case: Case):
-    from paper_2512_08537_amd import binding
-    for which, caches in ((binding.TARGET, case.cache_t), (binding.DRAFT, case.cache_d)):
-        last, last_dev = None, None
-        for l, (k, v) in enumerate(caches):
-            if last is not None and k is last[0]:
-                kd, vd = last_dev
-            else:
-                kd, vd = ctx.dev_store(k), ctx.dev_store(v)
-            ctx.spec_kv_load(which, l, kd, vd)
-            last, last_dev = (k, v), (kd, vd)
-        ctx.spec_kv_reset(which, np.full(case.B, case.n_ctx, dtype=np.int32))
-    ctx.sync()
+def to_np(o):
+    from paper_2512_08537_amd import workload
+    return workload.to_np(o)
 
 
-def gpu_inputs(ctx, case: Case):
-    return dict(pending=ctx.dev_f32(case.inp["pending"]), eps=ctx.dev_f32(case.inp["eps_draft"]),
-                r=ctx.dev_f32(case.inp["r"]))
-
-
-def to_np(o: dict) -> dict:
-    out = {}
-    for k, v in o.items():
-        if v is None:
-            continue
-        out[k] = v.float().cpu().numpy() if v.dtype.is_floating_point else v.cpu().numpy()
-    return out
-
-
-def run_gpu_round(case: Case, tau: float, ctx=None):
-    own = ctx is None
-    ctx = ctx or make_ctx(case)
-    g = gpu_inputs(ctx, case)
-    o = ctx.spec_round(g["pending"], g["eps"], g["r"], tau)
-    ctx.sync()
-    out = to_np(o)
-    from paper_2512_08537_amd import binding
-    out["len_t"] = ctx.spec_kv_lengths(binding.TARGET, case.B)
-    out["len_d"] = ctx.spec_kv_lengths(binding.DRAFT, case.B)
-    if own:
-        ctx.close()
-    return out
-
-
-# ------------------------------------------------------------------------------ oracle side
-def oracle_caches(case: Case, samples=None):
-    from oracle import transformer as tf
-    idx = list(range(case.B)) if samples is None else list(samples)
-    tc, dc = tf.KVCache(case.rc.target, len(idx)), tf.KVCache(case.rc.draft, len(idx))
-    for l, (k, v) in enumerate(case.cache_t):
-        tc.load(l, k[idx], v[idx])
-    for l, (k, v) in enumerate(case.cache_d):
-        dc.load(l, k[idx], v[idx])
-    return tc, dc
-
-
-def run_oracle_round(case: Case, tau: float, samples=None):
-    from oracle import round as rnd
-    idx = list(range(case.B)) if samples is None else list(samples)
-    tc, dc = oracle_caches(case, idx)
-    out = rnd.spec_round(case.rc, case.W, tc, dc, case.inp["pending"][idx], case.inp["eps_draft"][:, idx],
-                         case.inp["r"][idx], tau, len(idx))
-    out["len_t"] = np.array([tc.length(b) for b in range(len(idx))])
-    out["len_d"] = np.array([dc.length(b) for b in range(len(idx))])
-    return out
+def run_gpu_round(case, tau, ctx=None):
+    from paper_2512_08537_amd import workload
+    return workload.run_gpu_round(case, tau, ctx=ctx)
 
 
 def rel_inf(g, o):
