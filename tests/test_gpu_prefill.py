@@ -168,3 +168,31 @@ def test_prefill_of_thousands_of_rows_through_wide_layers():
     print(f"wide rows: last-row features {e:.2e}")
     assert e < TOL[DT_BF16]
     ctx.close()
+
+
+def test_prefill_with_more_rows_than_a_round_through_k_slice_planes():
+    """8 samples x 64 rows through layers with d_ff = 4096 in a context whose rounds have 72 rows: the down-projection's
+    K-slice partial planes (4 slices x 512 rows x d) are larger than a round's rows would need, and the context sizes
+    and checks them for the rows a forward may have."""
+    from synth.configs import RoundCfg, TfCfg, HeadCfg
+    from synth import configs as cf
+    tf_ = lambda L: TfCfg(n_layers=L, d_model=1024, n_heads=16, n_kv_heads=16, d_head=64, d_ff=4096, act=cf.ACT_GELU,
+                          norm=cf.NORM_LAYER, pos=cf.POS_LEARNED, has_bias=1, norm_eps=1e-5, max_pos=96)
+    rc = RoundCfg(name="planes", target=tf_(2), draft=tf_(1), head=HeadCfg(1, 128, 1024, n_steps=1), K=8, max_batch=8,
+                  max_ctx=96, entropy_layer=1, batch=8, n_ctx=1)
+    case = build_case(rc, seed=44)
+    ctx = make_ctx(case)
+    B, D, n_max = 8, 16, 64
+    rng = np.random.default_rng(10)
+    n = np.full(B, n_max, np.int32)
+    x = gen.bf16_round(rng.normal(size=(B, n_max, D)).astype(np.float32))
+    ctx.spec_kv_reset(0, None)
+    z_last = ctx.spec_prefill(0, ctx.dev_f32(x), n)
+    ctx.sync()
+    assert np.array_equal(ctx.spec_kv_lengths(0, B), n)
+    samples = [0, 5, 7]
+    _, zo = _oracle_prefill(case, 0, x, None, n, samples=samples)
+    e = rel_inf(z_last.float().cpu().numpy()[samples], np.stack([zo[b] for b in samples]))
+    print(f"planes: last-row features {e:.2e}")
+    assert e < TOL[DT_BF16]
+    ctx.close()

@@ -292,3 +292,59 @@ def test_attn_mode_round_runs_and_orders_entropy():
     # attention rows have 5 + i + 1 visible keys at draft step i: 0 < H <= ln(count)
     for i in range(rc.K):
         assert np.all(out["H"][:, i] > 0) and np.all(out["H"][:, i] <= math.log(6 + i) + 1e-12)
+
+
+def test_head_conditioning_path_written_out_by_hand():
+    """One block, non-zero modulation weights and a non-zero z: c = W_c z + b_c + temb(t), every modulation is a
+    projection of SiLU(c), split as shift | scale | gate (Sec. 3.2's conditioning on the AR feature).  Everything is
+    evaluated here with explicit loops and the math module; dropping SiLU(c), dropping temb from c, or permuting the
+    split changes the result by far more than the tolerance (checked below on the hand computation itself)."""
+    hc = HeadCfg(n_blocks=1, width=6, d_cond=5, d_latent=3, n_steps=1, t_freq_dim=4, t_scale=10.0)
+    W = head_w(hc, seed=3, std=0.5)
+    w, D = hc.width, hc.d_latent
+    Wf = {k: np.asarray(v, dtype=np.float64) for k, v in W.items()}
+    z = RNG.normal(size=hc.d_cond)
+    x_t = RNG.normal(size=D)
+    t = 0.6
+
+    def mv(vec, M, b):                                               # vec @ M + b by loops
+        return [sum(float(vec[k]) * float(M[k][j]) for k in range(len(vec))) + float(b[j]) for j in range(len(b))]
+
+    def silu(v):
+        return [a / (1.0 + math.exp(-a)) for a in v]
+
+    def ln(v):
+        m = sum(v) / len(v)
+        var = sum((a - m) ** 2 for a in v) / len(v)
+        return [(a - m) / math.sqrt(var + 1e-6) for a in v]
+
+    def by_hand(use_silu=True, use_temb=True, order=(0, 1, 2)):
+        half = hc.t_freq_dim // 2
+        om = [10000.0 ** (-k / half) for k in range(half)]
+        feat = [math.cos(t * hc.t_scale * o) for o in om] + [math.sin(t * hc.t_scale * o) for o in om]
+        temb = mv(silu(mv(feat, Wf["head.t1.w"], Wf["head.t1.b"])), Wf["head.t2.w"], Wf["head.t2.b"])
+        c = mv(z, Wf["head.c.w"], Wf["head.c.b"])
+        if use_temb:
+            c = [a + b for a, b in zip(c, temb)]
+        sc = silu(c) if use_silu else c
+        h = mv(x_t, Wf["head.in.w"], Wf["head.in.b"])
+        mod = mv(sc, Wf["head.B0.mod.w"], Wf["head.B0.mod.b"])
+        parts = [mod[0:w], mod[w:2 * w], mod[2 * w:3 * w]]
+        shift, scale, gate = parts[order[0]], parts[order[1]], parts[order[2]]
+        a = [n_ * (1.0 + s) + sh for n_, s, sh in zip(ln(h), scale, shift)]
+        a = silu(mv(a, Wf["head.B0.w1"], Wf["head.B0.b1"]))
+        br = mv(a, Wf["head.B0.w2"], Wf["head.B0.b2"])
+        h = [hv + g * b for hv, g, b in zip(h, gate, br)]
+        fm = mv(sc, Wf["head.f.mod.w"], Wf["head.f.mod.b"])
+        a = [n_ * (1.0 + s) + sh for n_, s, sh in zip(ln(h), fm[w:2 * w], fm[0:w])]
+        return np.array(mv(a, Wf["head.out.w"], Wf["head.out.b"]))
+
+    want = by_hand()
+    got = hd.velocity(hc, W, x_t[None, :], t, z[None, :])[0]
+    assert np.allclose(got, want, rtol=1e-11, atol=1e-13)
+    # the planted mistakes are visible at this size
+    for kw in (dict(use_silu=False), dict(use_temb=False), dict(order=(1, 0, 2)), dict(order=(0, 2, 1))):
+        assert np.abs(by_hand(**kw) - want).max() > 1e-3, kw
+    # and z really drives the modulation: another z, another velocity
+    got2 = hd.velocity(hc, W, x_t[None, :], t, (z + 1.0)[None, :])[0]
+    assert np.abs(got2 - got).max() > 1e-3

@@ -183,7 +183,7 @@ def test_gqa_with_repeated_kv_heads_equals_mha():
     assert np.allclose(za, zb, rtol=1e-11)
 
 
-def test_swiglu_equals_two_gemm_composition_and_up_projection():
+def test_up_projection_follows_the_final_norm():
     cfg = tiny("rms", L=1)
     W = weights(cfg)
     x = RNG.normal(size=(3, cfg.d_latent))
@@ -227,3 +227,103 @@ def test_class_id_row_uses_table_lookup():
     assert np.array_equal(z_a, z_b)
     z_c, _, _ = tf.forward_sample(cfg, W, "m", tf.KVCache(cfg, 1), 0, x, np.array([4, -1]))
     assert not np.allclose(z_a, z_c)
+
+
+# ----------------------------------------------------------------------------- MLP branches and the score scale, by hand
+def _plain_block_weights(cfg, W):
+    """Layer 0 with identity norms' gains, so that what the block adds can be written out by hand."""
+    V = {k: np.array(v, dtype=np.float64) for k, v in W.items()}
+    return V
+
+
+def test_swiglu_branch_equals_explicit_two_gemm_composition():
+    """h_out - h_mid = (SiLU(u W_g) * (u W_u)) W_d with every product taken by the triple loop and SiLU typed out:
+    a dropped SiLU, swapped gate/up, or a transposed operand fails here (no second oracle path is involved)."""
+    cfg = tiny("rms", L=1)
+    W = weights(cfg)
+    # switch the attention branch off (W_o = 0): the residual stream before the MLP is the embedding itself
+    W["m.L0.wo"] = np.zeros_like(W["m.L0.wo"])
+    x = RNG.normal(size=(3, cfg.d_latent))
+    _, sh, _ = tf.forward_sample(cfg, W, "m", tf.KVCache(cfg, 1), 0, x, shallow_layer=1)
+    h0 = np.array(loops.matmul_loops(x.tolist(), W["m.in.w"].astype(float).tolist())) + W["m.in.b"].astype(float)
+    g2 = W["m.L0.n2.g"].astype(float)
+    u = np.zeros_like(h0)
+    for i in range(h0.shape[0]):
+        ms = sum(float(v) ** 2 for v in h0[i]) / h0.shape[1]
+        for c in range(h0.shape[1]):
+            u[i, c] = h0[i, c] / math.sqrt(ms + cfg.norm_eps) * g2[c]
+    a = np.array(loops.matmul_loops(u.tolist(), W["m.L0.wg"].astype(float).tolist()))
+    b = np.array(loops.matmul_loops(u.tolist(), W["m.L0.wu"].astype(float).tolist()))
+    act = np.zeros_like(a)
+    for i in range(a.shape[0]):
+        for j in range(a.shape[1]):
+            act[i, j] = a[i, j] / (1.0 + math.exp(-a[i, j])) * b[i, j]
+    m = np.array(loops.matmul_loops(act.tolist(), W["m.L0.wd"].astype(float).tolist()))
+    assert np.allclose(sh, h0 + m, rtol=1e-11, atol=1e-13)
+    assert np.abs(m).max() > 1e-3                                   # the branch is not vacuous
+
+
+def test_gelu_branch_equals_explicit_composition():
+    """h_out - h_mid = GELU(u W_1 + b_1) W_2 + b_2, GELU(a) = a Phi(a) with the standard normal CDF from the
+    error function of the math module; products by the triple loop."""
+    cfg = tiny("ln", L=1)
+    W = weights(cfg)
+    W["m.L0.wo"] = np.zeros_like(W["m.L0.wo"])
+    W["m.L0.bo"] = np.zeros_like(W["m.L0.bo"])
+    n = 3
+    x = RNG.normal(size=(n, cfg.d_latent))
+    _, sh, _ = tf.forward_sample(cfg, W, "m", tf.KVCache(cfg, 1), 0, x, shallow_layer=1)
+    h0 = np.array(loops.matmul_loops(x.tolist(), W["m.in.w"].astype(float).tolist())) + W["m.in.b"].astype(float) \
+        + W["m.pos"][:n].astype(float)
+    g2, b2n = W["m.L0.n2.g"].astype(float), W["m.L0.n2.b"].astype(float)
+    u = np.zeros_like(h0)
+    for i in range(n):
+        mean = sum(h0[i]) / h0.shape[1]
+        var = sum((v - mean) ** 2 for v in h0[i]) / h0.shape[1]
+        for c in range(h0.shape[1]):
+            u[i, c] = (h0[i, c] - mean) / math.sqrt(var + cfg.norm_eps) * g2[c] + b2n[c]
+    a = np.array(loops.matmul_loops(u.tolist(), W["m.L0.w1"].astype(float).tolist())) + W["m.L0.b1"].astype(float)
+    act = np.array([[v * 0.5 * (1.0 + math.erf(v / math.sqrt(2.0))) for v in row] for row in a])
+    m = np.array(loops.matmul_loops(act.tolist(), W["m.L0.w2"].astype(float).tolist())) + W["m.L0.b2"].astype(float)
+    assert np.allclose(sh, h0 + m, rtol=1e-11, atol=1e-13)
+    assert np.abs(m).max() > 1e-3
+
+
+def test_score_scale_is_one_over_sqrt_head_dim_in_closed_form():
+    """One head, two keys, weights chosen so that q . k is known: row 1 sees keys 0 and 1 with scores
+    s_c = q_1 . k_c / sqrt(d_h); its attention entropy is the binary entropy of sigmoid(s_1 - s_0) and its
+    output is the sigmoid-weighted mean of the two values.  A missing or squared scale moves both."""
+    dh = 16
+    cfg = TfCfg(n_layers=1, d_model=dh, n_heads=1, n_kv_heads=1, d_head=dh, d_ff=8, act=ACT_GELU, norm=NORM_LAYER,
+                pos=POS_LEARNED, has_bias=1, d_latent=4, max_pos=8)
+    W = weights(cfg)
+    d = dh
+    # q = k = v = the normalised row itself (identity projections, no bias); W_o = I; MLP output switched off
+    W["m.L0.wqkv"] = np.concatenate([np.eye(d), np.eye(d), np.eye(d)], axis=1).astype(np.float32)
+    W["m.L0.bqkv"] = np.zeros(3 * d, np.float32)
+    W["m.L0.wo"] = np.eye(d, dtype=np.float32)
+    W["m.L0.bo"] = np.zeros(d, np.float32)
+    W["m.L0.w2"] = np.zeros_like(W["m.L0.w2"])
+    W["m.L0.b2"] = np.zeros_like(W["m.L0.b2"])
+    W["m.L0.n1.g"] = np.ones(d, np.float32)
+    W["m.L0.n1.b"] = np.zeros(d, np.float32)
+    x = RNG.normal(size=(2, 4))
+    _, sh, ha = tf.forward_sample(cfg, W, "m", tf.KVCache(cfg, 1), 0, x, shallow_layer=1)
+    h0 = x @ W["m.in.w"].astype(float) + W["m.in.b"].astype(float) + W["m.pos"][:2].astype(float)
+    u = np.zeros_like(h0)
+    for i in range(2):
+        mean = sum(h0[i]) / d
+        var = sum((v - mean) ** 2 for v in h0[i]) / d
+        u[i] = [(v - mean) / math.sqrt(var + cfg.norm_eps) for v in h0[i]]
+    s0 = sum(u[1][t] * u[0][t] for t in range(d)) / math.sqrt(dh)
+    s1 = sum(u[1][t] * u[1][t] for t in range(d)) / math.sqrt(dh)
+    p1 = 1.0 / (1.0 + math.exp(-(s1 - s0)))
+    p0 = 1.0 - p1
+    assert 0.02 < p0 < 0.98                                          # both keys matter
+    assert ha[0] == pytest.approx(0.0, abs=1e-14)                    # row 0 sees one key
+    assert ha[1] == pytest.approx(-(p0 * math.log(p0) + p1 * math.log(p1)), rel=1e-11)
+    assert np.allclose(sh[1], h0[1] + p0 * u[0] + p1 * u[1], rtol=1e-11)
+    # with the scale dropped (or applied twice) the same closed form gives another number
+    for wrong in (1.0, 1.0 / dh):
+        pw = 1.0 / (1.0 + math.exp(-(s1 - s0) * math.sqrt(dh) * wrong))
+        assert abs(pw - p1) > 1e-3
