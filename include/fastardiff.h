@@ -117,11 +117,16 @@ int spec_round_destroy(fard_ctx* ctx);
 /* Sets the cached length of every sample of model `which` (FARD_TARGET / FARD_DRAFT).
  * cache_len: HOST int32 [B] or NULL (all 0).  Does not touch cache contents. */
 int spec_kv_reset(fard_ctx* ctx, int32_t which, const int32_t* cache_len, int32_t B);
+/* The same from DEVICE memory, without a host synchronisation (a serving loop that rewinds or re-seats its samples
+ * between rounds of Alg. 1): cache_len[b] = clamp(cache_len_dev[b], 0, len_hi) for b < B.  len_hi (host) is the
+ * caller's upper bound of those lengths; capacity is checked against it from then on.  cache_len_dev: device int32 [B]. */
+int spec_kv_restore(fard_ctx* ctx, int32_t which, const int32_t* cache_len_dev, int32_t B, int32_t len_hi);
 /* Writes positions 0..n-1 of one layer's cache from plain tensors k, v [B, H_kv, n, d_head] in
  * storage type (synthetic caches).  Lengths are set with spec_kv_reset. */
 int spec_kv_load(fard_ctx* ctx, int32_t which, int32_t layer, const void* k, const void* v,
                  int32_t B, int32_t n);
-/* Copies the current lengths to HOST int32 [B].  Synchronises. */
+/* Copies the current lengths to HOST int32 [B].  Synchronises.  Also resets the host-side upper bound that the
+ * capacity checks use (it grows by K + 1 per round whatever was accepted) to the true maximum over all samples. */
 int spec_kv_lengths(fard_ctx* ctx, int32_t which, int32_t* out_host, int32_t B);
 /* cache_len[b] = base_len[b] + 1 + n_accept[b] for both models: the pending token and the accepted
  * drafts become context (Alg. 1 Step 4).  n_accept: device int32 [B]. `which`: FARD_TARGET,
@@ -167,6 +172,18 @@ int spec_prefill(fard_ctx* ctx, int32_t which, const float* x, const int32_t* fi
  *   surv_idx int32 [B*K] (first n_surv valid); n_surv int32 [1].  B*K = 0 gives n_surv = 0. */
 int entropy_prefilter(fard_ctx* ctx, const void* feat, int32_t B, int32_t K, int32_t L, float tau,
                       float* H, uint8_t* keep, int32_t* n_keep, int32_t* surv_idx, int32_t* n_surv);
+/* entropy_prefilter for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): needs no context and calls no allocating routine.  Same operation, same
+ * kernels and the same outputs as entropy_prefilter; the per-workgroup survivor counts that the large-batch path
+ * (B > 1024) passes from its first launch to its second live in an 8 KiB device array inside the library, one copy
+ * per GPU, held until the process ends.
+ *   dtype       FARD_F32 / FARD_BF16: element type of feat
+ *   hip_stream  hipStream_t to enqueue on (NULL: default stream) on the CURRENT device; does not synchronise
+ * Limits: B <= 2^21 samples and B * K <= 2^24 rows, else FARD_ECAPACITY.  All calls on one GPU share that array: calls
+ * that overlap on one GPU (different streams, different threads) race; calls in stream order do not (nothing in the
+ * array has to survive between calls or start at zero).  Errors are returned as codes only (no context, no text). */
+int entropy_prefilter_static(const void* feat, int32_t dtype, int32_t B, int32_t K, int32_t L, float tau, float* H,
+                             uint8_t* keep, int32_t* n_keep, int32_t* surv_idx, int32_t* n_surv, void* hip_stream);
 /* tau = 0.3 * mean_H - 0.1 * std_H (Sec. 4.3). Host-only helper. */
 float entropy_threshold(float mean_H, float std_H);
 

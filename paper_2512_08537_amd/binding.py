@@ -54,11 +54,13 @@ _SIGS = {
     "spec_round_init": [C.POINTER(RoundCfg), C.POINTER(Tensor), _i32, _vp, C.POINTER(_vp)],
     "spec_round_destroy": [_vp],
     "spec_kv_reset": [_vp, _i32, _vp, _i32],
+    "spec_kv_restore": [_vp, _i32, _vp, _i32, _i32],
     "spec_kv_load": [_vp, _i32, _i32, _vp, _vp, _i32, _i32],
     "spec_kv_lengths": [_vp, _i32, _vp, _i32],
     "spec_kv_commit": [_vp, _i32, _vp, _i32],
     "spec_forward": [_vp, _i32, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp],
     "entropy_prefilter": [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp],
+    "entropy_prefilter_static": [_vp, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp],
     "diffhead_decode": [_vp, _vp, _vp, _i32, _vp, _vp, _vp],
     "spec_draft": [_vp, _vp, _vp, _vp, _f32, _i32, _vp, _vp, _vp, _vp, _vp],
     "spec_verify": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp],
@@ -118,6 +120,20 @@ def _ptr(t):
     if t is None:
         return None
     return C.c_void_p(t.data_ptr())
+
+
+def entropy_prefilter_static(feat, tau, out, stream=None):
+    """feat: device tensor [B, K, L], float32 or bfloat16; out: dict of preallocated device tensors H [B,K] f32,
+    keep [B,K] u8, n_keep [B] i32, surv_idx [B*K] i32, n_surv [1] i32.  Allocates nothing."""
+    import torch
+    B, K, L = feat.shape
+    dt = FARD_BF16 if feat.dtype == torch.bfloat16 else FARD_F32
+    code = lib.entropy_prefilter_static(_ptr(feat), dt, B, K, L, float(tau), _ptr(out["H"]), _ptr(out["keep"]),
+                                        _ptr(out["n_keep"]), _ptr(out["surv_idx"]), _ptr(out["n_surv"]),
+                                        None if stream is None else C.c_void_p(stream.cuda_stream))
+    if code != 0:
+        raise FardError(code, "entropy_prefilter_static")
+    return out
 
 
 def entropy_threshold(mean_h: float, std_h: float) -> float:
@@ -204,6 +220,10 @@ class Context:
         else:
             a = np.ascontiguousarray(cache_len, dtype=np.int32)
             self._chk(lib.spec_kv_reset(self.h, which, a.ctypes.data_as(C.c_void_p), len(a)))
+
+    def spec_kv_restore(self, which, cache_len_dev, len_hi):
+        """cache_len_dev: device int32 [B]; len_hi: host upper bound of its values."""
+        self._chk(lib.spec_kv_restore(self.h, which, _ptr(cache_len_dev), cache_len_dev.numel(), int(len_hi)))
 
     def spec_kv_load(self, which, layer, k, v):
         """k, v: device tensors [B, H_kv, n, d_head] of the storage type."""

@@ -10,6 +10,7 @@
 
 #include <algorithm>
 #include <map>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -45,6 +46,11 @@ __global__ void len_commit_kernel(int* len, const int* base, const int* n_accept
     if (add < 1) add = 1;
     len[b] = base[b] + add;
   }
+}
+// len[b] = src[b] clamped to [0, hi]: the device values can never exceed the bound the host checks capacity with
+__global__ void len_restore_kernel(const int* __restrict__ src, int* __restrict__ len, int B, int hi) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) len[b] = min(max(src[b], 0), hi);
 }
 __global__ void copy_i32_kernel(const int* src, int* dst, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1028,6 +1034,22 @@ int spec_kv_reset(fard_ctx* c, int32_t which, const int32_t* cache_len, int32_t 
   return FARD_OK;
 }
 
+int spec_kv_restore(fard_ctx* c, int32_t which, const int32_t* cache_len_dev, int32_t B, int32_t len_hi) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (len_hi < 0 || len_hi > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "len_hi outside [0, max_ctx]");
+  if (B > 0 && !cache_len_dev) return fail(c, FARD_EINVAL, "null cache_len_dev");
+  Model& m = c->mdl[which];
+  if (B > 0) {
+    len_restore_kernel<<<(B + 255) / 256, 256, 0, c->stream>>>(cache_len_dev, m.len, B, len_hi);
+    HIPCHK(c, hipGetLastError());
+  }
+  m.len_hi = len_hi;
+  m.written = 0;
+  return FARD_OK;
+}
+
 int spec_kv_load(fard_ctx* c, int32_t which, int32_t layer, const void* k, const void* v, int32_t B, int32_t n) {
   if (check_ctx(c)) return FARD_EINVAL;
   if (which != FARD_TARGET && which != FARD_DRAFT) return fail(c, FARD_EINVAL, "which");
@@ -1044,8 +1066,16 @@ int spec_kv_lengths(fard_ctx* c, int32_t which, int32_t* out_host, int32_t B) {
   if (check_ctx(c)) return FARD_EINVAL;
   if ((which != FARD_TARGET && which != FARD_DRAFT) || !out_host) return fail(c, FARD_EINVAL, "which/out");
   if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
-  HIPCHK(c, hipMemcpyAsync(out_host, c->mdl[which].len, (size_t)B * 4, hipMemcpyDeviceToHost, c->stream));
+  // all max_batch lengths come back: the host's upper bound (which a round can only raise by K + 1, whatever was
+  // accepted) is reset to the true maximum, so that a caller looping over rounds does not run into FARD_ECAPACITY early
+  Model& m = c->mdl[which];
+  std::vector<int32_t> all((size_t)c->cfg.max_batch);
+  HIPCHK(c, hipMemcpyAsync(all.data(), m.len, all.size() * 4, hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  int hi = 0;
+  for (int32_t v : all) hi = std::max(hi, (int)v);
+  if (m.written == 0) m.len_hi = hi;       // (between a draft / verify and its commit the bound covers uncommitted rows)
+  for (int b = 0; b < B; ++b) out_host[b] = all[b];
   return FARD_OK;
 }
 
@@ -1220,6 +1250,50 @@ int entropy_prefilter(fard_ctx* c, const void* feat, int32_t B, int32_t K, int32
   if (!feat || !H || !keep || !n_keep || !surv_idx) return fail(c, FARD_EINVAL, "null argument");
   Bracket br(c, CLS_ENT, 0, (double)B * K * L * c->esz);
   HIPCHK(c, launch_entropy_prefilter(c->stream, c->bf16, feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, c->ent_blk));
+  return FARD_OK;
+}
+
+// ---- the pre-filter for callers that cannot allocate: no context, scratch in a file-scope device array
+constexpr int STATIC_PF_MAX_B = 1 << 21;                 // samples
+constexpr long STATIC_PF_MAX_ROWS = 1L << 24;            // B * K
+constexpr int STATIC_PF_MAX_DEVICES = 64;
+}  // extern "C"
+// per-workgroup survivor counts of the large-batch path (entropy_samples_kernel -> entropy_compact_kernel); every
+// GPU the library runs on holds its own copy until the process ends
+static __device__ __align__(256) int scratch[fard::ENT_MAX_BLOCKS];
+static int* g_scratch_ptr[STATIC_PF_MAX_DEVICES];        // the array's device address, per device (nullptr: not asked yet)
+static std::mutex g_scratch_mu;
+extern "C" {
+
+int entropy_prefilter_static(const void* feat, int32_t dtype, int32_t B, int32_t K, int32_t L, float tau, float* H,
+                             uint8_t* keep, int32_t* n_keep, int32_t* surv_idx, int32_t* n_surv, void* hip_stream) {
+  if (dtype != FARD_F32 && dtype != FARD_BF16) return FARD_EINVAL;
+  if (B < 0 || K < 0 || L < 1) return FARD_ESHAPE;
+  if (B > STATIC_PF_MAX_B || (long)B * K > STATIC_PF_MAX_ROWS) return FARD_ECAPACITY;
+  if (!n_surv) return FARD_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if ((long)B * K == 0) {
+    if (launch_fill_i32(s, n_surv, 0, 1) != hipSuccess) return FARD_EHIP;
+    if (B > 0 && n_keep && launch_fill_i32(s, n_keep, 0, B) != hipSuccess) return FARD_EHIP;
+    return FARD_OK;
+  }
+  if (!feat || !H || !keep || !n_keep || !surv_idx) return FARD_EINVAL;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_PF_MAX_DEVICES) return FARD_EHIP;
+  int* blk = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+      // the array's name is only a host-side handle: its address on the current device has to be asked for
+      int* p = nullptr;
+      if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FARD_EHIP;
+      g_scratch_ptr[dev] = p;
+    }
+    blk = g_scratch_ptr[dev];
+  }
+  // every workgroup of the first launch overwrites its own count before the second launch reads it: nothing to clear
+  if (launch_entropy_prefilter(s, dtype == FARD_BF16, feat, B, K, L, tau, H, keep, n_keep, surv_idx, n_surv, blk) != hipSuccess)
+    return FARD_EHIP;
   return FARD_OK;
 }
 
