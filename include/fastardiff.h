@@ -205,6 +205,16 @@ int spec_draft(fard_ctx* ctx, const float* x_pending, const int32_t* pending_id,
                float tau, int32_t B, float* H, uint8_t* keep, int32_t* n_keep, float* x_draft,
                float* mu_q);
 
+/* Alg. 1 Step 1, one draft step per call (a serving loop that interleaves other work, or that supplies the token
+ * a step reads): step i = 0 starts a draft stage like spec_draft does, steps must follow in order, and after the last
+ * one the state is that of spec_draft (spec_verify / spec_kv_commit as usual).  Same kernels and launches as spec_draft.
+ *   x_prev fp32 [B, D]: the token step i reads (token i-1; the pending token for i = 0), or NULL for i > 0: the
+ *   library's own draft x_draft[:, i-1, :].  prev_id int32 [B] or NULL (>= 0: that token is an id row).
+ *   The other arguments are those of spec_draft; a step writes column i of H / keep and row i of x_draft / mu_q.
+ * Errors: FARD_ESTATE for steps out of order, FARD_EINVAL for i outside [0, K) or a NULL x_prev at i = 0. */
+int spec_draft_step(fard_ctx* ctx, int32_t i, const float* x_prev, const int32_t* prev_id, const float* eps,
+                    float tau, int32_t B, float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q);
+
 /* Alg. 1 Steps 2-4: target forward over [pending, x_1..x_K'] per sample (K' = n_keep[b]), head on
  * all K'+1 rows with the shared noise, ratio and accept test.
  *   log_sigma_factor = ln Sigma of S3 item 2; sigma_p, sigma_q: std of the last transition.

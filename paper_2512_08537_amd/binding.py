@@ -63,6 +63,7 @@ _SIGS = {
     "entropy_prefilter_static": [_vp, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _vp],
     "diffhead_decode": [_vp, _vp, _vp, _i32, _vp, _vp, _vp],
     "spec_draft": [_vp, _vp, _vp, _vp, _f32, _i32, _vp, _vp, _vp, _vp, _vp],
+    "spec_draft_step": [_vp, _i32, _vp, _vp, _vp, _f32, _i32, _vp, _vp, _vp, _vp, _vp],
     "spec_verify": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp],
     "spec_accept": [_vp, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i32, _vp, _vp, _vp],
     "spec_round": [_vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _f32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
@@ -306,6 +307,13 @@ class Context:
         self._chk(lib.spec_draft(self.h, _ptr(x_pending), _ptr(pending_id), _ptr(eps), float(tau), B, _ptr(o["H"]),
                                  _ptr(o["keep"]), _ptr(o["n_keep"]), _ptr(o["x_draft"]), _ptr(o["mu_q"])))
         return o
+
+    def spec_draft_step(self, i, x_prev, eps, tau, out, prev_id=None):
+        """One draft step; out: the dict of _round_bufs that all steps of the stage share."""
+        B = out["n_keep"].numel()
+        self._chk(lib.spec_draft_step(self.h, int(i), _ptr(x_prev), _ptr(prev_id), _ptr(eps), float(tau), B, _ptr(out["H"]),
+                                      _ptr(out["keep"]), _ptr(out["n_keep"]), _ptr(out["x_draft"]), _ptr(out["mu_q"])))
+        return out
 
     def spec_verify(self, x_pending, x_draft, mu_q, n_keep, r, eps, log_sigma=0.0, sigma_p=None, sigma_q=None,
                     pending_id=None, want_z=False, out=None):

@@ -1319,55 +1319,105 @@ int spec_accept(fard_ctx* c, const float* x_draft, const float* mu_p, const floa
   return FARD_OK;
 }
 
-int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, float tau, int32_t B,
-               float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q) {
-  if (check_ctx(c)) return FARD_EINVAL;
-  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
-  if (B == 0) return FARD_OK;
-  if (!x_pending || !eps || !H || !keep || !n_keep || !x_draft || !mu_q) return fail(c, FARD_EINVAL, "null argument");
+// Start of a draft stage: the lengths to roll back to, every sample alive, outputs cleared.
+static int draft_begin(fard_ctx* c, int B, int32_t* n_keep, float* x_draft, float* mu_q) {
   Model& m = c->mdl[FARD_DRAFT];
-  if (pending_id && !m.cond) return fail(c, FARD_EINVAL, "pending_id given but the draft has no id table");
+  const int K = c->cfg.K, D = m.c.d_latent;
+  hipStream_t s = c->stream;
+  Bracket br(c, CLS_OTHER);
+  copy_i32_kernel<<<(B + 255) / 256, 256, 0, s>>>(m.len, m.len_base, B);
+  HIPCHK(c, hipGetLastError());
+  HIPCHK(c, launch_fill_i32(s, c->alive, 1, B));
+  HIPCHK(c, launch_fill_i32(s, n_keep, 0, B));
+  // dropped drafts keep finite values: they still travel through the dense draft rows
+  HIPCHK(c, launch_fill_f32(s, x_draft, 0.f, (size_t)B * K * D));
+  HIPCHK(c, launch_fill_f32(s, mu_q, 0.f, (size_t)B * K * D));
+  m.written = 0;
+  return FARD_OK;
+}
+
+// One row per sample: the row maps of a draft step (positions = current lengths).
+static int draft_maps(fard_ctx* c, int B) {
+  Model& m = c->mdl[FARD_DRAFT];
+  Bracket br(c, CLS_OTHER);
+  HIPCHK(c, launch_build_rows(c->stream, nullptr, 1, B, c->cfg.K, m.c.d_latent, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, B, 1));
+  return FARD_OK;
+}
+
+// Draft step i: reads the previous token of every sample (xs, row stride ldx), produces draft i of the samples that
+// are still speculating, advances the draft cache by one position.
+static int draft_step(fard_ctx* c, int i, const float* xs, int ldx, const int32_t* ids, const float* eps, float tau, int B,
+                      float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q) {
+  Model& m = c->mdl[FARD_DRAFT];
   const int K = c->cfg.K, D = m.c.d_latent, d = m.c.d_model, ls = c->cfg.entropy_layer;
-  if (m.len_hi + K > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "draft cache_len + K exceeds max_ctx");
-  if (m.c.pos == FARD_POS_LEARNED && m.len_hi + K > m.c.max_pos) return fail(c, FARD_ECAPACITY, "draft position beyond the learned table");
   hipStream_t s = c->stream;
   const size_t eps_stride = (size_t)B * (K + 1) * D;
   int rc;
-  { Bracket br(c, CLS_OTHER);
-    copy_i32_kernel<<<(B + 255) / 256, 256, 0, s>>>(m.len, m.len_base, B);
-    HIPCHK(c, hipGetLastError());
-    HIPCHK(c, launch_fill_i32(s, c->alive, 1, B));
-    HIPCHK(c, launch_fill_i32(s, n_keep, 0, B));
-    // dropped drafts keep finite values: they still travel through the dense draft rows
-    HIPCHK(c, launch_fill_f32(s, x_draft, 0.f, (size_t)B * K * D));
-    HIPCHK(c, launch_fill_f32(s, mu_q, 0.f, (size_t)B * K * D)); }
+  HIPCHK(c, embed_first_norm(c, FARD_DRAFT, xs, ldx, ids, B, nullptr));
+  const bool attn_mode = c->cfg.entropy_mode == FARD_ENT_ATTN;
+  if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0, true))) return rc;
+  // pending partial planes of the last shallow layer: the entropy rows add them on the fly and the next norm
+  // folds them into the stream; otherwise they are folded here
+  const bool ent_folds = !attn_mode && ls < m.c.n_layers && ent_rows_in_regs_f32(c->h, d, d);
+  if (!ent_folds && (rc = flush_parts(c, d, B, nullptr))) return rc;
+  { Bracket br(c, CLS_ENT, 0, (double)B * d * 4);
+    if (!attn_mode)
+      HIPCHK(c, launch_entropy_rows_f32(s, c->h, d, B, d, c->h_row, c->parts, ent_folds ? c->pend_n : 0, c->pend_stride));
+    HIPCHK(c, launch_entropy_step(s, attn_mode ? c->ent_heads : nullptr, m.c.n_heads, c->h_row, B, K, i, tau, H, keep, c->alive,
+                                  n_keep, c->act_idx, c->n_act, c->emap, c->omap)); }
+  if ((rc = run_layers(c, FARD_DRAFT, ls, m.c.n_layers, B, B, 1, nullptr, 0))) return rc;
+  // only samples that are still speculating reach the head
+  if ((rc = run_final(c, FARD_DRAFT, B, c->n_act, c->act_idx, c->z))) return rc;
+  if ((rc = run_head(c, c->z, B, c->n_act, eps, eps_stride, c->emap, c->omap, mu_q, x_draft))) return rc;
+  HIPCHK(c, launch_len_add(s, m.len, nullptr, 1, B, c->maps.row_pos));
+  m.len_hi += 1;
+  m.written += 1;
+  return FARD_OK;
+}
+
+static int draft_checks(fard_ctx* c, const float* x_first, const int32_t* id, const float* eps, int B, const float* H,
+                        const uint8_t* keep, const int32_t* n_keep, const float* x_draft, const float* mu_q, int steps) {
+  if (B < 0 || B > c->cfg.max_batch) return fail(c, FARD_ECAPACITY, "B > max_batch");
+  if (!x_first || !eps || !H || !keep || !n_keep || !x_draft || !mu_q) return fail(c, FARD_EINVAL, "null argument");
+  Model& m = c->mdl[FARD_DRAFT];
+  if (id && !m.cond) return fail(c, FARD_EINVAL, "pending_id given but the draft has no id table");
+  if (m.len_hi + steps > c->cfg.max_ctx) return fail(c, FARD_ECAPACITY, "draft cache_len + K exceeds max_ctx");
+  if (m.c.pos == FARD_POS_LEARNED && m.len_hi + steps > m.c.max_pos) return fail(c, FARD_ECAPACITY, "draft position beyond the learned table");
+  return FARD_OK;
+}
+
+int spec_draft(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* eps, float tau, int32_t B,
+               float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (B == 0) return FARD_OK;
+  int rc = draft_checks(c, x_pending, pending_id, eps, B, H, keep, n_keep, x_draft, mu_q, c->cfg.K);
+  if (rc) return rc;
+  const int K = c->cfg.K, D = c->mdl[FARD_DRAFT].c.d_latent;
+  if ((rc = draft_begin(c, B, n_keep, x_draft, mu_q))) return rc;
   // one row per sample in every step: the row maps are built once, the positions move on with the lengths
-  { Bracket br(c, CLS_OTHER);
-    HIPCHK(c, launch_build_rows(s, nullptr, 1, B, K, D, m.len, c->maps, nullptr, nullptr, nullptr, nullptr, B, 1)); }
+  if ((rc = draft_maps(c, B))) return rc;
   for (int i = 0; i < K; ++i) {
     const float* xs = (i == 0) ? x_pending : x_draft + (size_t)(i - 1) * D;
     const int ldx = (i == 0) ? D : K * D;
-    HIPCHK(c, embed_first_norm(c, FARD_DRAFT, xs, ldx, i == 0 ? pending_id : nullptr, B, nullptr));
-    const bool attn_mode = c->cfg.entropy_mode == FARD_ENT_ATTN;
-    if ((rc = run_layers(c, FARD_DRAFT, 0, ls, B, B, 1, nullptr, attn_mode ? ls : 0, true))) return rc;
-    // pending partial planes of the last shallow layer: the entropy rows add them on the fly and the next norm
-    // folds them into the stream; otherwise they are folded here
-    const bool ent_folds = !attn_mode && ls < m.c.n_layers && ent_rows_in_regs_f32(c->h, d, d);
-    if (!ent_folds && (rc = flush_parts(c, d, B, nullptr))) return rc;
-    { Bracket br(c, CLS_ENT, 0, (double)B * d * 4);
-      if (!attn_mode)
-        HIPCHK(c, launch_entropy_rows_f32(s, c->h, d, B, d, c->h_row, c->parts, ent_folds ? c->pend_n : 0, c->pend_stride));
-      HIPCHK(c, launch_entropy_step(s, attn_mode ? c->ent_heads : nullptr, m.c.n_heads, c->h_row, B, K, i, tau, H, keep, c->alive,
-                                    n_keep, c->act_idx, c->n_act, c->emap, c->omap)); }
-    if ((rc = run_layers(c, FARD_DRAFT, ls, m.c.n_layers, B, B, 1, nullptr, 0))) return rc;
-    // only samples that are still speculating reach the head
-    if ((rc = run_final(c, FARD_DRAFT, B, c->n_act, c->act_idx, c->z))) return rc;
-    if ((rc = run_head(c, c->z, B, c->n_act, eps, eps_stride, c->emap, c->omap, mu_q, x_draft))) return rc;
-    HIPCHK(c, launch_len_add(s, m.len, nullptr, 1, B, c->maps.row_pos));
+    if ((rc = draft_step(c, i, xs, ldx, i == 0 ? pending_id : nullptr, eps, tau, B, H, keep, n_keep, x_draft, mu_q))) return rc;
   }
-  m.len_hi += K;
-  m.written = K;
   return FARD_OK;
+}
+
+int spec_draft_step(fard_ctx* c, int32_t i, const float* x_prev, const int32_t* prev_id, const float* eps, float tau, int32_t B,
+                    float* H, uint8_t* keep, int32_t* n_keep, float* x_draft, float* mu_q) {
+  if (check_ctx(c)) return FARD_EINVAL;
+  if (i < 0 || i >= c->cfg.K) return fail(c, FARD_EINVAL, "step index outside [0, K)");
+  if (B == 0) return FARD_OK;
+  const int K = c->cfg.K, D = c->mdl[FARD_DRAFT].c.d_latent;
+  if (i > 0 && c->mdl[FARD_DRAFT].written != i) return fail(c, FARD_ESTATE, "draft steps must be taken in order, from step 0");
+  const float* xs = x_prev ? x_prev : (i > 0 ? x_draft + (size_t)(i - 1) * D : nullptr);
+  const int ldx = x_prev ? D : K * D;
+  int rc = draft_checks(c, xs, prev_id, eps, B, H, keep, n_keep, x_draft, mu_q, 1);
+  if (rc) return rc;
+  if (i == 0 && (rc = draft_begin(c, B, n_keep, x_draft, mu_q))) return rc;
+  if ((rc = draft_maps(c, B))) return rc;                // other calls may have used the row maps in between
+  return draft_step(c, i, xs, ldx, prev_id, eps, tau, B, H, keep, n_keep, x_draft, mu_q);
 }
 
 int spec_verify(fard_ctx* c, const float* x_pending, const int32_t* pending_id, const float* x_draft, const float* mu_q,

@@ -27,7 +27,7 @@ class Case:
 
 
 def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_draft=False, cache_layers_shared=False,
-               std_overrides=None, peaky=False, deep_gain=1.0) -> Case:
+               std_overrides=None, peaky=False, deep_gain=1.0, lazy=False) -> Case:
     rc = kind if isinstance(kind, RoundCfg) else (config(kind) if isinstance(kind, int) else reduced(kind))
     rc = clone(rc)
     if same_draft:
@@ -41,15 +41,28 @@ def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_d
         std_overrides["wqkv"] = 1.4 / np.sqrt(min(rc.target.d_model, rc.draft.d_model))
     if w_std is None:
         w_std = 0.02                                       # the workload recipe: N(0, 0.02)
-    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
-                       deep_from=rc.draft.n_layers, deep_gain=deep_gain)
     same_shape = (rc.draft.d_model, rc.draft.n_heads, rc.draft.n_kv_heads, rc.draft.d_ff) == \
                  (rc.target.d_model, rc.target.n_heads, rc.target.n_kv_heads, rc.target.d_ff)
+    # lazy: the weights are drawn tensor by tensor when read (gen.LazyWeights) instead of all at once; same values
+    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
+                       deep_from=rc.draft.n_layers, deep_gain=deep_gain, recipes_only=lazy)
+    aliases = {}
     if same_shape:
-        W.update(gen.truncated_draft(W, rc.target, rc.draft))
+        if lazy:
+            aliases = gen.truncated_draft(W, rc.target, rc.draft, names_only=True)
+        else:
+            W.update(gen.truncated_draft(W, rc.target, rc.draft))
     else:
-        W.update(gen.tf_weights(rc.draft, seed, "draft", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides))
-    W.update(gen.head_weights(rc.head, seed, rc.dtype, w_std=w_std, affine=affine))
+        W.update(gen.tf_weights(rc.draft, seed, "draft", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
+                                recipes_only=lazy))
+    W.update(gen.head_weights(rc.head, seed, rc.dtype, w_std=w_std, affine=affine, recipes_only=lazy))
+    if lazy:
+        numel = {}
+        for pre, shapes in (("target", gen.tf_weight_shapes(rc.target)), ("draft", gen.tf_weight_shapes(rc.draft)),
+                            ("head", gen.head_weight_shapes(rc.head))):
+            for name, (shape, _) in shapes.items():
+                numel[f"{pre}.{name}"] = int(np.prod(shape))
+        W = gen.LazyWeights(W, aliases, numel=numel)
     cache_t, cache_d = [], []
     for l in range(rc.target.n_layers):
         src = 0 if cache_layers_shared else l

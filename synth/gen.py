@@ -115,9 +115,10 @@ def head_weight_shapes(h: HeadCfg) -> dict:
     return s
 
 
-def _draw_weights(shapes, seed, prefix, dtype, w_std, affine, layers=None, std_overrides=None):
-    """affine=False: gains 1, biases 0 (the benchmark recipe).  affine=True: gains
-    1 + N(0, 0.1), biases N(0, 0.05) so that a wrong gain/bias index changes results."""
+def _weight_recipes(shapes, seed, prefix, dtype, w_std, affine, std_overrides=None):
+    """name -> zero-argument function that draws the tensor (its own sub-stream: the order of the calls never matters).
+    affine=False: gains 1, biases 0 (the benchmark recipe).  affine=True: gains 1 + N(0, 0.1), biases N(0, 0.05) so
+    that a wrong gain/bias index changes results."""
     out = {}
     for name, (shape, kind) in shapes.items():
         full = f"{prefix}.{name}"
@@ -127,18 +128,136 @@ def _draw_weights(shapes, seed, prefix, dtype, w_std, affine, layers=None, std_o
                 for key, val in std_overrides.items():
                     if name.endswith(key):
                         std = val
-            out[full] = normal(seed, full, shape, std, dtype)
+            out[full] = (lambda full=full, shape=shape, std=std: normal(seed, full, shape, std, dtype))
         elif kind == "g":
-            out[full] = (normal(seed, full, shape, 0.1, dtype, mean=1.0) if affine
-                         else np.ones(shape, np.float32))
+            out[full] = ((lambda full=full, shape=shape: normal(seed, full, shape, 0.1, dtype, mean=1.0)) if affine
+                         else (lambda shape=shape: np.ones(shape, np.float32)))
         else:
-            out[full] = (normal(seed, full, shape, 0.05, dtype) if affine
-                         else np.zeros(shape, np.float32))
+            out[full] = ((lambda full=full, shape=shape: normal(seed, full, shape, 0.05, dtype)) if affine
+                         else (lambda shape=shape: np.zeros(shape, np.float32)))
     return out
 
 
+def _draw_all(recipes: dict, workers: int = 8) -> dict:
+    """Draws every tensor; large sets on a few threads (numpy's generators release the GIL while they fill)."""
+    names = list(recipes)
+    if len(names) < 8:
+        return {n: recipes[n]() for n in names}
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        vals = list(ex.map(lambda n: recipes[n](), names))
+    return dict(zip(names, vals))
+
+
+def _draw_weights(shapes, seed, prefix, dtype, w_std, affine, layers=None, std_overrides=None):
+    return _draw_all(_weight_recipes(shapes, seed, prefix, dtype, w_std, affine, std_overrides))
+
+
+class LazyWeights:
+    """A weight set that is drawn tensor by tensor on demand instead of being held whole (the 11 B parameters of the
+    text-to-image configuration are 44 GB as float32).  Reading `W[name]` draws the tensor from its own sub-stream
+    (the same values as the eager dictionaries) and keeps it in a least-recently-used cache of `budget_bytes`;
+    `as_f64=True` hands out float64 arrays (what the CPU oracle widens to anyway).  `items()` walks all tensors in
+    order with `prefetch` of them being drawn ahead on threads (for uploading a whole set with bounded host memory)."""
+
+    def __init__(self, recipes: dict, aliases: dict | None = None, budget_bytes: int = 6 << 30, as_f64: bool = False,
+                 prefetch: int = 6, readahead: int = 0, numel: dict | None = None):
+        self._rec = dict(recipes)
+        self._alias = dict(aliases or {})
+        self._budget = int(budget_bytes)
+        self._f64 = as_f64
+        self._prefetch = prefetch
+        self._readahead = readahead                        # tensors drawn ahead of a reader that follows the listed order
+        self._numel = dict(numel or {})                    # name -> element count (sizes of tensors still being drawn)
+        self._names = list(self._rec)
+        self._order = {n: i for i, n in enumerate(self._names)}
+        self._pool = None
+        from collections import OrderedDict
+        self._cache = OrderedDict()
+        self._sizes = {}
+        self._bytes = 0
+
+    def _draw(self, name):
+        x = self._rec[self._alias.get(name, name)]()
+        return x.astype(np.float64) if self._f64 else x
+
+    def keys(self):
+        return list(self._rec) + list(self._alias)
+
+    def __iter__(self):
+        return iter(self.keys())
+
+    def __len__(self):
+        return len(self._rec) + len(self._alias)
+
+    def __contains__(self, name):
+        return name in self._rec or name in self._alias
+
+    def __getitem__(self, name):
+        if name not in self:
+            raise KeyError(name)
+        key = self._alias.get(name, name)
+        self._read_ahead(key)
+        if key in self._cache:
+            self._cache.move_to_end(key)
+            x = self._cache[key]
+            if hasattr(x, "result"):                       # still being drawn on a thread
+                x = x.result()
+                self._cache[key] = x
+            return x
+        x = self._draw(key)
+        self._put(key, x, x.nbytes)
+        return x
+
+    def _put(self, key, val, nbytes):
+        self._cache[key] = val
+        self._sizes[key] = nbytes
+        self._bytes += nbytes
+        while self._bytes > self._budget and len(self._cache) > 1:
+            k, _ = self._cache.popitem(last=False)
+            self._bytes -= self._sizes.pop(k)
+
+    def _read_ahead(self, key):
+        """A reader that walks the tensors in their listed order (a forward pass does) finds the next few already
+        being drawn on threads."""
+        if self._readahead <= 0 or key not in self._order:
+            return
+        if self._pool is None:
+            from concurrent.futures import ThreadPoolExecutor
+            self._pool = ThreadPoolExecutor(max_workers=self._readahead)
+        i = self._order[key]
+        for nxt in self._names[i + 1:i + 1 + self._readahead]:
+            if nxt not in self._cache:
+                self._put(nxt, self._pool.submit(self._draw, nxt), self._nbytes(nxt))
+
+    def _nbytes(self, key):
+        return self._numel.get(key, 0) * (8 if self._f64 else 4)
+
+    def view(self, as_f64: bool, budget_bytes: int | None = None, readahead: int = 0) -> "LazyWeights":
+        """The same tensors through a cache of its own (e.g. float64 for the oracle beside float32 for the upload)."""
+        return LazyWeights(self._rec, self._alias, self._budget if budget_bytes is None else budget_bytes, as_f64,
+                           self._prefetch, readahead, self._numel)
+
+    def items(self):
+        from concurrent.futures import ThreadPoolExecutor
+        names = self.keys()
+        with ThreadPoolExecutor(max_workers=self._prefetch) as ex:
+            pending = []
+            it = iter(names)
+            for n in it:
+                pending.append((n, ex.submit(self._draw, n)))
+                if len(pending) >= self._prefetch:
+                    break
+            while pending:
+                n, fut = pending.pop(0)
+                nxt = next(it, None)
+                if nxt is not None:
+                    pending.append((nxt, ex.submit(self._draw, nxt)))
+                yield n, fut.result()
+
+
 def tf_weights(c: TfCfg, seed: int, prefix: str, dtype: int, w_std=0.02, affine=False,
-               std_overrides=None, deep_from=None, deep_gain=1.0) -> dict:
+               std_overrides=None, deep_from=None, deep_gain=1.0, recipes_only=False) -> dict:
     """deep_from / deep_gain: the output projections (wo, w2 / wd) of layers >= deep_from are drawn
     with std w_std * deep_gain.  With deep_from = L_draft this makes the deep layers refinements of
     the shallow ones, so that a draft made of the first L_draft layers predicts the target's feature
@@ -148,22 +267,23 @@ def tf_weights(c: TfCfg, seed: int, prefix: str, dtype: int, w_std=0.02, affine=
         for l in range(deep_from, c.n_layers):
             for nm in ("wo", "w2", "wd"):
                 ov[f"L{l}.{nm}"] = w_std * deep_gain
-    return _draw_weights(tf_weight_shapes(c), seed, prefix, dtype, w_std, affine, std_overrides=ov)
+    rec = _weight_recipes(tf_weight_shapes(c), seed, prefix, dtype, w_std, affine, std_overrides=ov)
+    return rec if recipes_only else _draw_all(rec)
 
 
 def head_weights(h: HeadCfg, seed: int, dtype: int, w_std=0.02, affine=False,
-                 std_overrides=None) -> dict:
-    return _draw_weights(head_weight_shapes(h), seed, "head", dtype, w_std, affine,
-                         std_overrides=std_overrides)
+                 std_overrides=None, recipes_only=False) -> dict:
+    rec = _weight_recipes(head_weight_shapes(h), seed, "head", dtype, w_std, affine, std_overrides=std_overrides)
+    return rec if recipes_only else _draw_all(rec)
 
 
-def truncated_draft(target_w: dict, tc: TfCfg, dc: TfCfg) -> dict:
+def truncated_draft(target_w: dict, tc: TfCfg, dc: TfCfg, names_only=False) -> dict:
     """Draft = the target's embeddings, its first L_d layers and its final norm
-    (a draft 'initialised with the target').  Needs equal widths."""
+    (a draft 'initialised with the target').  Needs equal widths.  names_only: draft name -> target name."""
     assert (tc.d_model, tc.n_heads, tc.n_kv_heads, tc.d_ff) == (dc.d_model, dc.n_heads, dc.n_kv_heads, dc.d_ff)
     out = {}
     for name in tf_weight_shapes(dc):
-        out["draft." + name] = target_w["target." + name]
+        out["draft." + name] = "target." + name if names_only else target_w["target." + name]
     return out
 
 

@@ -24,8 +24,13 @@ def _pack(xs):
 
 @pytest.mark.parametrize("kind", ["ln-gelu-bf16", "gqa-rope-bf16", "ln-gelu-f32", "mid-bf16"])
 @pytest.mark.parametrize("which", [0, 1])
-def test_forward_matches_oracle_with_ragged_rows(kind, which):
-    case = build_case(kind, seed=21, peaky=True)
+@pytest.mark.parametrize("peaky", [False, True])
+def test_forward_matches_oracle_with_ragged_rows(kind, which, peaky):
+    """peaky=False: the workload recipe (weights N(0, 0.02)); the attention-row entropy of layer l_s is held to the
+    stated 1e-3.  peaky=True: a stress variant outside the recipe (QKV weights scaled until the scores have a standard
+    deviation near 2, so that a wrong mask or K/Q layout shows as an error of order 1); there the bf16 rounding of q
+    and k alone moves a row's entropy by up to 1e-2, and the entropy bar is 2e-2."""
+    case = build_case(kind, seed=21, peaky=peaky)
     rc = case.rc
     ctx = make_ctx(case)
     B, K, D = case.B, rc.K, rc.target.d_latent
@@ -46,8 +51,7 @@ def test_forward_matches_oracle_with_ragged_rows(kind, which):
     print(f"z {ez:.2e} shallow {es:.2e} h_attn {eh:.2e} (H range {hao.min():.2f}..{hao.max():.2f})")
     assert ez < tol
     assert es < tol
-    # attention-row entropies inherit the bf16 rounding of q and k: looser than the feature-mode bar
-    assert eh < (2e-2 if rc.dtype == DT_BF16 else 1e-4)
+    assert eh < (1e-4 if rc.dtype == DT_F32 else (2e-2 if peaky else 1e-3))
     # commit=False leaves lengths alone
     assert np.array_equal(ctx.spec_kv_lengths(which, B), np.full(B, case.n_ctx))
     ctx.close()

@@ -13,20 +13,12 @@ pytestmark = pytest.mark.gpu
 TOL = {DT_BF16: 2e-2, DT_F32: 2e-4}
 
 
-def _compare_round(case, g, o, tau, samples=None, chain=False):
+def _compare_round(case, g, o, tau, samples=None):
     """Element-wise comparison; decisions are compared where they are not within the stated
-    distance of their threshold (entropy 1e-3 of tau; ln r within 1e-3*max(1,|ln rho|) of ln rho).
-
-    chain=True (full-size configs[2] / [4] only): the K draft steps are a dependent chain -- the latent of step i
-    is the input of step i+1 and enters the draft cache -- so the per-step bf16 error accumulates about linearly
-    (measured there: latents 0.5-0.9 % at step 0, 1.4-2.4 % at step 7; entropy 1e-4 at step 0, up to 1.5e-3 at
-    step 7).  Step i is then held to (i + 1) times the base tolerance; step 0, which has no chain behind it,
-    to the base tolerance itself."""
+    distance of their threshold (entropy 1e-3 of tau; ln r within 1e-3*max(1,|ln rho|) of ln rho)."""
     idx = list(range(case.B)) if samples is None else list(samples)
     tol = TOL[case.rc.dtype]
     K = case.rc.K
-    if chain:
-        return _compare_round_chain(case, g, o, tau, idx, tol)
     Hg, Ho = g["H"][idx], o["H"]
     # entropies of executed steps
     executed = np.zeros_like(Ho, dtype=bool)
@@ -125,12 +117,30 @@ def test_attn_mode_entropy_round():
     tau = float(np.median(o_all["H"][:, 1]))
     o = run_oracle_round(case, tau=tau)
     g = run_gpu_round(case, tau=tau)
-    # attention-row entropies come from bf16 q, k: looser than the 1e-3 of the feature mode
+    # a stress variant outside the workload recipe (scores with a standard deviation near 2): the bf16 rounding of
+    # q and k alone moves these entropies by up to 1e-2; the stated 1e-3 is held at the recipe, in
+    # test_attn_mode_entropy_at_the_workload_recipe
     executed = np.zeros_like(o["H"], dtype=bool)
     for b in range(case.B):
         executed[b, :min(int(o["n_keep"][b]) + 1, case.rc.K)] = True
     eH = float(np.abs(g["H"] - o["H"])[executed].max())
     assert eH < 2e-2
+
+
+def test_attn_mode_entropy_at_the_workload_recipe():
+    """ATTN-mode entropy (Eq. 1 / S2.1 read on the attention rows of draft layer l_s) at configs[1]'s full shape and
+    the workload recipe, held to the stated 1e-3 on every draft step (teacher-forced, so that a step is not charged
+    with the drift of the steps before it) and on the free-running first step."""
+    case = build_case(1, seed=0, affine=False)
+    case.rc.entropy_mode = ENT_ATTN
+    idx = [0, case.B - 1]
+    o = run_oracle_round(case, tau=-1.0, samples=idx)
+    assert o["H"].min() > 1.0                              # ln(130) = 4.9 for uniform rows: these are attention entropies
+    ctx = make_ctx(case)
+    free = teacher_forced_round(case, ctx, o, idx)
+    for bi, b in enumerate(idx):
+        assert abs(float(free["H"][b, 0]) - float(o["H"][bi, 0])) <= 1e-3
+    ctx.close()
 
 
 def test_two_rounds_in_a_row_reuse_the_context():
@@ -173,43 +183,157 @@ def test_config1_full_size_sampled_samples():
         assert np.array_equal(g[k], g2[k]), k
 
 
-def _compare_round_chain(case, g, o, tau, idx, tol):
-    K = case.rc.K
+def teacher_forced_round(case, ctx, o, idx, tau=-1.0, W_oracle=None):
+    """The full-size check that bounds the kernels rather than the chain: the K draft steps depend on one another
+    (the latent of step i is the input of step i + 1 and enters the draft cache), so a free-running comparison of
+    step 7 measures seven steps of accumulated bf16 rounding.  Here every draft step of the sampled samples is fed the
+    ORACLE's previous token (spec_draft_step), and spec_verify gets the oracle's drafts, draft means and survivor
+    counts; every row is then held to the flat bars (latents and means 2e-2 over the sample's tensor, entropy 1e-3
+    absolute).  The other samples of the batch run on the library's own tokens, so the launch shapes are those of the
+    benchmark.  Returns the free-running round (whose drift against the oracle is printed, not gated)."""
+    from paper_2512_08537_amd import binding
+    rc, B, K = case.rc, case.B, case.rc.K
+    tol = TOL[rc.dtype]
+    gi = gpu_inputs(ctx, case)
+    lens = np.full(B, case.n_ctx, dtype=np.int32)
+
+    def rewind():
+        ctx.spec_kv_reset(binding.TARGET, lens)
+        ctx.spec_kv_reset(binding.DRAFT, lens)
+
+    rewind()
+    free = to_np(ctx.spec_round(gi["pending"], gi["eps"], gi["r"], tau))
+    ctx.sync()
+    # --- draft steps on the oracle's tokens
+    rewind()
+    out = ctx._round_bufs(B)
+    for i in range(K):
+        x_prev = case.inp["pending"].copy() if i == 0 else free["x_draft"][:, i - 1].copy()
+        if i > 0:
+            for bi, b in enumerate(idx):
+                if i - 1 < int(o["n_keep"][bi]):
+                    x_prev[b] = o["x"][bi, i - 1]
+        ctx.spec_draft_step(i, ctx.dev_f32(x_prev), gi["eps"], tau, out)
+    ctx.sync()
+    g = to_np(out)
     for bi, b in enumerate(idx):
         nk = int(o["n_keep"][bi])
+        n_ex = min(nk + 1, K)
+        eh = np.abs(g["H"][b, :n_ex] - o["H"][bi, :n_ex])
+        drift_h = np.abs(free["H"][b, :n_ex] - o["H"][bi, :n_ex])
+        print(f"sample {b}: entropy per step (teacher-forced) {np.array2string(eh, precision=1)}  free-running {np.array2string(drift_h, precision=1)}")
+        assert eh.max() <= 1e-3
         assert int(g["n_keep"][b]) == nk
-        for i in range(min(nk + 1, K)):
-            eh = abs(float(g["H"][b, i]) - float(o["H"][bi, i]))
-            assert eh <= 1e-3 * (i + 1), (i, eh)
-        for i in range(nk):
-            ex, eq = rel_inf(g["x_draft"][b, i], o["x"][bi, i]), rel_inf(g["mu_q"][b, i], o["mu_q"][bi, i])
-            assert ex < tol * (i + 1), (i, ex)
-            assert eq < tol * (i + 1), (i, eq)
-        for j in range(nk + 1):                              # verify row j has drafts 0..j-1 behind it
-            ep = rel_inf(g["mu_p"][b, j], o["mu_p"][bi, j])
-            assert ep < tol * (j + 1), (j, ep)
-        assert not g["mu_p"][b, nk + 1:].any()
-    return np.ones(len(idx), dtype=bool)
+        if nk:
+            per = [rel_inf(g["mu_q"][b, i], o["mu_q"][bi, i]) for i in range(nk)]
+            drift = [rel_inf(free["mu_q"][b, i], o["mu_q"][bi, i]) for i in range(nk)]
+            print(f"sample {b}: mu_q per step (teacher-forced) {np.array2string(np.array(per), precision=4)}  free-running {np.array2string(np.array(drift), precision=4)}")
+            assert rel_inf(g["mu_q"][b, :nk], o["mu_q"][bi, :nk]) < tol
+            assert rel_inf(g["x_draft"][b, :nk], o["x"][bi, :nk]) < tol
+            assert max(per) < 2 * tol                      # no single step hides behind a large row of the tensor
+    # --- verify on the oracle's drafts
+    x_d, mu_q, nk_all = free["x_draft"].copy(), free["mu_q"].copy(), free["n_keep"].copy()
+    for bi, b in enumerate(idx):
+        x_d[b], mu_q[b], nk_all[b] = o["x"][bi], o["mu_q"][bi], o["n_keep"][bi]
+    rewind()
+    v = ctx.spec_verify(gi["pending"], ctx.dev_f32(x_d), ctx.dev_f32(mu_q), ctx.dev_i32(nk_all), gi["r"], gi["eps"], want_z=True)
+    ctx.sync()
+    v = to_np(v)
+    from oracle import accept as oac
+    sg = rc.head.sigma_last * rc.head.temperature
+    for bi, b in enumerate(idx):
+        nk = int(o["n_keep"][bi])
+        ep = rel_inf(v["mu_p"][b, :nk + 1], o["mu_p"][bi, :nk + 1])
+        ez = rel_inf(v["z_p"][b, :nk + 1], o["z_p"][bi])
+        per = [rel_inf(v["mu_p"][b, j], o["mu_p"][bi, j]) for j in range(nk + 1)]
+        drift = [rel_inf(free["mu_p"][b, j], o["mu_p"][bi, j]) for j in range(min(nk, int(free["n_keep"][b])) + 1)]
+        print(f"sample {b}: verify z_p {ez:.2e} mu_p {ep:.2e}; per row {np.array2string(np.array(per), precision=4)}  free-running {np.array2string(np.array(drift), precision=4)}")
+        assert ez < tol and ep < tol
+        assert max(per) < 2 * tol
+        assert not v["mu_p"][b, nk + 1:].any()
+        if nk:
+            # ln rho: exact rule on the library's own means (unit level), and against the oracle's value
+            _, lr_unit, _ = oac.accept(x_d[b:b + 1], v["mu_p"][b:b + 1], mu_q[b:b + 1], case.inp["r"][b:b + 1], nk_all[b:b + 1], 0.0, sg, sg)
+            assert np.allclose(v["log_ratio"][b, :nk], lr_unit[0, :nk], rtol=1e-3, atol=2e-3)
+            el = rel_inf(v["log_ratio"][b, :nk], o["log_ratio"][bi, :nk])
+            print(f"sample {b}: ln rho against the oracle {el:.2e}")
+            assert el < tol
+    return free
 
 
-def test_config2_full_size_sampled_sample():
+def test_config2_full_size_teacher_forced():
     """BASELINE configs[2] (L=32, d=1280, B=64: 576 verify rows, K = 1280 / 5120 GEMMs) at full size; the oracle
-    recomputes one of the 64 samples."""
+    recomputes one of the 64 samples; flat bars on every step and row (teacher_forced_round)."""
     case = build_case(2, seed=0, affine=False)
-    g = run_gpu_round(case, tau=-1.0)
     idx = [case.B - 1]
     o = run_oracle_round(case, tau=-1.0, samples=idx)
-    _compare_round(case, g, o, -1.0, samples=idx, chain=True)
-    assert np.isfinite(g["mu_p"]).all() and np.isfinite(g["log_ratio"]).all()
+    ctx = make_ctx(case)
+    free = teacher_forced_round(case, ctx, o, idx)
+    # the free-running round itself: its first step and first verify row have no chain behind them
+    for bi, b in enumerate(idx):
+        assert abs(float(free["H"][b, 0]) - float(o["H"][bi, 0])) <= 1e-3
+        assert rel_inf(free["mu_q"][b, 0], o["mu_q"][bi, 0]) < 2e-2
+        assert rel_inf(free["mu_p"][b, 0], o["mu_p"][bi, 0]) < 2e-2
+    assert np.isfinite(free["mu_p"]).all() and np.isfinite(free["log_ratio"]).all()
+    ctx.close()
 
 
-def test_config4_full_size_sampled_sample():
+def test_config4_full_size_teacher_forced():
     """BASELINE configs[4] shape (configs[2] model, B=256, n_ctx=1024: 2304 verify rows, 33 key blocks per head) at
     full size, one synthetic cache shared by all layers (44 GB of distinct cache would not fit the host); the
-    oracle recomputes one sample."""
+    oracle recomputes two samples; flat bars on every step and row."""
     case = build_case(4, seed=0, affine=False, cache_layers_shared=True)
-    g = run_gpu_round(case, tau=-1.0)
     idx = [0, case.B // 2]
     o = run_oracle_round(case, tau=-1.0, samples=idx)
-    _compare_round(case, g, o, -1.0, samples=idx, chain=True)
-    assert np.isfinite(g["mu_p"]).all() and np.isfinite(g["log_ratio"]).all()
+    ctx = make_ctx(case)
+    free = teacher_forced_round(case, ctx, o, idx)
+    for bi, b in enumerate(idx):
+        assert abs(float(free["H"][b, 0]) - float(o["H"][bi, 0])) <= 1e-3
+        assert rel_inf(free["mu_q"][b, 0], o["mu_q"][bi, 0]) < 2e-2
+        assert rel_inf(free["mu_p"][b, 0], o["mu_p"][bi, 0]) < 2e-2
+    assert np.isfinite(free["mu_p"]).all() and np.isfinite(free["log_ratio"]).all()
+    ctx.close()
+
+
+def test_config0_full_round_fp32():
+    """BASELINE configs[0] at its own shape (4 layers, d = 256, 4 heads, MLP 1024, 1-layer draft, K = 4, batch 1,
+    64 cached tokens, 3-block head, one step, fp32): the whole batch, every output, at the fp32 bar; the cache is
+    built by the library's own prefill of 64 latents, as that configuration says."""
+    from oracle import transformer as tf
+    from oracle import round as rnd
+    from paper_2512_08537_amd import binding
+    case = build_case(0, seed=0, affine=False)
+    rc = case.rc
+    assert (rc.target.n_layers, rc.target.d_model, rc.K, case.B, case.n_ctx, rc.dtype) == (4, 256, 4, 1, 64, DT_F32)
+    ctx = make_ctx(case)
+    rng = np.random.default_rng(0)
+    x = rng.normal(size=(1, 64, rc.target.d_latent)).astype(np.float32)
+    n = np.array([64], np.int32)
+    tc, dc = tf.KVCache(rc.target, 1), tf.KVCache(rc.draft, 1)
+    for which, cfg, prefix, cache in ((binding.TARGET, rc.target, "target", tc), (binding.DRAFT, rc.draft, "draft", dc)):
+        ctx.spec_kv_reset(which, None)
+        ctx.spec_prefill(which, ctx.dev_f32(x), n)
+        tf.forward_sample(cfg, case.W, prefix, cache, 0, x[0], commit=True)
+    for tau in (-1.0, None):
+        if tau is None:                                    # the paper's threshold rule on this round's entropies
+            tau = float(binding.entropy_threshold(float(o["H"].mean()), float(o["H"].std())))
+            tc.truncate(0, 64), dc.truncate(0, 64)
+            ctx.spec_kv_reset(binding.TARGET, n), ctx.spec_kv_reset(binding.DRAFT, n)
+        o = rnd.spec_round(rc, case.W, tc, dc, case.inp["pending"], case.inp["eps_draft"], case.inp["r"], tau, 1)
+        gi = gpu_inputs(ctx, case)
+        g = to_np(ctx.spec_round(gi["pending"], gi["eps"], gi["r"], tau))
+        ctx.sync()
+        nk = int(o["n_keep"][0])
+        assert int(g["n_keep"][0]) == nk == rc.K
+        assert np.abs(g["H"] - o["H"]).max() <= 1e-3
+        for k_g, k_o in (("x_draft", "x"), ("mu_q", "mu_q"), ("mu_p", "mu_p")):
+            e = rel_inf(g[k_g], o[k_o])
+            print(f"configs[0] tau {tau:.3f}: {k_g} {e:.2e}")
+            assert e < TOL[DT_F32]
+        assert rel_inf(g["log_ratio"], o["log_ratio"]) < 2e-3
+        with np.errstate(divide="ignore"):
+            margin = np.abs(o["log_ratio"] - np.log(case.inp["r"].astype(np.float64)))
+        if (margin > 1e-3 * np.maximum(1.0, np.abs(o["log_ratio"]))).all():
+            assert np.array_equal(g["n_accept"], o["n_accept"])
+        assert np.array_equal(ctx.spec_kv_lengths(binding.TARGET, 1), [64 + 1 + int(g["n_accept"][0])])
+    ctx.close()
