@@ -257,6 +257,9 @@ struct fard_ctx {
   int* g_cu_nq = nullptr;
   uint8_t* g_keep = nullptr;
   // deferred residual update: K-slice partial sums of the last down-projection, folded in by the next norm
+  // keys of one (sample, kv head) split over several attention workgroups: their partial results (see AttnSplit)
+  float *attn_o = nullptr, *attn_mla = nullptr;
+  int attn_rows = 0;
   float* parts = nullptr;
   size_t parts_cap = 0;                    // floats that parts holds
   int pend_n = 0;
@@ -654,8 +657,9 @@ int load_head(fard_ctx* c, Loader& ld) {
 }
 
 constexpr int GEN_J_MAX = 64;            // resampling tries that the staged (graph) generation path holds
-constexpr int PART_MAX_SLICES = 8;      // K slices of a deferred residual update
+constexpr int PART_MAX_SLICES = 16;     // K slices of a deferred residual update
 constexpr int PART_MAX_ROWS = 640;
+constexpr int ATTN_MAX_SPLIT = 8;        // attention workgroups per (sample, kv head) at most
 
 int cap_nq(const fard_ctx* c, int which);
 
@@ -731,6 +735,15 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<int>(c, &c->s_nk, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->s_na, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->s_tr, g.max_batch))) return rc;
+  // split-key attention: only contexts whose full batch leaves most of the chip idle (samples x kv heads < 256)
+  if (c->bf16) {
+    int hk_min = std::min(c->mdl[0].c.n_kv_heads, c->mdl[1].c.n_kv_heads), dh_max = std::max(c->mdl[0].c.d_head, c->mdl[1].c.d_head);
+    if ((long)g.max_batch * hk_min < 256) {
+      c->attn_rows = M;
+      if ((rc = dalloc<float>(c, &c->attn_o, (size_t)ATTN_MAX_SPLIT * M * hmax * dh_max))) return rc;
+      if ((rc = dalloc<float>(c, &c->attn_mla, (size_t)ATTN_MAX_SPLIT * M * hmax * 4))) return rc;
+    }
+  }
   // planes for any forward the workspace admits (a prefill pass has more rows than a round), up to the row limit
   if (c->bf16) {
     c->parts_cap = (size_t)PART_MAX_SLICES * std::min(std::max(M, MR), PART_MAX_ROWS) * dmax;
@@ -750,29 +763,62 @@ KvGeom kv_geom(fard_ctx* c, Model& m, int layer) {
   return g;
 }
 
+// GEMMs of 65 to 128 rows against tens of MB of weights (the verify stage of the 5120-wide configuration: 72 rows,
+// 52-283 MB per matrix): K is split over workgroups of the streaming kernel on 128-column tiles and every split writes
+// its own plane; the kernel that follows (RoPE + cache append, the next norm) sums the planes.  Returns the number of
+// planes, 0 when the shape does not call for it.  Measured at 72 rows: QKV 7168 x 5120 35 -> 25 us, output projection
+// 26.5 -> 20.6 us, down-projection 49.5 -> 39 us.
+int plane_splits(const fard_ctx* c, int M, int N, int K) {
+  if (!c->bf16 || c->parts == nullptr || M <= 64 || M > 128 || K % 256 != 0 || N % 32 != 0) return 0;
+  if ((size_t)K * N * 2 < ((size_t)16 << 20)) return 0;
+  const int tiles = (N + 127) / 128;
+  if (tiles >= 200) return 0;                              // the column tiles alone cover the chip
+  int want = (200 + tiles - 1) / tiles;
+  want = std::min(want, std::min(PART_MAX_SLICES, K / 256));
+  const int n = gemm_plane_count(K, want);
+  if (n < 2 || (size_t)n * M * N > c->parts_cap) return 0;
+  return n;
+}
+
 // The down-projection with a long K and a few hundred rows at most: K slices of 1024 as separate workgroups of
 // the narrow kernel, each writing its partial sums to its own plane; no atomics.  The planes stay pending until
 // the next norm (or flush_parts) adds them to the residual stream.
 bool parts_eligible(const fard_ctx* c, int M, int N, int K) {
-  return c->bf16 && c->parts != nullptr && M <= PART_MAX_ROWS && K > 2048 && (K + 1023) / 1024 <= PART_MAX_SLICES && N <= 8192 &&
+  if (plane_splits(c, M, N, K) > 0) return true;
+  return c->bf16 && c->parts != nullptr && M <= PART_MAX_ROWS && K > 2048 && (K + 1023) / 1024 <= 8 && N <= 8192 &&
          N % 32 == 0 && K % 64 == 0 && (size_t)((K + 1023) / 1024) * M * N <= c->parts_cap;
 }
 
-hipError_t gemm_parts(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
-                      const int* m_dev) {
+// out planes <- A W (+ bias in plane 0); *n_planes and *stride describe them.  The planes are c->parts.
+hipError_t gemm_planes(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
+                       const int* m_dev, int* n_planes, size_t* stride) {
   GemmArgs a;
   a.A = A; a.lda = lda; a.W = W; a.bias = bias; a.out = c->parts; a.ldo = N; a.gate = nullptr; a.ldg = 0;
   a.M = M; a.N = N; a.K = K; a.m_dev = m_dev; a.act = ACT_NONE; a.epi = EPI_PARTIAL;
-  a.k_slices = (K + 1023) / 1024;
+  const int wide = plane_splits(c, M, N, K);
+  a.k_slices = wide > 0 ? wide : (K + 1023) / 1024;
   a.part_stride = (size_t)M * N;
   if ((size_t)a.k_slices * a.part_stride > c->parts_cap) return hipErrorInvalidValue;   // never launch past the planes
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * N * 4;
   Bracket br(c, CLS_GEMM, fl, by);
-  hipError_t e = launch_gemm_narrow(c->stream, a);
+  hipError_t e = wide > 0 ? launch_gemm_bf16_planes(c->stream, a) : launch_gemm_narrow(c->stream, a);
   if (e == hipSuccess) {
-    c->pend_n = a.k_slices;
-    c->pend_stride = a.part_stride;
+    *n_planes = a.k_slices;
+    *stride = a.part_stride;
+  }
+  return e;
+}
+
+// A residual update left as pending planes: the next norm adds them to the stream.
+hipError_t gemm_parts(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
+                      const int* m_dev) {
+  int n = 0;
+  size_t stride = 0;
+  hipError_t e = gemm_planes(c, A, lda, W, bias, M, N, K, m_dev, &n, &stride);
+  if (e == hipSuccess) {
+    c->pend_n = n;
+    c->pend_stride = stride;
   }
   return e;
 }
@@ -801,20 +847,39 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
                             c->parts, c->pend_n, c->pend_stride, c->h));
       c->pend_n = 0;
     }
-    HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
     KvGeom kg = kv_geom(c, m, l);
     // learned positions, bf16: the attention kernel stores the new K / V rows itself
     const bool fused_append = c->bf16 && t.pos != FARD_POS_ROPE;
-    if (!fused_append) {
+    if (!fused_append && c->bf16 && plane_splits(c, M, QN, d) > 0) {
+      // the QKV product as K-slice planes, summed by the kernel that rotates q, k and appends k, v to the cache
+      int n_pl = 0;
+      size_t pl_stride = 0;
+      HIPCHK(c, gemm_planes(c, c->u, d, L.wqkv, L.bqkv, M, QN, d, m_dev, &n_pl, &pl_stride));
       Bracket br(c, CLS_OTHER);
-      HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE, t.rope_theta, c->maps.row_sample,
-                                   c->maps.row_pos, M, m_dev));
+      HIPCHK(c, launch_rope_append_planes(s, c->parts, n_pl, pl_stride, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE,
+                                          t.rope_theta, c->maps.row_sample, c->maps.row_pos, M, m_dev));
+    } else {
+      HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
+      if (!fused_append) {
+        Bracket br(c, CLS_OTHER);
+        HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE, t.rope_theta, c->maps.row_sample,
+                                     c->maps.row_pos, M, m_dev));
+      }
     }
     const int acap = cap_nq(c, which);
     if (nq_max <= acap) {
+      // few samples x kv heads against a long cache: the key blocks of each are dealt to several workgroups (the
+      // count depends on the batch and the cache capacity only, so that every call of a shape takes the same path)
+      AttnSplit sp{};
+      const int pairs = B * t.n_kv_heads;
+      if (c->attn_o != nullptr && !fused_append && pairs < 256 && M <= c->attn_rows) {
+        const int n = std::min(std::min(ATTN_MAX_SPLIT, 256 / pairs), (c->cfg.max_ctx + 31) / 32 / 2);
+        if (n >= 2) { sp.n = n; sp.rows = c->attn_rows; sp.o = c->attn_o; sp.mla = c->attn_mla; }
+      }
       Bracket br(c, CLS_ATTN);
       HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, m.len, c->maps.row_start, B, nq_max, c->ao, HD,
-                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0));
+                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0, nullptr, 1,
+                                 sp.n > 1 ? &sp : nullptr, M, m_dev));
     } else {
       // more rows per sample than one attention workgroup holds: passes of acap rows (c->ap_* hold their row ranges
       // and first positions), all in one launch once every row's K / V is in the cache
@@ -839,9 +904,13 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
       ex_1.ln_cs = L.cs1; ex_1.ln_eps = t.norm_eps; ex_1.ln_rms = t.norm == FARD_NORM_RMS;
       HIPCHK(c, gemm(c, c->u, d, L.w1f, L.b1f, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU, nullptr, 0, &ex_1));
     } else {
-      HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
+      // (the output projection of the wide 72-row layers also leaves planes, which the second norm adds to the stream)
+      if (plane_splits(c, M, d, HD) > 0) HIPCHK(c, gemm_parts(c, c->ao, HD, L.wo, L.bo, M, d, HD, m_dev));
+      else HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
       { Bracket br(c, CLS_OTHER);
-        HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u)); }
+        HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u,
+                              c->parts, c->pend_n, c->pend_stride, c->h));
+        c->pend_n = 0; }
       if (t.act == FARD_ACT_GELU) {
         HIPCHK(c, gemm(c, c->u, d, L.w1, L.b1, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU));
       } else {

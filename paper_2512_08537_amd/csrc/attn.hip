@@ -19,6 +19,8 @@
 // fp32 path: one wave per (row, head), scores staged in LDS; for the small fp32 configuration.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace fard {
 
 namespace {
@@ -28,7 +30,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
                                                         const int* __restrict__ cache_len,
                                                         const int* __restrict__ row_start, const int* __restrict__ row_cnt,
                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads,
-                                                        int append, int pass_stride) {
+                                                        int append, int pass_stride, AttnSplit sp) {
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
@@ -116,7 +118,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
       __threadfence_block();
       __syncthreads();
     }
-    const int kb_lo = (phase == 0) ? 0 : tail0, kb_hi = (phase == 0) ? tail0 : n_blocks;
+      int kb_lo = (phase == 0) ? 0 : tail0, kb_hi = (phase == 0) ? tail0 : n_blocks;
+    if (sp.n > 1) {                                        // this workgroup's share of the key blocks (append == 0)
+      kb_lo = (int)(((long)n_blocks * blockIdx.z) / sp.n);
+      kb_hi = (int)(((long)n_blocks * (blockIdx.z + 1)) / sp.n);
+    }
   for (int kb = kb_lo + wave; kb < kb_hi; kb += 4) {
     const bf16x8* kblk = (const bf16x8*)(Kb + (size_t)kb * 32 * DH);
     const bf16x8* vblk = (const bf16x8*)(Vb + (size_t)kb * 32 * DH);
@@ -256,9 +262,28 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
       lstar += f * s_l[w][c];
       astar += f * (s_a[w][c] + dl * s_l[w][c]);
     }
-    const float inv = 1.0f / lstar;
     const int gq = c / nq, j = c - gq * nq;
     const int head = hk * G + gq;
+    if (sp.n > 1) {
+      // keys split over workgroups: this one's running triple and unnormalised O row (relative to its own maximum)
+      // go to the planes that attn_merge_kernel folds
+      const size_t slot = ((size_t)blockIdx.z * sp.rows + (r0 + j)) * n_heads + head;
+      f32x4 lo, hi;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float acc = s_o[(d8 * 8 + i) * OLD + c];
+        if constexpr (SLABS) {
+#pragma unroll
+          for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
+        }
+        if (i < 4) lo[i] = acc; else hi[i - 4] = acc;
+      }
+      *(f32x4*)(sp.o + slot * DH + d8 * 8) = lo;
+      *(f32x4*)(sp.o + slot * DH + d8 * 8 + 4) = hi;
+      if (d8 == 0) *(f32x4*)(sp.mla + slot * 4) = f32x4{mstar, lstar, astar, 0.f};
+      continue;
+    }
+    const float inv = 1.0f / lstar;
     bf16x8 v;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -271,6 +296,42 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__
     }
     *(bf16x8*)(out + (size_t)(r0 + j) * ldo + (size_t)head * DH + d8 * 8) = v;
     if (ent_heads != nullptr && d8 == 0) ent_heads[(size_t)(r0 + j) * n_heads + head] = logf(lstar) - astar * inv;
+  }
+}
+
+// Folds the per-split results of attn_bf16_kernel: thread -> (row, head, 8 dims).
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnSplit sp, int n_heads, int dh, int M, const int* __restrict__ m_dev,
+                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads) {
+  const int Me = eff_rows(M, m_dev);
+  const int d8n = dh >> 3;
+  const long total = (long)Me * n_heads * d8n;
+  for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
+    const int d8 = (int)(idx % d8n);
+    const long rh = idx / d8n;                             // row * n_heads + head
+    float mstar = -INFINITY;
+    for (int s = 0; s < sp.n; ++s) mstar = fmaxf(mstar, sp.mla[((size_t)s * sp.rows * n_heads + rh) * 4]);
+    float lstar = 0.f, astar = 0.f;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int s = 0; s < sp.n; ++s) {
+      const size_t slot = (size_t)s * sp.rows * n_heads + rh;
+      const f32x4 t = *(const f32x4*)(sp.mla + slot * 4);
+      if (t[0] == -INFINITY) continue;                     // a split that saw no visible key
+      const float dl = t[0] - mstar, f = __expf(dl);
+      lstar += f * t[1];
+      astar += f * (t[2] + dl * t[1]);
+      const f32x4 lo = *(const f32x4*)(sp.o + slot * dh + d8 * 8), hi = *(const f32x4*)(sp.o + slot * dh + d8 * 8 + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { acc[i] += f * lo[i]; acc[4 + i] += f * hi[i]; }
+    }
+    const float inv = 1.0f / lstar;
+    const int row = (int)(rh / n_heads), head = (int)(rh - (long)row * n_heads);
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (bf16)(acc[i] * inv);
+    *(bf16x8*)(out + (size_t)row * ldo + (size_t)head * dh + d8 * 8) = v;
+    if (ent_heads != nullptr && d8 == 0) ent_heads[rh] = logf(lstar) - astar * inv;
   }
 }
 
@@ -329,7 +390,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv, const int* cache_len,
                             const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads, int append,
-                            const int* row_cnt, int n_pass) {
+                            const int* row_cnt, int n_pass, const AttnSplit* split, int M, const int* m_dev) {
   if (B <= 0 || nq_max <= 0 || n_pass <= 0) return hipSuccess;
   // several passes at once read rows that an earlier pass of the same launch would have had to store
   if (n_pass > 1 && (append || row_cnt == nullptr || n_pass > 65535 || (long)B * n_pass > 65535)) return hipErrorInvalidValue;
@@ -345,22 +406,33 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
   const int G = n_heads / kv.n_kv_heads;
   const int cols = G * nq_max;
   if (cols > 64 || n_heads % kv.n_kv_heads != 0) return hipErrorInvalidValue;
-  const dim3 grid(B * kv.n_kv_heads, n_pass);
+  AttnSplit sp{};
+  sp.n = 1;
+  if (split != nullptr && split->n > 1) {
+    if (append || n_pass != 1 || split->o == nullptr || split->mla == nullptr || M > split->rows || M < 1) return hipErrorInvalidValue;
+    sp = *split;
+  }
+  const dim3 grid(B * kv.n_kv_heads, n_pass, sp.n);
   const int ps = B;
   const bf16* q = (const bf16*)qkv;
   bf16* o = (bf16*)out;
+  float* eh = sp.n > 1 ? nullptr : ent_heads;              // with split keys the merge writes the entropies
+#define FARD_ATT(DHV, NQBV) attn_bf16_kernel<DHV, NQBV><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, eh, append, ps, sp)
   if (kv.d_head == 64) {
-    if (cols <= 32) attn_bf16_kernel<64, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
-    else attn_bf16_kernel<64, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
+    if (cols <= 32) FARD_ATT(64, 1); else FARD_ATT(64, 2);
   } else if (kv.d_head == 128) {
-    if (cols <= 32) attn_bf16_kernel<128, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
-    else attn_bf16_kernel<128, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
+    if (cols <= 32) FARD_ATT(128, 1); else FARD_ATT(128, 2);
   } else if (kv.d_head == 32) {
-    if (cols <= 32) attn_bf16_kernel<32, 1><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
-    else attn_bf16_kernel<32, 2><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, ent_heads, append, ps);
+    if (cols <= 32) FARD_ATT(32, 1); else FARD_ATT(32, 2);
   } else {
     return hipErrorInvalidValue;
   }
+#undef FARD_ATT
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || sp.n <= 1) return e;
+  const long total = (long)M * n_heads * (kv.d_head / 8);
+  const unsigned blocks = (unsigned)std::min<long>((total + 255) / 256, 2048);
+  attn_merge_kernel<<<blocks, 256, 0, s>>>(sp, n_heads, kv.d_head, M, m_dev, o, ldo, ent_heads);
   return hipGetLastError();
 }
 

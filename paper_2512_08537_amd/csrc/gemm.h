@@ -11,7 +11,8 @@ enum Epi {
   EPI_RESID = 2,       // out_f32[m, n] += acc + bias[n]                    (residual stream update)
   EPI_GATE_RESID = 3,  // out_f32[m, n] += gate[m, n] * (acc + bias[n])
   EPI_SWIGLU = 4,      // out_T[m, j]   = silu(acc[m, gate col j]) * acc[m, up col j]  (interleaved columns)
-  EPI_PARTIAL = 5,     // out_f32[z][m, n] = partial sum of K slice z (+ bias[n] in slice 0); narrow kernel only:
+  EPI_PARTIAL = 5,     // out_f32[z][m, n] = partial sum of K slice z (+ bias[n] in slice 0); narrow kernel, or the streaming
+                       // kernel through launch_gemm_bf16_planes:
                        // the consumer (the next norm) adds the k_slices planes to the residual stream
 };
 
@@ -45,6 +46,14 @@ inline size_t packed_elems(int K, int N) { return (size_t)K * (size_t)N; }
 // Returns hipSuccess or the launch error.  K % 64 == 0 and N % 32 == 0 are required (bf16 path).
 hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a);
 hipError_t launch_gemm_f32(hipStream_t s, const GemmArgs& a);
+
+// K split over workgroups of the streaming kernel, every split writing its partial sums to its own fp32 plane
+// (a.epi == EPI_PARTIAL, plane z at out + z * part_stride, bias in plane 0; no atomics): for GEMMs of up to 128 rows
+// against tens of MB of weights, where the column tiles alone are too few workgroups to stream the weights and wider
+// tiles are needed so that the activation panel is not re-read once per 32 columns.  a.k_slices must be
+// gemm_plane_count(K, wanted): the number of planes actually written for a wanted split count.
+int gemm_plane_count(int K, int splits);
+hipError_t launch_gemm_bf16_planes(hipStream_t s, const GemmArgs& a);
 
 // Narrow-tile GEMM: one workgroup per 16 columns and 16-64 rows, no K split (no atomics; EPI_RESID and
 // EPI_GATE_RESID read-modify-write their tile), bf16 A.  Meant for M <= 64, or a few hundred rows when K

@@ -27,7 +27,7 @@ namespace {
 // Register e of a 32x32 accumulator holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
 template <int KIND, bool FULL, int WM, int WN>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN], int m0, int M, int nb0, int nblocks,
-                                         int cl, int rhalf, bool add_bias, bool atomic) {
+                                         int cl, int rhalf, bool add_bias, bool atomic, int sp) {
   if constexpr (KIND == EPI_SWIGLU) {
     if constexpr (WN == 2) {
       if (nb0 + 1 >= nblocks) return;
@@ -60,6 +60,8 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN
             ((bf16*)a.out)[o] = (bf16)apply_act(v, a.act);
           } else if constexpr (KIND == EPI_STORE_F32) {
             ((float*)a.out)[o] = apply_act(v, a.act);
+          } else if constexpr (KIND == EPI_PARTIAL) {
+            ((float*)a.out)[(size_t)sp * a.part_stride + o] = v;   // the K split's own plane: no atomics
           } else {
             if constexpr (KIND == EPI_GATE_RESID) v *= a.gate[(size_t)row * a.ldg + col];
             float* dst = (float*)a.out + o;
@@ -185,28 +187,37 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
   for (int p = 0; p < P; ++p) load_b(p, p);
 
   const int q_total = n_chunks * SPW;
+  // The activation fragments of step g + 1 are read from LDS while the MFMAs of step g run (two sets of registers), and
+  // every step ends with a scheduling barrier: without it the compiler gathers the ring's refills of a whole group of
+  // steps at the group's start and waits for all of them at its end, so that the memory pipe runs empty once per group.
+  bf16x8 af[2][WM];
+  auto read_af = [&](int ks, int slot) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+      af[slot][i] = *(const bf16x8*)(&lds[(32 * i + (lane & 31)) * LDS_STRIDE + ks * 16 + (lane >> 5) * 8]);
+  };
+  static_assert(SPW % 2 == 0 && G % 2 == 0, "fragment sets alternate by step parity");
   for (int q0 = 0; q0 < q_total; q0 += G) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const int q = q0 + g;
+      const int ks = kw * SPW + (g % SPW);                 // k-step inside the chunk
       if (g % SPW == 0) {                                  // chunk boundary (static position)
         const int c = q / SPW;
         if (c > 0) __syncthreads();                        // every wave is done reading the previous chunk
         store_a();
         __syncthreads();
         load_a(c + 1);                                     // prefetch; zeros past the last chunk
+        read_af(ks, g & 1);
       }
-      const int ks = kw * SPW + (g % SPW);                 // k-step inside the chunk
-      bf16x8 af[WM];
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-        af[i] = *(const bf16x8*)(&lds[(32 * i + (lane & 31)) * LDS_STRIDE + ks * 16 + (lane >> 5) * 8]);
+      if ((g + 1) % SPW != 0) read_af(ks + 1, (g + 1) & 1);
 #pragma unroll
       for (int j = 0; j < WN; ++j)
 #pragma unroll
         for (int i = 0; i < WM; ++i)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], breg[g % P][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[g & 1][i], breg[g % P][j], acc[i][j], 0, 0, 0);
       load_b(q + P, g % P);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
@@ -238,12 +249,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
 
   // epilogue, specialised on (kind, whole tile inside M) so that the executed path is straight-line
   const bool full = (m0 + BM <= M);
-  const bool atomic = splits > 1;
+  const bool atomic = splits > 1 && a.epi != EPI_PARTIAL;
   const int cl = lane & 31, rhalf = (lane >> 5) * 4;
 #define FARD_EPI(KIND)                                                                              \
   do {                                                                                              \
-    if (full) epilogue<KIND, true, WM, WN>(a, acc, m0, M, nb0, nblocks, cl, rhalf, sp == 0, atomic); \
-    else epilogue<KIND, false, WM, WN>(a, acc, m0, M, nb0, nblocks, cl, rhalf, sp == 0, atomic);     \
+    if (full) epilogue<KIND, true, WM, WN>(a, acc, m0, M, nb0, nblocks, cl, rhalf, sp == 0, atomic, sp); \
+    else epilogue<KIND, false, WM, WN>(a, acc, m0, M, nb0, nblocks, cl, rhalf, sp == 0, atomic, sp);     \
   } while (0)
   switch (a.epi) {
     case EPI_STORE: FARD_EPI(EPI_STORE); break;
@@ -251,6 +262,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
     case EPI_RESID: FARD_EPI(EPI_RESID); break;
     case EPI_GATE_RESID: FARD_EPI(EPI_GATE_RESID); break;
     case EPI_SWIGLU: FARD_EPI(EPI_SWIGLU); break;
+    case EPI_PARTIAL: FARD_EPI(EPI_PARTIAL); break;
     default: break;
   }
 #undef FARD_EPI
@@ -560,6 +572,10 @@ hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
       const int m64 = (a.M + 63) / 64, m96 = (a.M + 95) / 96;
       if (m64 * 64 < m96 * 96 || m96 * ((a.N + 127) / 128) < 256) return launch_cfg<2, 1, 1, 16, 256>(s, a, 1);
     }
+    // 65-96 rows with a SwiGLU epilogue: one 96-row tile of the streaming kernel, two waves per 64 packed columns sharing
+    // the k-steps (measured at 72 x 27648 x 5120: 62 us against 78 us for two 64-row tiles of the resident-activation
+    // kernel, which stream every weight panel twice)
+    if (a.epi == EPI_SWIGLU && a.M > 64 && a.M <= 96) return launch_cfg<3, 2, 2, 16, 256>(s, a, 1);
     // up to 96 rows, or a SwiGLU epilogue: the resident-activation kernel on 64-row tiles, sized so that the
     // grid stays within one workgroup per CU
     if (!resid && (a.M <= 96 || a.epi == EPI_SWIGLU) && a.M <= 640 && a.K % 256 == 0) {
@@ -656,6 +672,27 @@ hipError_t launch_gemm_bf16(hipStream_t s, const GemmArgs& a) {
   // workgroups on, - 13-37 % below)
   if ((long)((a.N + 255) / 256) * ((a.M + 127) / 128) >= 900) return launch_wm<4>(s, a);
   return launch_wm<3>(s, a);
+}
+
+int gemm_plane_count(int K, int splits) {
+  const int total_chunks = (K + 255) / 256;
+  if (splits > total_chunks) splits = total_chunks;
+  if (splits < 1) splits = 1;
+  const int cps = (total_chunks + splits - 1) / splits;
+  return (total_chunks + cps - 1) / cps;
+}
+
+hipError_t launch_gemm_bf16_planes(hipStream_t s, const GemmArgs& a) {
+  if (a.M <= 0) return hipSuccess;
+  if (a.epi != EPI_PARTIAL || a.K % 64 != 0 || a.N % 32 != 0 || a.lda % 8 != 0) return hipErrorInvalidValue;
+  if (a.k_slices != gemm_plane_count(a.K, a.k_slices) || a.part_stride < (size_t)a.M * a.ldo) return hipErrorInvalidValue;
+  // 128-column workgroups, one 32-column block per wave, a 16-step weight ring (measured at 72 rows against 50-280 MB of
+  // weights: ahead of 256- and 64-column workgroups and of an 8-step ring at every split count)
+  if (a.M <= 32) return launch_cfg<1, 1, 1, 16, 256>(s, a, a.k_slices);
+  if (a.M <= 64) return launch_cfg<2, 1, 1, 16, 256>(s, a, a.k_slices);
+  if (a.M <= 96) return launch_cfg<3, 1, 1, 16, 256>(s, a, a.k_slices);
+  if (a.M <= 128) return launch_cfg<4, 1, 1, 16, 256>(s, a, a.k_slices);
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_gemm_f32(hipStream_t s, const GemmArgs& a) {

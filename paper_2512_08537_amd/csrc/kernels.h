@@ -81,6 +81,13 @@ hipError_t launch_rope_append(hipStream_t s, void* qkv, int ld, int n_heads, KvG
                               float rope_theta, const int* row_sample, const int* row_pos, int M,
                               const int* m_dev);
 
+// The same with the rows still in the K-slice planes of the QKV product (fp32 [n_parts][M, ld], plane p at
+// parts + p * part_stride): the planes are summed, q and k rotated in fp32; q goes to qkv as bf16 (the k and v columns of
+// qkv are not written), k and v to the cache.  bf16 caches only.
+hipError_t launch_rope_append_planes(hipStream_t s, const float* parts, int n_parts, size_t part_stride, void* qkv, int ld,
+                                     int n_heads, KvGeom kv, int rope, float rope_theta, const int* row_sample,
+                                     const int* row_pos, int M, const int* m_dev);
+
 // Copies plain [B, Hkv, n, dh] tensors (storage type of the context) into the cache at positions 0..n-1.
 hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v, int B, int n);
 
@@ -92,10 +99,20 @@ hipError_t launch_kv_load(hipStream_t s, KvGeom kv, const void* k, const void* v
 // rows; cache_len[b] is then the position of the first of them); without it the rows are row_start[b] .. row_start[b+1].
 // n_pass > 1: that many passes in one launch; pass p reads entries [p * B, (p + 1) * B) of cache_len, row_start and
 // row_cnt.  The K / V rows of all passes must be in the cache already (append == 0).
+// split (optional, n > 1; bf16, append == 0, n_pass == 1): the 32-key blocks of every (sample, kv head) are dealt to n
+// workgroups, each leaving its running softmax triple and unnormalised output rows in the planes of `split`, and a
+// second launch folds them (few samples x kv heads against a long context would otherwise occupy a fraction of the
+// chip).  M / m_dev: packed rows of the call (host bound / optional device count), needed by that second launch.
+struct AttnSplit {
+  int n;              // workgroups per (sample, kv head)
+  int rows;           // row capacity of the planes
+  float* o;           // [n][rows][n_heads][d_head] unnormalised outputs, relative to the split's own maximum
+  float* mla;         // [n][rows][n_heads][4] running maximum, sum, entropy accumulator
+};
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv,
                             const int* cache_len, const int* row_start, int B, int nq_max,
                             void* out, int ldo, float* ent_heads, int append, const int* row_cnt = nullptr,
-                            int n_pass = 1);
+                            int n_pass = 1, const AttnSplit* split = nullptr, int M = 0, const int* m_dev = nullptr);
 
 // Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
 // Up to ENT_SAMPLE_MODE_MIN_B samples: a wave per row, then one workgroup thresholds and compacts.  Above: a

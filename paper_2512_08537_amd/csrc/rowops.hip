@@ -330,6 +330,73 @@ __global__ __launch_bounds__(256) void rope_append_kernel(T* __restrict__ qkv, i
   }
 }
 
+// The same from the K-slice planes of the QKV product (fp32 [n_parts][M, ld], bias in plane 0): sums the planes, rotates
+// q and k in fp32, writes q as bf16 into qkv (what the attention kernel reads) and k, v into the cache.
+// Grid (rows, head groups): a thread owns 4 consecutive dims c .. c+3 of the first half of one head and their partners
+// c + d_head/2 ..; all its loads (2 x 16 bytes per plane, PMAX planes at most per batch) are requested before the first sum.
+template <int PMAX>
+__global__ __launch_bounds__(256) void rope_append_planes_kernel(const float* __restrict__ parts, int n_parts, size_t part_stride,
+                                                                 bf16* __restrict__ qkv, int ld, int n_heads, KvGeom kv, int rope,
+                                                                 float theta, const int* __restrict__ row_sample,
+                                                                 const int* __restrict__ row_pos, int M, const int* m_dev) {
+  const int Me = eff_rows(M, m_dev);
+  const int r = blockIdx.x;
+  if (r >= Me) return;
+  const int dh = kv.d_head, Hk = kv.n_kv_heads, half = dh >> 1;
+  const int tph = half >> 2;                               // threads per head
+  const int hpw = 256 / tph;                               // heads per workgroup
+  const int hd = blockIdx.y * hpw + threadIdx.x / tph;     // q heads, then k heads, then v heads
+  if (hd >= n_heads + 2 * Hk) return;
+  const int c = (threadIdx.x % tph) * 4;
+  const int b = row_sample[r], pos = row_pos[r];
+  const float* p0 = parts + (size_t)r * ld + (size_t)hd * dh + c;
+  f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
+  for (int pb = 0; pb < n_parts; pb += PMAX) {
+    f32x4 tl[PMAX], th[PMAX];
+#pragma unroll
+    for (int p = 0; p < PMAX; ++p) {
+      const int pp = pb + p < n_parts ? pb + p : pb;       // (a re-read that is not added)
+      tl[p] = *(const f32x4*)(p0 + (size_t)pp * part_stride);
+      th[p] = *(const f32x4*)(p0 + (size_t)pp * part_stride + half);
+    }
+#pragma unroll
+    for (int p = 0; p < PMAX; ++p)
+      if (pb + p < n_parts) { lo += tl[p]; hi += th[p]; }
+  }
+  const bool is_v = hd >= n_heads + Hk;
+  if (rope && !is_v) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float sn, cs;
+      const float inv = powf(theta, -2.0f * (float)(c + e) / (float)dh);
+      sincosf((float)pos * inv, &sn, &cs);
+      const float a = lo[e], bb = hi[e];
+      lo[e] = a * cs - bb * sn;
+      hi[e] = bb * cs + a * sn;
+    }
+  }
+  bf16x4 blo, bhi;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { blo[e] = (bf16)lo[e]; bhi[e] = (bf16)hi[e]; }
+  const size_t head_elems = (size_t)kv.ctx_pad * dh;
+  if (hd < n_heads) {
+    bf16* q = qkv + (size_t)r * ld + (size_t)hd * dh + c;
+    *(bf16x4*)q = blo;
+    *(bf16x4*)(q + half) = bhi;
+  } else if (!is_v) {
+    bf16* kc = (bf16*)kv.k + ((size_t)b * Hk + (hd - n_heads)) * head_elems;
+    *(bf16x4*)(kc + k_offset_bf16(pos, c, dh)) = blo;      // 8 consecutive dims of a key are contiguous in the cache
+    *(bf16x4*)(kc + k_offset_bf16(pos, c + half, dh)) = bhi;
+  } else {
+    bf16* vc = (bf16*)kv.v + ((size_t)b * Hk + (hd - n_heads - Hk)) * head_elems;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      vc[v_offset_bf16(pos, c + e, dh)] = blo[e];
+      vc[v_offset_bf16(pos, c + half + e, dh)] = bhi[e];
+    }
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void kv_load_kernel(KvGeom kv, const T* __restrict__ k, const T* __restrict__ v,
                                                       int B, int n) {
@@ -1299,6 +1366,22 @@ hipError_t launch_rope_append(hipStream_t s, void* qkv, int ld, int n_heads, KvG
     rope_append_kernel<bf16><<<M, 256, 0, s>>>((bf16*)qkv, ld, n_heads, kv, rope, rope_theta, row_sample, row_pos, M, m_dev);
   else
     rope_append_kernel<float><<<M, 256, 0, s>>>((float*)qkv, ld, n_heads, kv, rope, rope_theta, row_sample, row_pos, M, m_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_append_planes(hipStream_t s, const float* parts, int n_parts, size_t part_stride, void* qkv, int ld,
+                                     int n_heads, KvGeom kv, int rope, float rope_theta, const int* row_sample,
+                                     const int* row_pos, int M, const int* m_dev) {
+  if (M <= 0) return hipSuccess;
+  const int dh = kv.d_head;
+  // a head's first half in groups of 4 dims; 16-byte loads of the planes, 8-byte stores of q and k
+  if (!kv.is_bf16 || n_parts < 1 || dh % 16 != 0 || dh > 2048 || 256 % (dh / 8) != 0 || ld % 4 != 0 || part_stride % 4 != 0 ||
+      (((uintptr_t)parts) & 15) != 0 || (((uintptr_t)qkv) & 7) != 0)
+    return hipErrorInvalidValue;
+  const int hpw = 256 / (dh / 8);
+  const dim3 grid(M, (n_heads + 2 * kv.n_kv_heads + hpw - 1) / hpw);
+  rope_append_planes_kernel<8><<<grid, 256, 0, s>>>(parts, n_parts, part_stride, (bf16*)qkv, ld, n_heads, kv, rope, rope_theta,
+                                                    row_sample, row_pos, M, m_dev);
   return hipGetLastError();
 }
 

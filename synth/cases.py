@@ -39,12 +39,18 @@ def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_d
         # is far from uniform (a wrong K/Q layout shows) yet bf16 rounding of q, k stays within the bar
         std_overrides = dict(std_overrides or {})
         std_overrides["wqkv"] = 1.4 / np.sqrt(min(rc.target.d_model, rc.draft.d_model))
-    if w_std is None:
-        w_std = 0.02                                       # the workload recipe: N(0, 0.02)
+    # the workload recipe: N(0, 0.02) up to 2048 channels; wider models draw N(0, (0.64 / sqrt(d_model))^2), the std at
+    # which a projection's gain std * sqrt(fan_in) is what 0.02 gives the 1024-wide configuration (with 0.02 itself a
+    # 5120-wide pre-norm stack amplifies every rounding error: see the design notes)
+    def recipe_std(cfg):
+        if w_std is not None:
+            return w_std
+        return 0.02 if cfg.d_model <= 2048 else 0.64 / float(np.sqrt(cfg.d_model))
+    std_t, std_d, std_h = recipe_std(rc.target), recipe_std(rc.draft), (0.02 if w_std is None else w_std)
     same_shape = (rc.draft.d_model, rc.draft.n_heads, rc.draft.n_kv_heads, rc.draft.d_ff) == \
                  (rc.target.d_model, rc.target.n_heads, rc.target.n_kv_heads, rc.target.d_ff)
     # lazy: the weights are drawn tensor by tensor when read (gen.LazyWeights) instead of all at once; same values
-    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
+    W = gen.tf_weights(rc.target, seed, "target", rc.dtype, w_std=std_t, affine=affine, std_overrides=std_overrides,
                        deep_from=rc.draft.n_layers, deep_gain=deep_gain, recipes_only=lazy)
     aliases = {}
     if same_shape:
@@ -53,9 +59,9 @@ def build_case(kind, seed=0, n_ctx=None, B=None, affine=True, w_std=None, same_d
         else:
             W.update(gen.truncated_draft(W, rc.target, rc.draft))
     else:
-        W.update(gen.tf_weights(rc.draft, seed, "draft", rc.dtype, w_std=w_std, affine=affine, std_overrides=std_overrides,
+        W.update(gen.tf_weights(rc.draft, seed, "draft", rc.dtype, w_std=std_d, affine=affine, std_overrides=std_overrides,
                                 recipes_only=lazy))
-    W.update(gen.head_weights(rc.head, seed, rc.dtype, w_std=w_std, affine=affine, recipes_only=lazy))
+    W.update(gen.head_weights(rc.head, seed, rc.dtype, w_std=std_h, affine=affine, recipes_only=lazy))
     if lazy:
         numel = {}
         for pre, shapes in (("target", gen.tf_weight_shapes(rc.target)), ("draft", gen.tf_weight_shapes(rc.draft)),

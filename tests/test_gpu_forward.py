@@ -170,3 +170,31 @@ def test_capacity_and_argument_errors():
         ctx.spec_kv_commit(-1, ctx.dev_i32(np.zeros(B)))
     assert e.value.code == -6
     ctx.close()
+
+
+def test_forward_of_72_rows_through_k_slice_planes():
+    """72 rows (8 samples x 9) through one 3072-wide layer whose QKV, output and down projections are 19-25 MB each: the
+    shapes at which K is split over workgroups of the streaming kernel and the products leave as planes that the RoPE /
+    cache-append kernel and the next norm sum (the verify stage of the 5120-wide configuration, reduced).  All samples
+    against the oracle, ragged row counts included in a second call."""
+    from synth.configs import (RoundCfg, TfCfg, HeadCfg, ACT_SWIGLU, NORM_RMS, POS_ROPE)
+    tgt = TfCfg(n_layers=2, d_model=3072, n_heads=24, n_kv_heads=4, d_head=128, d_ff=4096,
+                act=ACT_SWIGLU, norm=NORM_RMS, pos=POS_ROPE, has_bias=0, norm_eps=1e-6)
+    drf = TfCfg(n_layers=1, d_model=256, n_heads=2, n_kv_heads=1, d_head=128, d_ff=192,
+                act=ACT_SWIGLU, norm=NORM_RMS, pos=POS_ROPE, has_bias=0, norm_eps=1e-6, d_out=3072)
+    rc = RoundCfg(name="planes-72", target=tgt, draft=drf, head=HeadCfg(1, 128, 3072, n_steps=1), K=8, max_batch=8,
+                  max_ctx=64, entropy_layer=1, batch=8, n_ctx=40)
+    case = build_case(rc, seed=45, w_std=0.012)            # (a branch gain below one at this width, as trained layers have)
+    ctx = make_ctx(case)
+    B, D = 8, 16
+    rng = np.random.default_rng(12)
+    for n_q in (np.full(B, 9), np.array([9, 0, 9, 3, 9, 9, 1, 9])):
+        xs = [gen.bf16_round(rng.normal(size=(n, D)).astype(np.float32)) for n in n_q]
+        z, sh, _ = ctx.spec_forward(0, ctx.dev_f32(_pack(xs)), n_q, commit=False, want_shallow=True, nq_max=9)
+        ctx.sync()
+        zo, sho, _ = _oracle_forward(case, 0, xs, shallow=1)
+        ez = rel_inf(z.float().cpu().numpy()[:int(n_q.sum())], np.concatenate(zo))
+        es = rel_inf(sh.cpu().numpy()[:int(n_q.sum())], np.concatenate(sho))
+        print(f"72 rows through planes, n_q {n_q.tolist()}: z {ez:.2e} shallow {es:.2e}")
+        assert ez < 2e-2 and es < 2e-2
+    ctx.close()

@@ -183,14 +183,22 @@ def test_config1_full_size_sampled_samples():
         assert np.array_equal(g[k], g2[k]), k
 
 
-def teacher_forced_round(case, ctx, o, idx, tau=-1.0, W_oracle=None):
+def rel_rms(g, o):
+    """Root-mean-square error over the root-mean-square of the oracle's values."""
+    o = np.asarray(o, dtype=np.float64)
+    return float(np.sqrt(np.mean((np.asarray(g, dtype=np.float64) - o) ** 2) / max(np.mean(o ** 2), 1e-300)))
+
+
+def teacher_forced_round(case, ctx, o, idx, tau=-1.0, verify_tol=None, verify_mu_tol=None):
     """The full-size check that bounds the kernels rather than the chain: the K draft steps depend on one another
     (the latent of step i is the input of step i + 1 and enters the draft cache), so a free-running comparison of
     step 7 measures seven steps of accumulated bf16 rounding.  Here every draft step of the sampled samples is fed the
     ORACLE's previous token (spec_draft_step), and spec_verify gets the oracle's drafts, draft means and survivor
     counts; every row is then held to the flat bars (latents and means 2e-2 over the sample's tensor, entropy 1e-3
     absolute).  The other samples of the batch run on the library's own tokens, so the launch shapes are those of the
-    benchmark.  Returns the free-running round (whose drift against the oracle is printed, not gated)."""
+    benchmark.  Returns the free-running round (whose drift against the oracle is printed, not gated).
+    verify_tol / verify_mu_tol: other bars for the target's features and for the means decoded from them (see
+    tests/test_gpu_config3.py; there the head is checked on the oracle's features in a step of its own)."""
     from paper_2512_08537_amd import binding
     rc, B, K = case.rc, case.B, case.rc.K
     tol = TOL[rc.dtype]
@@ -241,15 +249,19 @@ def teacher_forced_round(case, ctx, o, idx, tau=-1.0, W_oracle=None):
     v = to_np(v)
     from oracle import accept as oac
     sg = rc.head.sigma_last * rc.head.temperature
+    tol_z = tol if verify_tol is None else verify_tol
+    tol_mu = tol_z if verify_mu_tol is None else verify_mu_tol
     for bi, b in enumerate(idx):
         nk = int(o["n_keep"][bi])
+        rz, rp = rel_rms(v["z_p"][b, :nk + 1], o["z_p"][bi]), rel_rms(v["mu_p"][b, :nk + 1], o["mu_p"][bi, :nk + 1])
+        print(f"sample {b}: verify rms-relative z_p {rz:.2e} mu_p {rp:.2e}")
         ep = rel_inf(v["mu_p"][b, :nk + 1], o["mu_p"][bi, :nk + 1])
         ez = rel_inf(v["z_p"][b, :nk + 1], o["z_p"][bi])
         per = [rel_inf(v["mu_p"][b, j], o["mu_p"][bi, j]) for j in range(nk + 1)]
         drift = [rel_inf(free["mu_p"][b, j], o["mu_p"][bi, j]) for j in range(min(nk, int(free["n_keep"][b])) + 1)]
         print(f"sample {b}: verify z_p {ez:.2e} mu_p {ep:.2e}; per row {np.array2string(np.array(per), precision=4)}  free-running {np.array2string(np.array(drift), precision=4)}")
-        assert ez < tol and ep < tol
-        assert max(per) < 2 * tol
+        assert ez < tol_z and ep < tol_mu
+        assert max(per) < 2 * tol_mu
         assert not v["mu_p"][b, nk + 1:].any()
         if nk:
             # ln rho: exact rule on the library's own means (unit level), and against the oracle's value
@@ -257,7 +269,7 @@ def teacher_forced_round(case, ctx, o, idx, tau=-1.0, W_oracle=None):
             assert np.allclose(v["log_ratio"][b, :nk], lr_unit[0, :nk], rtol=1e-3, atol=2e-3)
             el = rel_inf(v["log_ratio"][b, :nk], o["log_ratio"][bi, :nk])
             print(f"sample {b}: ln rho against the oracle {el:.2e}")
-            assert el < tol
+            assert el < tol_mu
     return free
 
 
