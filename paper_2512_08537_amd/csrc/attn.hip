@@ -25,8 +25,13 @@ namespace fard {
 
 namespace {
 
+#ifndef ATTN_OCC
+#define ATTN_OCC 4
+#endif
+#define ATTN_MIN_WG(DH, NQB) (((DH) == 64 && (NQB) == 1) ? ATTN_OCC : 1)
+
 template <int DH, int NQB>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const bf16* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
+__global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(const bf16* __restrict__ qkv, int ld, int n_heads, KvGeom kv,
                                                         const int* __restrict__ cache_len,
                                                         const int* __restrict__ row_start, const int* __restrict__ row_cnt,
                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads,
