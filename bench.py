@@ -26,19 +26,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
+CLASSES = ("gemm", "attention", "entropy", "other", "gemm_narrow")     # spec_profile_read's kernel classes
 
 
-def hbm_traffic_per_launch(config):
-    """HBM bytes per GEMM launch from the committed rocprofv3 --pmc summary of this benchmark (FETCH_SIZE and
-    WRITE_SIZE, scaled by a plain copy kernel).  The summary names the kernel sources it was measured on
-    (`sources_sha16`); None when no summary covers the configuration or the sources have changed since."""
+def hbm_traffic_per_launch(config, kernel_class):
+    """HBM bytes per launch of a GEMM kernel class ("gemm": the streaming kernels, "gemm_narrow") from the committed
+    rocprofv3 --pmc summary of this benchmark (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy kernel).  The summary
+    names the kernel sources it was measured on (`sources_sha16`); None when no summary covers the configuration or the
+    sources have changed since."""
     from paper_2512_08537_amd.build import sources_hash
     path = os.path.join(ROOT, "profiles", f"gemm_cfg{config}_hbm_traffic.txt")
     val, sha = None, None
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
+                if line.startswith(f"traffic_bytes_per_launch[{kernel_class}]:"):
                     val = int(line.split(":")[1])
                 if line.startswith("sources_sha16:"):
                     sha = line.split(":")[1].strip()
@@ -141,9 +143,13 @@ def measure(cfg_idx, args, headline):
     ctx.spec_profile_enable(True)
     for _ in range(args.steps):
         step()
-    prof = {name: ctx.spec_profile_read(i) for i, name in enumerate(("gemm", "attention", "entropy", "other"))}
+    prof = {name: ctx.spec_profile_read(i) for i, name in enumerate(CLASSES)}
     ctx.spec_profile_enable(False)
-    g = prof["gemm"]
+    # the dominant kernel class: the streaming GEMM kernels (every GEMM above a few hundred rows; at configs[3] the
+    # weight stream of the 72-row verify stage) or the narrow-tile GEMM kernel (draft steps, head decodes, and at
+    # configs[1] nearly every GEMM), whichever the round spends more time in; the other one is in `kernels`
+    dom = "gemm" if prof["gemm"]["ms"] >= prof["gemm_narrow"]["ms"] else "gemm_narrow"
+    g = prof[dom]
     # An event pair around every launch adds the dispatch gap to each bracket: the brackets of a round sum to more
     # than the round takes without them.  That excess, spread evenly over the launches, is taken off every bracket,
     # which brings the figure to the kernel durations a rocprofv3 trace shows (profiles/).
@@ -161,11 +167,13 @@ def measure(cfg_idx, args, headline):
     intensity = g["flops"] / max(g["bytes"], 1.0)
     hbm_bound = intensity < peak * 1e12 / (PEAK_HBM_GBS * 1e9)
     roofline = {"bound": "hbm" if hbm_bound else ("mfma" if rc.dtype == 1 else "alu"),
-                "kernel": "GEMM kernels of the round (gemm_narrow_kernel, gemm_bf16_kernel, gemm_bf16_res_kernel)",
+                "kernel": ("streaming GEMM kernels (gemm_bf16_kernel, gemm_bf16_res_kernel: all instances)" if dom == "gemm"
+                           else "narrow-tile GEMM kernel (gemm_narrow_kernel: all instances)"),
+                "share_of_round_kernel_time": round(g["ms"] / max(all_ms, 1e-9), 4),
                 "achieved": round(g_gbs, 1) if hbm_bound else round(g_tflops, 3),
                 "peak": PEAK_HBM_GBS if hbm_bound else peak, "unit": "GB/s" if hbm_bound else "TFLOP/s",
                 "frac": round(g_gbs / PEAK_HBM_GBS, 5) if hbm_bound else round(g_tflops / peak, 5),
-                "traffic": hbm_traffic_per_launch(cfg_idx), "launches_per_step": g["launches"] / args.steps,
+                "traffic": hbm_traffic_per_launch(cfg_idx, dom), "launches_per_step": g["launches"] / args.steps,
                 "avg_launch_us": round(g_avg_us, 3), "avg_launch_us_with_event_pair": round(g_raw_us, 3),
                 "event_pair_overhead_us": round(overhead_us, 3),
                 "flops_per_launch": g["flops"] / max(g["launches"], 1),
@@ -188,6 +196,13 @@ def measure(cfg_idx, args, headline):
                for k, v in prof.items()}
     kernels["attention"]["achieved_GBs"] = round(att_gbs, 1)
     kernels["attention"]["frac_hbm"] = round(att_gbs / PEAK_HBM_GBS, 5)
+    for name in ("gemm", "gemm_narrow"):
+        v = prof[name]
+        ms_c = max(v["ms"] - overhead_us * 1e-3 * v["launches"], 0.25 * v["ms"])
+        if ms_c > 0:
+            kernels[name]["achieved_GBs"] = round(v["bytes"] / (ms_c * 1e-3) / 1e9, 1)
+            kernels[name]["achieved_TFLOPs"] = round(v["flops"] / (ms_c * 1e-3) / 1e12, 2)
+            kernels[name]["avg_launch_us"] = round(ms_c / max(v["launches"], 1) * 1e3, 3)
     res["roofline"], res["kernels"] = roofline, kernels
     if not headline:
         ctx.close()
@@ -237,7 +252,7 @@ def measure(cfg_idx, args, headline):
             nk = out["n_keep"].cpu().numpy()
             ctx.spec_profile_enable(True)
             step(tv)
-            pf = {name: ctx.spec_profile_read(i) for i, name in enumerate(("gemm", "attention", "entropy", "other"))}
+            pf = {name: ctx.spec_profile_read(i) for i, name in enumerate(CLASSES)}
             ctx.spec_profile_enable(False)
             sweep.append({"target_filtered": frac, "tau": round(tv, 5), "filtered": round(1.0 - float(nk.sum()) / (B * K), 4),
                           "surviving_drafts": int(nk.sum()), "verify_rows": int(nk.sum()) + B,

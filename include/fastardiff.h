@@ -344,7 +344,8 @@ int spec_peak_probe(fard_ctx* ctx, int32_t kind, const void* buf, int64_t bytes,
 /* Per-kernel timing with HIP events on the context's stream.  enable = 1 brackets every launch of
  * the named kernel class between two events; spec_profile_read synchronises and returns the
  * accumulated time (ms) and launch count since enable, then clears them.
- * class: 0 GEMM, 1 attention, 2 entropy, 3 everything else. */
+ * class: 0 GEMMs of the streaming kernels (every GEMM above a few hundred rows, the weight stream of the 72-row verify
+ * stage), 1 attention, 2 entropy, 3 everything else, 4 GEMMs of the narrow-tile kernel (draft steps, head decodes). */
 int spec_profile_enable(fard_ctx* ctx, int32_t enable);
 int spec_profile_read(fard_ctx* ctx, int32_t kernel_class, float* total_ms, int64_t* launches,
                       double* flops, double* bytes);

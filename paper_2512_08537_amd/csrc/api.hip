@@ -203,7 +203,7 @@ struct Prof {
   std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
   std::vector<int> cls;
   size_t used = 0;
-  double flops[4] = {0, 0, 0, 0}, bytes[4] = {0, 0, 0, 0};
+  double flops[5] = {0, 0, 0, 0, 0}, bytes[5] = {0, 0, 0, 0, 0};
 };
 
 // A captured round: spec_round called again with the arguments of `key` replays `exec` instead of launching
@@ -334,7 +334,7 @@ struct Bracket {
     if (slot != (size_t)-1) (void)hipEventRecord(c->prof.pool[slot].second, c->stream);
   }
 };
-enum { CLS_GEMM = 0, CLS_ATTN = 1, CLS_ENT = 2, CLS_OTHER = 3 };
+enum { CLS_GEMM = 0, CLS_ATTN = 1, CLS_ENT = 2, CLS_OTHER = 3, CLS_GEMM_NARROW = 4, CLS_COUNT = 5 };
 
 // ------------------------------------------------------------------------------ weight upload
 struct Loader {
@@ -591,9 +591,10 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
   }
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
-  Bracket br(c, CLS_GEMM, fl, by);
+  const bool narrow = c->bf16 && routes_narrow(M, N, K, epi) && narrow_supported(a);
+  Bracket br(c, narrow ? CLS_GEMM_NARROW : CLS_GEMM, fl, by);
   if (!c->bf16) return launch_gemm_f32(c->stream, a);
-  if (routes_narrow(M, N, K, epi) && narrow_supported(a)) return launch_gemm_narrow(c->stream, a);
+  if (narrow) return launch_gemm_narrow(c->stream, a);
   return launch_gemm_bf16(c->stream, a);
 }
 
@@ -801,7 +802,7 @@ hipError_t gemm_planes(fard_ctx* c, const void* A, int lda, const void* W, const
   if ((size_t)a.k_slices * a.part_stride > c->parts_cap) return hipErrorInvalidValue;   // never launch past the planes
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * N * 4;
-  Bracket br(c, CLS_GEMM, fl, by);
+  Bracket br(c, wide > 0 ? CLS_GEMM : CLS_GEMM_NARROW, fl, by);
   hipError_t e = wide > 0 ? launch_gemm_bf16_planes(c->stream, a) : launch_gemm_narrow(c->stream, a);
   if (e == hipSuccess) {
     *n_planes = a.k_slices;
@@ -1841,7 +1842,7 @@ int spec_gemm_narrow(fard_ctx* c, const void* A, const void* W, const float* bia
   }
   HIPCHK(c, launch_pack_weight(c->stream, W, 1, N, K, N, c->gemm_tmp, 0, 1));
   a.W = c->gemm_tmp;
-  { Bracket br(c, CLS_GEMM, 2.0 * M * (double)N * K, (double)K * N * 2);
+  { Bracket br(c, CLS_GEMM_NARROW, 2.0 * M * (double)N * K, (double)K * N * 2);
     HIPCHK(c, launch_gemm_narrow(c->stream, a)); }
   return FARD_OK;
 }
@@ -1879,7 +1880,7 @@ int spec_gemm_norm(fard_ctx* c, const void* x, const void* W, const float* g, co
   a.M = M; a.N = N; a.K = K; a.m_dev = nullptr; a.act = act; a.epi = EPI_STORE;
   a.ln_cs = cs; a.ln_eps = eps; a.ln_rms = norm_type == FARD_NORM_RMS;
   if (!narrow_supported(a)) return fail(c, FARD_ESHAPE, "unsupported shape");
-  { Bracket br(c, CLS_GEMM, 2.0 * M * (double)N * K, (double)K * N * 2);
+  { Bracket br(c, CLS_GEMM_NARROW, 2.0 * M * (double)N * K, (double)K * N * 2);
     HIPCHK(c, launch_gemm_narrow(c->stream, a)); }
   return FARD_OK;
 }
@@ -1924,13 +1925,13 @@ int spec_profile_enable(fard_ctx* c, int32_t enable) {
   HIPCHK(c, hipStreamSynchronize(c->stream));
   c->prof.on = enable != 0;
   c->prof.used = 0;
-  for (int i = 0; i < 4; ++i) c->prof.flops[i] = c->prof.bytes[i] = 0;
+  for (int i = 0; i < CLS_COUNT; ++i) c->prof.flops[i] = c->prof.bytes[i] = 0;
   return FARD_OK;
 }
 
 int spec_profile_read(fard_ctx* c, int32_t kernel_class, float* total_ms, int64_t* launches, double* flops, double* bytes) {
   if (check_ctx(c)) return FARD_EINVAL;
-  if (kernel_class < 0 || kernel_class > 3) return fail(c, FARD_EINVAL, "kernel_class");
+  if (kernel_class < 0 || kernel_class >= CLS_COUNT) return fail(c, FARD_EINVAL, "kernel_class");
   HIPCHK(c, hipStreamSynchronize(c->stream));
   float tot = 0.f;
   int64_t n = 0;

@@ -25,6 +25,9 @@ namespace {
 // (528 / 1040 B): the 16-byte reads of 32 consecutive rows spread over all banks.
 
 // Register e of a 32x32 accumulator holds row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+
+// Direct epilogue: every wave stores its own accumulator blocks, no barrier.  For tiles of many-row products, where a
+// compute unit runs workgroup after workgroup and the waves' stores overlap the next tiles' MFMAs.
 template <int KIND, bool FULL, int WM, int WN>
 __device__ __forceinline__ void epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN], int m0, int M, int nb0, int nblocks,
                                          int cl, int rhalf, bool add_bias, bool atomic, int sp) {
@@ -73,10 +76,100 @@ __device__ __forceinline__ void epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN
   }
 }
 
+// Staged epilogue, for products of one row tile (M <= 128), whose launch is one workgroup per compute unit.
+// The tile leaves through LDS, 32 rows at a time: the waves that hold the sums write
+// their accumulator block, then all 256 threads read it back row-contiguous and store 16 bytes per lane (whole cache
+// lines), in a loop of a few dozen instructions.  The direct epilogue, unrolled over the 16 WM WN accumulator registers, with
+// its row and kind tests per element, runs to several thousand instructions per kernel; here every workgroup executes
+// it once, cold, and its instruction fetches queue behind the weight stream (measured at 72 rows: 4.3 us of a
+// 16 us launch between the last MFMA and the last store).  lds: 32 x (BN + 4) floats.
+template <int WM, int WN, int NWN>
+__device__ __forceinline__ void staged_epilogue(const GemmArgs& a, f32x16 (&acc)[WM][WN], float* lds, int m0, int M,
+                                                int n0, bool holds_sums, int nw, bool add_bias, bool atomic, int sp) {
+  constexpr int BNW = 32 * WN, BN = BNW * NWN, LDT = BN + 4;
+  constexpr int GPR = BN / 4;                              // groups of 4 columns per row
+  constexpr int RSTEP = 256 / GPR;                         // rows covered by one pass of the 256 threads
+  static_assert(256 % GPR == 0 && 32 % RSTEP == 0, "a thread keeps its column group over all rows");
+  const int lane = threadIdx.x & 63;
+  const int col = (threadIdx.x % GPR) * 4, r0 = threadIdx.x / GPR;
+  const int gc = n0 + col;
+  const int N = a.N, epi = a.epi;
+  f32x4 bias4 = {0.f, 0.f, 0.f, 0.f};
+  if (epi != EPI_SWIGLU && a.bias != nullptr && add_bias && gc < N) bias4 = *(const f32x4*)(a.bias + gc);
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    const int mb = m0 + 32 * i;
+    if (mb >= M) break;                                    // uniform over the workgroup
+    __syncthreads();                                       // the staging area is free
+    if (holds_sums) {
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          lds[(8 * (e >> 2) + 4 * (lane >> 5) + (e & 3)) * LDT + nw * BNW + 32 * j + (lane & 31)] = acc[i][j][e];
+    }
+    __syncthreads();
+    if (epi == EPI_SWIGLU) {
+      // packed column blocks alternate gate / up (32 columns each): output column = packed / 2
+      constexpr int OGPR = BN / 8;                         // groups of 4 output columns per row
+      bf16* out = (bf16*)a.out;
+      for (int idx = threadIdx.x; idx < 32 * OGPR; idx += 256) {
+        const int row = idx / OGPR, oc = (idx - row * OGPR) * 4;
+        const int pc = (oc >> 5) * 64 + (oc & 31);         // packed column of the gate value
+        const int gr = mb + row;
+        if (gr >= M || n0 + pc + 32 >= N) continue;        // gate and up blocks both inside N
+        const f32x4 g = *(const f32x4*)(&lds[row * LDT + pc]), u = *(const f32x4*)(&lds[row * LDT + pc + 32]);
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)(silu(g[e]) * u[e]);
+        *(bf16x4*)(out + (size_t)gr * a.ldo + (n0 >> 1) + oc) = o;
+      }
+      continue;
+    }
+    if (atomic) {
+      // partial sums of a split K range meet in memory: one column per lane, so that an atomic instruction of a wave
+      // covers whole 128-byte segments
+      for (int idx = threadIdx.x; idx < 32 * BN; idx += 256) {
+        const int row = idx / BN, c = idx - row * BN;
+        const int gr = mb + row, gn = n0 + c;
+        if (gr >= M || gn >= N) continue;
+        float v = lds[row * LDT + c];
+        if (a.bias != nullptr && add_bias) v += a.bias[gn];
+        if (epi == EPI_GATE_RESID) v *= a.gate[(size_t)gr * a.ldg + gn];
+        atomicAdd((float*)a.out + (size_t)gr * a.ldo + gn, v);
+      }
+      continue;
+    }
+    if (gc >= N) continue;                                 // N % 32 == 0: a group is all in or all out
+    for (int row = r0; row < 32; row += RSTEP) {
+      const int gr = mb + row;
+      if (gr >= M) break;
+      f32x4 v = *(const f32x4*)(&lds[row * LDT + col]) + bias4;
+      const size_t o = (size_t)gr * a.ldo + gc;
+      if (epi == EPI_STORE) {
+        bf16x4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = (bf16)apply_act(v[e], a.act);
+        *(bf16x4*)((bf16*)a.out + o) = t;
+      } else if (epi == EPI_STORE_F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], a.act);
+        *(f32x4*)((float*)a.out + o) = v;
+      } else if (epi == EPI_PARTIAL) {
+        *(f32x4*)((float*)a.out + (size_t)sp * a.part_stride + o) = v;   // the K split's own plane: no atomics
+      } else {
+        if (epi == EPI_GATE_RESID) v *= *(const f32x4*)(a.gate + (size_t)gr * a.ldg + gc);
+        float* dst = (float*)a.out + o;
+        *(f32x4*)dst = *(const f32x4*)dst + v;
+      }
+    }
+  }
+}
+
 // WM x WN: 32x32 accumulator blocks per wave.  KW: waves of the workgroup that share the same output
 // columns and split every chunk's 16 k-steps between them (their partial sums meet in LDS at the end);
 // the other 4/KW waves sit side by side along N.  P: ring depth in k-steps of one wave.
-template <int WM, int WN, int KW, int P, int KC>
+template <int WM, int WN, int KW, int P, int KC, bool STAGED>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles, int m_tiles, int splits,
                                                         int chunks_per_split, int xm) {
   constexpr int KSTEPS = KC / 16;                          // MFMA k-steps per chunk
@@ -89,7 +182,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
   constexpr int PIECES = BM * (KC / 8);                    // 16-byte pieces in one A chunk
   constexpr int PPT = PIECES / 256;                        // pieces per thread (BM multiple of 32 -> exact)
   constexpr int RED_FLOATS = (KW > 1) ? NWN * WM * WN * 16 * 64 : 0;
-  constexpr int LDS_BYTES = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
+  constexpr int STAGE_BYTES = STAGED ? 32 * (32 * WN * NWN + 4) * 4 : 0;   // one 32-row block of the tile on its way out
+  constexpr int LDS_AR = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
+  constexpr int LDS_BYTES = LDS_AR > STAGE_BYTES ? LDS_AR : STAGE_BYTES;
   static_assert(G % P == 0 && G % SPW == 0, "ring depth and steps per wave must be powers of two");
   extern __shared__ __attribute__((aligned(16))) char lds_raw[];   // LDS_BYTES, passed at launch
   bf16* lds = (bf16*)lds_raw;
@@ -244,9 +339,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs a, int n_tiles,
             for (int e = 0; e < 16; ++e) acc[i][j][e] += red[((i * WN + j) * 16 + e) * 64 + lane];
       }
     }
-    if (kw != 0) return;
   }
 
+  // waves kw == 0 hold the tile's sums
+  if constexpr (STAGED) {
+    staged_epilogue<WM, WN, NWN>(a, acc, (float*)lds_raw, m0, M, nt * NWN * WN * 32, kw == 0, nw, sp == 0,
+                                 splits > 1 && a.epi != EPI_PARTIAL, sp);
+    return;
+  }
+  if (kw != 0) return;
   // epilogue, specialised on (kind, whole tile inside M) so that the executed path is straight-line
   const bool full = (m0 + BM <= M);
   const bool atomic = splits > 1 && a.epi != EPI_PARTIAL;
@@ -297,17 +398,25 @@ hipError_t launch_cfg(hipStream_t s, const GemmArgs& a, int splits) {
   // same formula as in the kernel: the activation chunk or the partial sums of the KW wave groups
   constexpr int LDS_STRIDE = KC + 8;
   constexpr int RED_FLOATS = (KW > 1) ? (4 / KW) * WM * WN * 16 * 64 : 0;
-  constexpr int LDS_BYTES = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
+  constexpr int STAGE_BYTES = 32 * (BN + 4) * 4;            // staged epilogue only; one size for both instances
+  constexpr int LDS_AR = (BM * LDS_STRIDE * 2 > RED_FLOATS * 4) ? BM * LDS_STRIDE * 2 : RED_FLOATS * 4;
+  constexpr int LDS_BYTES = LDS_AR > STAGE_BYTES ? LDS_AR : STAGE_BYTES;
+  // one row tile: one workgroup per compute unit, each through its epilogue once -> the staged, compact one
+  const bool staged = m_tiles == 1;
   if constexpr (LDS_BYTES > 64 * 1024) {
     static bool attr_set = false;                          // per template instance
     if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<WM, WN, KW, P, KC>,
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<WM, WN, KW, P, KC, true>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<WM, WN, KW, P, KC, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
       if (e != hipSuccess) return e;
       attr_set = true;
     }
   }
-  gemm_bf16_kernel<WM, WN, KW, P, KC><<<grid, 256, LDS_BYTES, s>>>(a, n_tiles, m_tiles, splits, cps, xm);
+  if (staged) gemm_bf16_kernel<WM, WN, KW, P, KC, true><<<grid, 256, LDS_BYTES, s>>>(a, n_tiles, m_tiles, splits, cps, xm);
+  else gemm_bf16_kernel<WM, WN, KW, P, KC, false><<<grid, 256, LDS_BYTES, s>>>(a, n_tiles, m_tiles, splits, cps, xm);
   return hipGetLastError();
 }
 

@@ -221,6 +221,18 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
     const int c4 = threadIdx.x + i * 256;
     x[i] = (c4 < n4) ? ((const f32x4*)row)[c4] : f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  // the row's modulation (AdaLN) is requested with the row itself: one memory round trip instead of a second one after
+  // the reduction
+  f32x4 scv[VPT], shv[VPT];
+  if (scale) {
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int c4 = threadIdx.x + i * 256;
+      const int cc = c4 < n4 ? c4 : 0;
+      scv[i] = *(const f32x4*)(scale + (size_t)r * ldm + cc * 4);
+      shv[i] = *(const f32x4*)(shift + (size_t)r * ldm + cc * 4);
+    }
+  }
   if (n_parts > 0) {
     // deferred residual update: the preceding GEMM left K-slice partial sums; fold them in (and write the row back)
     const size_t ro = (size_t)(in_map ? in_map[r] : r) * d;
@@ -269,11 +281,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
     for (int e = 0; e < 4; ++e) y[e] = (x[i][e] - mean) * rstd;
     if (g) { const f32x4 v = ((const f32x4*)g)[c4]; y *= v; }
     if (b) { const f32x4 v = ((const f32x4*)b)[c4]; y += v; }
-    if (scale) {
-      const f32x4 sc = *(const f32x4*)(scale + (size_t)r * ldm + c4 * 4);
-      const f32x4 sh = *(const f32x4*)(shift + (size_t)r * ldm + c4 * 4);
-      y = y * (1.0f + sc) + sh;
-    }
+    if (scale) y = y * (1.0f + scv[i]) + shv[i];
     store4<T>(out + (size_t)r * d + c4 * 4, y[0], y[1], y[2], y[3]);
   }
 }

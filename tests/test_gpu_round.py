@@ -349,3 +349,55 @@ def test_config0_full_round_fp32():
             assert np.array_equal(g["n_accept"], o["n_accept"])
         assert np.array_equal(ctx.spec_kv_lengths(binding.TARGET, 1), [64 + 1 + int(g["n_accept"][0])])
     ctx.close()
+
+
+def test_draft_steps_one_by_one_equal_spec_draft_and_lengths_restore_from_device():
+    """spec_draft_step K times (tokens taken from the library's own previous drafts) is spec_draft bit for bit, with
+    other calls on the context in between; spec_kv_restore rewinds the lengths from device memory and clamps them to
+    the bound the host is given; spec_kv_lengths resets the host's bound to the true maximum."""
+    import torch
+    from paper_2512_08537_amd import binding
+    case = build_case("mid-bf16", seed=37, std_overrides={"in.w": 0.5})
+    rc, B, K = case.rc, case.B, case.rc.K
+    ctx = make_ctx(case)
+    gi = gpu_inputs(ctx, case)
+    o_all = to_np(ctx.spec_draft(gi["pending"], gi["eps"], -1.0))
+    tau = float(np.median(o_all["H"]))                     # some samples stop early
+    lens = ctx.dev_i32(np.full(B, case.n_ctx, dtype=np.int32))
+    ctx.spec_kv_restore(binding.DRAFT, lens, case.n_ctx)
+    ref = to_np(ctx.spec_draft(gi["pending"], gi["eps"], tau))
+    assert 0 < ref["n_keep"].sum() < B * K
+    assert np.array_equal(ctx.spec_kv_lengths(binding.DRAFT, B), np.full(B, case.n_ctx + K))
+    ctx.spec_kv_restore(binding.DRAFT, lens, case.n_ctx)
+    out = ctx._round_bufs(B)
+    junk = ctx.dev_f32(np.zeros((B, 16), np.float32))
+    for i in range(K):
+        ctx.spec_draft_step(i, gi["pending"] if i == 0 else None, gi["eps"], tau, out)
+        if i == 2:                                          # another call in between uses the row maps and the workspace
+            ctx.spec_forward(binding.TARGET, junk, np.ones(B, np.int32), commit=False)
+    ctx.sync()
+    got = to_np(out)
+    for k in ("H", "keep", "n_keep", "x_draft", "mu_q"):
+        assert np.array_equal(got[k], ref[k]), k
+    with pytest.raises(binding.FardError) as e:             # steps out of order
+        ctx.spec_draft_step(3, None, gi["eps"], tau, out)
+    assert e.value.code == -6
+    # lengths from device memory: clamped to the host's bound, and the bound is what capacity is checked against
+    big = ctx.dev_i32(np.array([5, 10 ** 6, -4] + [7] * (B - 3), dtype=np.int32))
+    ctx.spec_kv_restore(binding.TARGET, big, 40)
+    got_len = ctx.spec_kv_lengths(binding.TARGET, B)
+    assert got_len[0] == 5 and got_len[1] == 40 and got_len[2] == 0 and (got_len[3:] == 7).all()
+    with pytest.raises(binding.FardError) as e:
+        ctx.spec_kv_restore(binding.TARGET, big, rc.max_ctx + 1)
+    assert e.value.code == -3
+    # a round raises the host's bound by K + 1 whatever was accepted; reading the lengths brings it back to the truth
+    ctx.spec_kv_restore(binding.TARGET, lens, rc.max_ctx - K - 1)      # the bound says: nearly full
+    ctx.spec_kv_restore(binding.DRAFT, lens, case.n_ctx)
+    ctx.spec_round(gi["pending"], gi["eps"], gi["r"], -1.0)
+    with pytest.raises(binding.FardError):                  # by the bound there is no room for another round
+        ctx.spec_round(gi["pending"], gi["eps"], gi["r"], -1.0)
+    ctx.spec_kv_lengths(binding.TARGET, B)                  # true lengths: n_ctx + 1 + n_accept
+    ctx.spec_kv_restore(binding.DRAFT, lens, case.n_ctx)
+    ctx.spec_round(gi["pending"], gi["eps"], gi["r"], -1.0)
+    ctx.sync()
+    ctx.close()
