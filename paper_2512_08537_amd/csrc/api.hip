@@ -197,6 +197,9 @@ struct HeadW {
   float *in_b = nullptr, *c_b = nullptr, *mod_b_all = nullptr, *out_b = nullptr, *temb = nullptr;
   std::vector<BlockW> B;
   int mod_n = 0;
+  // bf16 path: per block j the mod GEMM also yields c0_j = shift_j W1_j and c1_j = (1 + scale_j) W1_j (columns
+  // fold_base + 2 w j and + w), so that the block's modulated norm can be folded into its first GEMM; 0: not built
+  int fold_base = 0;
 };
 struct Prof {
   bool on = false;
@@ -248,6 +251,8 @@ struct fard_ctx {
   Prof prof;
   // workspace
   float *h = nullptr, *x_in = nullptr, *ent_heads = nullptr, *h_row = nullptr;
+  void* hv = nullptr;            // head: bf16 rows h (1 + scale of the next block), written by a block's second GEMM
+  float* hmom = nullptr;         // head: [rows][w / 16] (mean, centred squares) of h per 16-column tile
   void *u = nullptr, *qkv = nullptr, *ao = nullptr, *ff = nullptr, *z = nullptr, *ztmp = nullptr;
   RowMaps maps{};
   int *aux_row = nullptr, *row_ids = nullptr;
@@ -577,6 +582,14 @@ struct GemmExtra {
   const float* ln_cs = nullptr;
   float ln_eps = 0.f;
   int ln_rms = 0;
+  // modulated-norm fold (GemmArgs): producer side, consumer side
+  const float* copy_scale = nullptr;
+  int copy_ld = 0;
+  float* mom_out = nullptr;
+  int mom_ld = 0;
+  const float *ada_mom = nullptr, *ada_c1 = nullptr, *ada_c0 = nullptr;
+  int ada_mom_ld = 0, ada_ld = 0;
+  float ada_eps = 0.f;
 };
 
 hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, void* out, int ldo, int M,
@@ -588,6 +601,9 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
   if (ex) {
     if (!c->bf16 || !routes_narrow(M, N, K, epi)) return hipErrorInvalidValue;   // only the narrow kernel has them
     a.copy_bf16 = ex->copy_bf16; a.ln_cs = ex->ln_cs; a.ln_eps = ex->ln_eps; a.ln_rms = ex->ln_rms;
+    a.copy_scale = ex->copy_scale; a.copy_ld = ex->copy_ld; a.mom_out = ex->mom_out; a.mom_ld = ex->mom_ld;
+    a.ada_mom = ex->ada_mom; a.ada_mom_ld = ex->ada_mom_ld; a.ada_c1 = ex->ada_c1; a.ada_c0 = ex->ada_c0; a.ada_ld = ex->ada_ld;
+    a.ada_eps = ex->ada_eps;
   }
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
@@ -607,14 +623,32 @@ int load_head(fard_ctx* c, Loader& ld) {
   if ((rc = ld.vec("head.in.b", w, 0.f, false, &hw.in_b))) return rc;
   if ((rc = ld.gemm_weight({"head.c.w"}, hc.d_cond, {w}, false, &hw.c_w))) return rc;
   if ((rc = ld.vec("head.c.b", w, 0.f, false, &hw.c_b))) return rc;
-  // all modulation projections share their input silu(c): one wide GEMM [w, (3 Nb + 2) w]
+  // all modulation projections share their input silu(c): one wide GEMM [w, (3 Nb + 2) w]; on the bf16 path 2 Nb w
+  // more columns follow (fold_base), see below
+  const bool fold = c->bf16 && w % 64 == 0 && w <= 2048;
   std::vector<std::string> names;
   std::vector<int> Ns;
   for (int j = 0; j < Nb; ++j) { names.push_back("head.B" + std::to_string(j) + ".mod.w"); Ns.push_back(3 * w); }
   names.push_back("head.f.mod.w");
   Ns.push_back(2 * w);
-  hw.mod_n = (3 * Nb + 2) * w;
-  if ((rc = ld.gemm_weight(names, w, Ns, false, &hw.mod_all))) return rc;
+  const int base_n = (3 * Nb + 2) * w;
+  hw.mod_n = base_n + (fold ? 2 * Nb * w : 0);
+  hw.fold_base = fold ? base_n : 0;
+  if (!fold) {
+    if ((rc = ld.gemm_weight(names, w, Ns, false, &hw.mod_all))) return rc;
+  } else {
+    if ((rc = dalloc_bytes(c, &hw.mod_all, (size_t)w * hw.mod_n * c->esz))) return rc;
+    int col0 = 0;
+    for (size_t i = 0; i < names.size(); ++i) {
+      const fard_tensor* t;
+      if ((rc = ld.need(names[i], (int64_t)w * Ns[i], &t))) return rc;
+      const void* src;
+      if ((rc = ld.device_src(t, &src))) return rc;
+      HIPCHK(c, launch_pack_weight(c->stream, src, t->dtype == FARD_BF16, Ns[i], w, Ns[i], hw.mod_all, col0 / 32, 1));
+      col0 += Ns[i];
+      if (ld.staging.size() > 8) ld.release_staging();
+    }
+  }
   if ((rc = dalloc<float>(c, &hw.mod_b_all, hw.mod_n))) return rc;
   HIPCHK(c, launch_fill_f32(c->stream, hw.mod_b_all, 0.f, hw.mod_n));
   for (int j = 0; j <= Nb; ++j) {
@@ -635,6 +669,55 @@ int load_head(fard_ctx* c, Loader& ld) {
   }
   if ((rc = ld.table("head.out.w", (int64_t)w * D, &hw.out_w))) return rc;
   if ((rc = ld.vec("head.out.b", D, 0.f, false, &hw.out_b))) return rc;
+
+  if (fold) {
+    // The modulated norm of block j, a1 = LN(h)(1 + scale) + shift, times W1 with the row-wise factors outside the sum:
+    //   a1 W1 = rstd ((h (1 + scale)) W1 - mean (1 + scale) W1) + shift W1.
+    // (1 + scale) W1 and shift W1 are affine in the conditioning s = silu(c) like scale and shift themselves
+    // (scale = s Wsc + bsc): (1 + scale) W1 = s (Wsc W1) + (1 + bsc) W1, shift W1 = s (Wsh W1) + bsh W1.  The products
+    // Wsc W1 and Wsh W1 are formed here, once, and packed as further columns of the mod GEMM.
+    void *tmod = nullptr, *tw1 = nullptr, *tf = nullptr;
+    float *ones = nullptr, *tv = nullptr;
+    HIPCHK(c, hipMalloc(&tmod, (size_t)w * 3 * w * 2));
+    HIPCHK(c, hipMalloc(&tw1, (size_t)w * w * 2));
+    HIPCHK(c, hipMalloc(&tf, (size_t)w * w * 2));
+    HIPCHK(c, hipMalloc((void**)&ones, (size_t)w * 4));
+    HIPCHK(c, hipMalloc((void**)&tv, (size_t)w * 4));
+    HIPCHK(c, launch_fill_f32(c->stream, ones, 1.f, (size_t)w));
+    auto to_bf16 = [&](const std::string& name, int64_t numel, void* dst) -> int {
+      const fard_tensor* t;
+      int r = ld.need(name, numel, &t);
+      if (r) return r;
+      const void* src;
+      if ((r = ld.device_src(t, &src))) return r;
+      const unsigned blocks = (unsigned)std::min<size_t>(((size_t)numel + 255) / 256, 4096);
+      if (t->dtype == FARD_BF16) convert_kernel<bf16, bf16><<<blocks, 256, 0, c->stream>>>((const bf16*)src, (bf16*)dst, (size_t)numel);
+      else convert_kernel<float, bf16><<<blocks, 256, 0, c->stream>>>((const float*)src, (bf16*)dst, (size_t)numel);
+      HIPCHK(c, hipGetLastError());
+      return FARD_OK;
+    };
+    for (int j = 0; j < Nb && rc == FARD_OK; ++j) {
+      const std::string q = "head.B" + std::to_string(j) + ".";
+      if ((rc = to_bf16(q + "mod.w", (int64_t)w * 3 * w, tmod))) break;
+      if ((rc = to_bf16(q + "w1", (int64_t)w * w, tw1))) break;
+      float* bj = hw.mod_b_all + (size_t)3 * w * j;                      // shift, scale, gate biases of block j
+      float* fb = hw.mod_b_all + (size_t)hw.fold_base + (size_t)2 * w * j;   // c0, c1 biases
+      for (int which = 0; which < 2; ++which) {                          // 0: shift -> c0, 1: scale -> c1
+        GemmArgs a;
+        a.A = (const bf16*)tmod + (size_t)which * w; a.lda = 3 * w; a.W = hw.B[j].w1; a.bias = nullptr; a.out = tf; a.ldo = w;
+        a.gate = nullptr; a.ldg = 0; a.M = w; a.N = w; a.K = w; a.m_dev = nullptr; a.act = ACT_NONE; a.epi = EPI_STORE;
+        HIPCHK(c, launch_gemm_bf16(c->stream, a));
+        HIPCHK(c, launch_pack_weight(c->stream, tf, 1, w, w, w, hw.mod_all, (hw.fold_base + 2 * w * j + which * w) / 32, 1));
+        // bias row: bsh W1, or (1 + bsc) W1 = ones W1 + bsc W1
+        HIPCHK(c, launch_matvec(c->stream, 1, bj + (size_t)which * w, tw1, nullptr, w, w, ACT_NONE, which ? tv : fb));
+        if (which) HIPCHK(c, launch_matvec(c->stream, 1, ones, tw1, tv, w, w, ACT_NONE, fb + w));
+      }
+      ld.release_staging();
+    }
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipFree(tmod); (void)hipFree(tw1); (void)hipFree(tf); (void)hipFree(ones); (void)hipFree(tv);
+    if (rc) return rc;
+  }
 
   // time embedding of the S fixed sampler times t_k = 1 - k/S, computed once
   void *t1w, *t2w;
@@ -705,6 +788,8 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc_bytes(c, &c->sc, (size_t)g.head.n_steps * M * w * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->a1, (size_t)M * w * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->a2, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->hv, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc<float>(c, &c->hmom, (size_t)(w / 16 + 1) * M * 2))) return rc;
   if ((rc = dalloc<int>(c, &c->alive, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->act_idx, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->n_act, 4))) return rc;
@@ -970,18 +1055,41 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
   { Bracket br(c, CLS_OTHER);
     HIPCHK(c, launch_head_prep(s, c->bf16, eps, emap, hc.temperature, D, hw.in_w, hw.in_b, c->cz, hw.temb, S, c->hh, c->sc,
                                c->xt, w, n, n_dev)); }
+  // From the second block of a step on the modulated norm has no launch of its own when the rows are few (the launch
+  // is then the cost; measured: a gain up to 64 rows, none above): the gate-residual GEMM of block j - 1 leaves
+  // v = bf16(h (1 + scale_j)) and the tile moments of h, and block j's first GEMM multiplies v and applies mean, rstd,
+  // c1_j = (1 + scale_j) W1_j and c0_j = shift_j W1_j (columns fold_base.. of the mod GEMM, computed only then).
+  const bool fold = hw.fold_base > 0 && n <= 64 && routes_narrow(n, w, w, EPI_GATE_RESID) && routes_narrow(n, w, w, EPI_STORE) &&
+                    w / 32 <= 48;
   // the modulations of all S steps in one GEMM over S n rows (rows past the device-side count are unused)
-  HIPCHK(c, gemm(c, c->sc, w, hw.mod_all, hw.mod_b_all, c->mod, hw.mod_n, S * n, hw.mod_n, w, nullptr, EPI_STORE_F32, ACT_NONE));
+  const int mod_cols = fold ? hw.mod_n : (hw.fold_base > 0 ? hw.fold_base : hw.mod_n);
+  HIPCHK(c, gemm(c, c->sc, w, hw.mod_all, hw.mod_b_all, c->mod, hw.mod_n, S * n, mod_cols, w, nullptr, EPI_STORE_F32, ACT_NONE));
   for (int k = 0; k < S; ++k) {
     const float t = 1.0f - (float)k / (float)S;
     const float t_next = 1.0f - (float)(k + 1) / (float)S;
     const float* modk = c->mod + (size_t)k * n * hw.mod_n;
     for (int j = 0; j < Nb; ++j) {
       const float* mj = modk + (size_t)3 * w * j;
-      { Bracket br(c, CLS_OTHER);
-        HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1)); }
-      HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
-      HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n));
+      const bool folded = fold && j > 0;
+      if (!folded) {
+        { Bracket br(c, CLS_OTHER);
+          HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1)); }
+        HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
+      } else {
+        GemmExtra ex;
+        ex.ada_mom = c->hmom; ex.ada_mom_ld = w / 16;
+        ex.ada_c0 = modk + (size_t)hw.fold_base + (size_t)2 * w * j; ex.ada_c1 = ex.ada_c0 + w; ex.ada_ld = hw.mod_n;
+        ex.ada_eps = 1e-6f;
+        HIPCHK(c, gemm(c, c->hv, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU, nullptr, 0, &ex));
+      }
+      if (fold && j + 1 < Nb) {
+        GemmExtra ex;
+        ex.copy_bf16 = c->hv; ex.copy_scale = modk + (size_t)3 * w * (j + 1) + w; ex.copy_ld = hw.mod_n;
+        ex.mom_out = c->hmom; ex.mom_ld = w / 16;
+        HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n, &ex));
+      } else {
+        HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n));
+      }
     }
     HeadStepArgs a;
     a.hh = c->hh; a.w = w;

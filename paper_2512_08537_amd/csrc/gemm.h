@@ -38,6 +38,23 @@ struct GemmArgs {
                                    // and bias = b0 + beta W0 folded by the caller; statistics come from the A fragments
   float ln_eps = 0.f;
   int ln_rms = 0;                  // 1: RMS norm (no mean)
+  // A modulated LayerNorm between two GEMMs without a launch of its own (the head's AdaLN blocks, Sec. 3.2):
+  // the GEMM that updates the rows h (EPI_RESID / EPI_GATE_RESID) also writes v = bf16(h (1 + copy_scale)) to
+  // copy_bf16 and, per row and 16-column tile, the tile's mean and centred sum of squares to mom_out;
+  const float* copy_scale = nullptr;   // [M, copy_ld] fp32: scale of the norm that follows
+  int copy_ld = 0;
+  float* mom_out = nullptr;            // [M][mom_ld >= N / 16] pairs (mean, sum of squares about it), a row's tiles side by side
+  int mom_ld = 0;
+  // the next GEMM multiplies v and finishes, with the rows' mean_r and rstd_r merged from the tile moments,
+  //   out[r, n] = act(rstd_r (acc[r, n] - mean_r c1[r, n]) + c0[r, n] + bias[n]),
+  // c1[r, :] = (1 + scale_r) W and c0[r, :] = shift_r W supplied by the caller:
+  //   LN(h)(1 + scale) + shift times W, with the row-wise factors taken out of the sum over k.
+  const float* ada_mom = nullptr;      // [M][ada_mom_ld >= K / 16] pairs, as written through mom_out
+  int ada_mom_ld = 0;
+  const float* ada_c1 = nullptr;       // [M, ada_ld] fp32
+  const float* ada_c0 = nullptr;
+  int ada_ld = 0;
+  float ada_eps = 0.f;
 };
 
 // Packed bf16 weight size in elements for a [K, N] matrix (K % 16 == 0, N % 32 == 0).

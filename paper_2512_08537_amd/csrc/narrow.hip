@@ -30,13 +30,20 @@ namespace {
 // 4 columns and walks the rows.  The operands that do not depend on the product (gate, old value of a
 // read-modify-write target, bias) are requested by prefetch() at kernel start; finish() adds the 4 waves'
 // partial tiles through LDS and writes 8-16 bytes per thread.
-template <int MT, int NT>
+// ADA: the kernel instance carries the operands of the modulated-norm fold (GemmArgs::ada_*, copy_scale, mom_out);
+// the other instances keep their register budget.
+template <int MT, int NT, bool ADA>
 struct NarrowEpi {
   static constexpr int CG = 4 * NT;                        // 4-column groups per row
   static constexpr int RPP = 256 / CG;                     // rows per pass
   static constexpr int EP = (16 * MT + RPP - 1) / RPP;     // passes
   static constexpr int LDT = 16 * NT + 4;                  // floats per row of a partial tile in LDS
+  static constexpr int ROWS = 16 * MT;                     // rows of the tile
+  static constexpr int TPR = 256 / ROWS;                   // threads that share a row's tile moments (16 or 8 consecutive lanes)
+  static constexpr int MOMT = 128 / TPR;                   // tile moments per thread: K <= 2048
   f32x4 gate[EP], old[EP], bias4, cs4;
+  f32x4 c1[ADA ? EP : 1], c0[ADA ? EP : 1], vs[ADA ? EP : 1];   // modulated-norm fold (ada_*); scale of the bf16 copy
+  float mom_m[ADA ? MOMT : 1], mom_q[ADA ? MOMT : 1], mom_pivot;   // this thread's share of its row's tile moments
   int er, ec;
   __device__ __forceinline__ void prefetch(const GemmArgs& a, int M, int m0, int n0) {
     er = threadIdx.x / CG;
@@ -55,11 +62,73 @@ struct NarrowEpi {
     if (a.bias != nullptr && blockIdx.z == 0) bias4 = *(const f32x4*)(a.bias + n0 + ec);
     cs4 = f32x4{0.f, 0.f, 0.f, 0.f};
     if (a.ln_cs != nullptr) cs4 = *(const f32x4*)(a.ln_cs + n0 + ec);
+    if constexpr (ADA) {
+    if (a.ada_mom != nullptr || a.copy_scale != nullptr) {
+#pragma unroll
+      for (int i = 0; i < EP; ++i) {
+        int r = m0 + er + RPP * i;
+        r = r < M ? r : M - 1;
+        if (a.ada_mom != nullptr) {
+          c1[i] = *(const f32x4*)(a.ada_c1 + (size_t)r * a.ada_ld + n0 + ec);
+          c0[i] = *(const f32x4*)(a.ada_c0 + (size_t)r * a.ada_ld + n0 + ec);
+        }
+        if (a.copy_scale != nullptr) vs[i] = *(const f32x4*)(a.copy_scale + (size_t)r * a.copy_ld + n0 + ec);
+      }
+    }
+    if (a.ada_mom != nullptr) {
+      // (mean, centred sum of squares) of every 16-column tile of the rows, left by the GEMM that wrote them:
+      // thread t of the TPR that share row tid / TPR takes tiles t, t + TPR, ...
+      int r = m0 + (int)threadIdx.x / TPR;
+      r = r < M ? r : M - 1;
+      const int n_tiles = a.K >> 4, t0 = threadIdx.x % TPR;
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      const f32x2* mp = (const f32x2*)a.ada_mom + (size_t)r * a.ada_mom_ld;   // the row's tiles are consecutive pairs
+      mom_pivot = mp[0][0];
+#pragma unroll
+      for (int i = 0; i < MOMT; ++i) {
+        const int tile = t0 + TPR * i;
+        const f32x2 q = mp[tile < n_tiles ? tile : 0];
+        mom_m[i] = q[0];
+        mom_q[i] = q[1];
+      }
+    }
+    }
+  }
+  // mean and 1 / std of the tile's rows from the tile moments (pairwise update of Chan et al. for equal counts, about
+  // the first tile's mean as pivot), into rowstat[row] = {mean, rstd}; all threads, before the epilogue's barrier
+  __device__ __forceinline__ void row_stats(const GemmArgs& a, float* rowstat) {
+    const int n_tiles = a.K >> 4, t0 = threadIdx.x % TPR;
+    float sd = 0.f, sd2 = 0.f, sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < MOMT; ++i) {
+      if (t0 + TPR * i < n_tiles) {
+        const float d = mom_m[i] - mom_pivot;
+        sd += d;
+        sd2 = fmaf(d, d, sd2);
+        sq += mom_q[i];
+      }
+    }
+    auto red = [](float v) {
+      v += dpp_move<DPP_SWAP1>(v);
+      v += dpp_move<DPP_SWAP2>(v);
+      v += dpp_move<DPP_HALF_MIRROR>(v);
+      if (TPR == 16) v += dpp_move<DPP_MIRROR>(v);
+      return v;
+    };
+    sd = red(sd); sd2 = red(sd2); sq = red(sq);
+    if (t0 == 0) {
+      const float inv_t = 1.0f / (float)n_tiles;
+      const float mean = mom_pivot + sd * inv_t;
+      const float m2 = sq + 16.0f * fmaxf(sd2 - sd * sd * inv_t, 0.f);
+      const int row = threadIdx.x / TPR;
+      rowstat[row * 2] = mean;
+      rowstat[row * 2 + 1] = 1.0f / sqrtf(m2 / (float)a.K + a.ada_eps);
+    }
   }
   // LNF: stat holds the 4 waves' (sum x, sum x^2) of every row of the tile, over their shares of K
   template <bool LNF>
-  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT][NT], float* red, const float* stat, int M,
-                                         int m0, int n0) {
+  __device__ __forceinline__ void finish(const GemmArgs& a, const f32x4 (&acc)[MT][NT], float* red, const float* stat,
+                                         float* rowstat, int M, int m0, int n0) {
     const int lane = threadIdx.x & 63, kw = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
@@ -68,6 +137,7 @@ struct NarrowEpi {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
           red[(kw * 16 * MT + 16 * i + 4 * (lane >> 4) + e) * LDT + 16 * j + (lane & 15)] = acc[i][j][e];
+    if constexpr (ADA) { if (a.ada_mom != nullptr) row_stats(a, rowstat); }
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < EP; ++i) {
@@ -89,6 +159,7 @@ struct NarrowEpi {
         const float rstd = rsqrtf(var + a.ln_eps);
         v = (v - cs4 * mean) * rstd;
       }
+      if constexpr (ADA) { if (a.ada_mom != nullptr) v = (v - c1[i] * rowstat[row * 2]) * rowstat[row * 2 + 1] + c0[i]; }
       v += bias4;
       const size_t o = (size_t)(m0 + row) * a.ldo + n0 + ec;
       if (a.epi == EPI_STORE) {
@@ -107,9 +178,31 @@ struct NarrowEpi {
         *(f32x4*)((float*)a.out + o) = nv;
         if (a.copy_bf16 != nullptr) {
           bf16x4 t;
+          if (ADA && a.copy_scale != nullptr) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) t[e] = (bf16)nv[e];
+            for (int e = 0; e < 4; ++e) t[e] = (bf16)(nv[e] * (1.0f + vs[ADA ? i : 0][e]));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = (bf16)nv[e];
+          }
           *(bf16x4*)((bf16*)a.copy_bf16 + o) = t;
+        }
+        if (ADA && a.mom_out != nullptr) {
+          // moments of the updated row over this 16-column tile: its 4 threads are one quad of lanes (the quad
+          // shares the row, so it is whole or skipped as one)
+          float sm = (nv[0] + nv[1]) + (nv[2] + nv[3]);
+          sm += dpp_move<DPP_SWAP1>(sm);
+          sm += dpp_move<DPP_SWAP2>(sm);
+          const float mean = sm * (1.0f / 16.0f);
+          float q = 0.f;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { const float d = nv[e] - mean; q = fmaf(d, d, q); }
+          q += dpp_move<DPP_SWAP1>(q);
+          q += dpp_move<DPP_SWAP2>(q);
+          if ((threadIdx.x & 3) == 0) {
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            *((f32x2*)a.mom_out + (size_t)(m0 + row) * a.mom_ld + ((n0 + ec) >> 4)) = f32x2{mean, q};
+          }
         }
       }
     }
@@ -120,11 +213,11 @@ struct NarrowEpi {
 // flight (its whole K range when ONESHOT).
 // LNF: the norm of the rows is applied in the epilogue (GemmArgs::ln_cs); the row statistics are summed from the
 // activation fragments on their way into the MFMAs.
-template <int MT, int NT, int NS, bool ONESHOT, bool LNF>
-__global__ __launch_bounds__(256, (LNF && NS == 8) ? 2 : 1) void gemm_narrow_kernel(GemmArgs a) {   // (the statistics must
+template <int MT, int NT, int NS, bool ONESHOT, bool LNF, bool ADA>
+__global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_narrow_kernel(GemmArgs a) {   // (the statistics must
   // not cost the 32 x 64 tile its second workgroup per compute unit: 16 registers over the limit otherwise)
-  using Epi = NarrowEpi<MT, NT>;
-  extern __shared__ __attribute__((aligned(16))) float red[];   // 4 * 16 * MT * Epi::LDT floats (+ 4 * 16 * MT * 2 if LNF)
+  using Epi = NarrowEpi<MT, NT, ADA>;
+  extern __shared__ __attribute__((aligned(16))) float red[];   // 4 * 16 * MT * Epi::LDT floats (+ 4 * 16 * MT * 2 if LNF) + 16 * MT * 2
   const int M = eff_rows(a.M, a.m_dev);
   const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
   if (m0 >= M) return;
@@ -218,6 +311,7 @@ __global__ __launch_bounds__(256, (LNF && NS == 8) ? 2 : 1) void gemm_narrow_ker
   }
 
   float* stat = red + 4 * 16 * MT * Epi::LDT;
+  float* rowstat = stat + (LNF ? 4 * 16 * MT * 2 : 0);
   if constexpr (LNF) {
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
@@ -229,7 +323,7 @@ __global__ __launch_bounds__(256, (LNF && NS == 8) ? 2 : 1) void gemm_narrow_ker
       }
     }
   }
-  epi.template finish<LNF>(a, acc, red, stat, M, m0, n0);
+  epi.template finish<LNF>(a, acc, red, stat, rowstat, M, m0, n0);
 }
 
 }  // namespace
@@ -238,6 +332,11 @@ bool narrow_supported(const GemmArgs& a) {
   if (a.epi == EPI_PARTIAL && (a.k_slices < 1 || a.k_slices > 64 || (a.k_slices > 1 && a.part_stride < (size_t)a.M * a.ldo))) return false;
   if (a.ln_cs != nullptr && (a.epi == EPI_PARTIAL || a.k_slices > 1)) return false;
   if (a.copy_bf16 != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
+  if (a.copy_scale != nullptr && a.copy_bf16 == nullptr) return false;
+  if (a.mom_out != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
+  if (a.ada_mom != nullptr && ((a.epi != EPI_STORE && a.epi != EPI_STORE_F32) || a.ln_cs != nullptr || a.K > 2048 ||
+                               a.ada_c1 == nullptr || a.ada_c0 == nullptr))
+    return false;
   return a.M >= 1 && a.N % 32 == 0 && a.K % 64 == 0 && a.epi != EPI_SWIGLU;
 }
 
@@ -247,24 +346,33 @@ hipError_t launch_gemm_narrow(hipStream_t s, const GemmArgs& a) {
   const int steps = ((a.K / 32 + kz - 1) / kz + 3) / 4;      // 32-k steps of the busiest wave
   // rows beyond one workgroup's tile go to further workgroups (blockIdx.y) that re-read the weight columns
   // out of L2: ids of one column tile differ by a multiple of 8, so they share an XCD when N % 128 == 0
-#define FARD_NR_L(MTV, NTV, NSV, ONE, LNFV)                                                                \
+#define FARD_NR_L(MTV, NTV, NSV, ONE, LNFV, ADAV)                                                          \
   do {                                                                                                     \
-    constexpr size_t lds = (size_t)4 * 16 * MTV * (16 * NTV + 4 + (LNFV ? 2 : 0)) * sizeof(float);         \
+    constexpr size_t lds = ((size_t)4 * 16 * MTV * (16 * NTV + 4 + (LNFV ? 2 : 0)) + 16 * MTV * 2) * sizeof(float); \
     if constexpr (lds > 64 * 1024) {                                                                       \
       static bool attr_set = false;                                                                        \
       if (!attr_set) {                                                                                     \
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_narrow_kernel<MTV, NTV, NSV, ONE, LNFV>,      \
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_narrow_kernel<MTV, NTV, NSV, ONE, LNFV, ADAV>, \
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
         if (e != hipSuccess) return e;                                                                     \
         attr_set = true;                                                                                   \
       }                                                                                                    \
     }                                                                                                      \
-    gemm_narrow_kernel<MTV, NTV, NSV, ONE, LNFV><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV), kz), 256, lds, s>>>(a); \
+    gemm_narrow_kernel<MTV, NTV, NSV, ONE, LNFV, ADAV><<<dim3(a.N / (16 * NTV), (a.M + 16 * MTV - 1) / (16 * MTV), kz), 256, lds, s>>>(a); \
   } while (0)
+  // the modulated-norm fold: the tile shapes the head's GEMMs take (K = N <= 1536)
+  if (a.ada_mom != nullptr || a.mom_out != nullptr || a.copy_scale != nullptr) {
+    if (a.ln_cs != nullptr || steps > 12) return hipErrorInvalidValue;
+    if (a.M <= 64) { if (steps <= 8) FARD_NR_L(1, 1, 8, true, false, true); else FARD_NR_L(1, 1, 12, true, false, true); }
+    else if (steps <= 8 && a.N % 64 == 0) FARD_NR_L(2, 4, 8, true, false, true);
+    else if (steps <= 8) FARD_NR_L(2, 2, 8, true, false, true);
+    else FARD_NR_L(2, 2, 12, true, false, true);
+    return hipGetLastError();
+  }
 #define FARD_NR(MTV, NTV, NSV, ONE)                      \
   do {                                                   \
-    if (a.ln_cs != nullptr) FARD_NR_L(MTV, NTV, NSV, ONE, true); \
-    else FARD_NR_L(MTV, NTV, NSV, ONE, false);           \
+    if (a.ln_cs != nullptr) FARD_NR_L(MTV, NTV, NSV, ONE, true, false); \
+    else FARD_NR_L(MTV, NTV, NSV, ONE, false, false);    \
   } while (0)
   if (a.M <= 64) {
     // a few dozen rows: 16-row workgroups (more of them, half the activation bytes each) measured ahead of
