@@ -675,11 +675,10 @@ hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
   const bool resid = (a.epi == EPI_RESID || a.epi == EPI_GATE_RESID);
   if constexpr (WM == 3) {
     // a few hundred rows, full-K store epilogue: 64-row streaming tiles when they waste fewer rows than 96-row ones
-    // or the 96-row grid would leave compute units idle (measured over whole rounds: 9.83 -> 9.24 ms at 576 rows,
-    // 29.4 -> 29.0 ms with 256-row draft steps, against the resident-activation kernel and the 96-row tiles)
+    // (measured over whole rounds against the resident-activation kernel: 29.4 -> 29.0 ms with 256-row draft steps)
     if (!resid && a.epi != EPI_SWIGLU && a.M > 96 && a.M <= 640) {
       const int m64 = (a.M + 63) / 64, m96 = (a.M + 95) / 96;
-      if (m64 * 64 < m96 * 96 || m96 * ((a.N + 127) / 128) < 256) return launch_cfg<2, 1, 1, 16, 256>(s, a, 1);
+      if (m64 * 64 < m96 * 96) return launch_cfg<2, 1, 1, 8, 256>(s, a, 1);
     }
     // 65-96 rows with a SwiGLU epilogue: one 96-row tile of the streaming kernel, two waves per 64 packed columns sharing
     // the k-steps (measured at 72 x 27648 x 5120: 62 us against 78 us for two 64-row tiles of the resident-activation
@@ -701,11 +700,29 @@ hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
   const int total_chunks = (a.K + KC - 1) / KC;
   auto tiles = [&](int bn) { return ((a.N + bn - 1) / bn) * m_tiles; };
   auto splits_for = [&](int t) { return (resid && t < 256) ? (256 + t - 1) / t : 1; };
-  if (tiles(256) >= 512) return launch_cfg<WM, 2, 1, 16, 256>(s, a, 1);                // plenty of wide tiles: one wave per SIMD, so the
-  // weight ring is what hides the memory latency (16 k-steps deep: 6144 x 13824 x 5120 in 1.01 ms against 1.33 ms with 8; 32 spill)
+  if constexpr (WM >= 3) {
+    // Hundreds to thousands of rows: MFMA-bound tiles, many per compute unit.  An 8-step weight ring (not 16) keeps
+    // 64x256, 64x128 and 96x128 tiles within 256 registers, so two workgroups share a compute unit and one's epilogue
+    // and ramp overlap the other's MFMA loop; measured over the verify and prefill shapes (TFLOP/s, 16-step ring of
+    // the same or the previously routed tile -> 8-step): 6144 x 7168 x 5120 966 -> 1184 and 6144 x 5120 x 5120
+    // 804 -> 1062 (64x256), 6144 x 5120 x 13824 953 -> 1064 (128x128), SwiGLU 6144 x 27648 x 5120 1176 -> 1255
+    // (128x256), 8256 x 5120 x 1280 624 -> 890, 4128 x 3072 x 1024 447 -> 761 and 2304 x 5120 x 1280 685 -> 807
+    // (64x128), 576 x 5120 x 1280 442 -> 540 (96x128).
+    auto t = [&](int bm, int bn) { return ((a.N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
+    if (a.epi == EPI_SWIGLU) {
+      if (tiles(256) >= 512) return launch_cfg<4, 2, 1, 8, 256>(s, a, 1);
+    } else if (!resid || t(64, 128) >= 512 || (t(64, 128) >= 256 && a.K <= 2048)) {
+      // (a residual epilogue with few tiles or a long K keeps the K split over workgroups below)
+      if (a.K > 8192 && t(128, 128) >= 512) return launch_cfg<4, 1, 1, 8, 256>(s, a, 1);
+      if (t(64, 256) >= 900) return launch_cfg<2, 2, 1, 8, 256>(s, a, 1);
+      if (t(64, 128) >= 400) return launch_cfg<2, 1, 1, 8, 256>(s, a, 1);
+      if (!resid) return launch_cfg<3, 1, 1, 8, 256>(s, a, 1);
+    }
+  }
+  if (tiles(256) >= 512) return launch_cfg<WM, 2, 1, 16, 256>(s, a, 1);
   if (a.epi != EPI_SWIGLU && tiles(128) * (resid ? total_chunks : 1) >= 256)
-    return launch_cfg<WM, 1, 1, 16, 256>(s, a, splits_for(tiles(128)));
-  if (WM > 1 && a.epi != EPI_SWIGLU) return launch_cfg<WM, 1, 1, 16, 256>(s, a, splits_for(tiles(128)));
+    return launch_cfg<WM, 1, 1, WM >= 3 ? 8 : 16, 256>(s, a, splits_for(tiles(128)));
+  if (WM > 1 && a.epi != EPI_SWIGLU) return launch_cfg<WM, 1, 1, WM >= 3 ? 8 : 16, 256>(s, a, splits_for(tiles(128)));
   if (a.epi == EPI_SWIGLU || tiles(64) >= 192) return launch_cfg<WM, 2, 4, 8, 256>(s, a, splits_for(tiles(64)));
   return launch_cfg<WM, 1, 4, 8, 256>(s, a, splits_for(tiles(32)));
 }
