@@ -234,13 +234,27 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
     }
   }
   if (n_parts > 0) {
-    // deferred residual update: the preceding GEMM left K-slice partial sums; fold them in (and write the row back)
+    // deferred residual update: the preceding GEMM left K-slice partial sums; fold them in (and write the row back).
+    // Four planes at a time, all their loads requested before the first is added: plane by plane the kernel waited for
+    // memory once per plane (10-14 us for a 5120-wide row with 5 planes).
     const size_t ro = (size_t)(in_map ? in_map[r] : r) * d;
+    for (int p0 = 0; p0 < n_parts; p0 += 4) {
+      f32x4 t[4][VPT];
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) {
-      const int c4 = threadIdx.x + i * 256;
-      if (c4 < n4) {
-        for (int p = 0; p < n_parts; ++p) x[i] += *(const f32x4*)(parts + (size_t)p * part_stride + ro + c4 * 4);
+      for (int q = 0; q < 4; ++q) {
+        const int p = p0 + q < n_parts ? p0 + q : n_parts - 1;
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+          const int c4 = threadIdx.x + i * 256;
+          t[q][i] = *(const f32x4*)(parts + (size_t)p * part_stride + ro + (c4 < n4 ? c4 : 0) * 4);
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (p0 + q < n_parts) {
+#pragma unroll
+          for (int i = 0; i < VPT; ++i) x[i] += t[q][i];
+        }
       }
     }
   }
@@ -977,15 +991,18 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
     sh[i] = ok ? ((const f32x4*)shp)[c4] : z4;
   }
   // Operands of the later phases (output projection, sampler update, next step's input projection) are requested
-  // here, before the first barrier, when they fit in registers (bf16, D = 16, w <= 1024): the kernel then waits
+  // here, before the first barrier, when they fit in registers (bf16, D = 16, w <= 2048): the kernel then waits
   // for memory once instead of once per phase.
   constexpr bool CAN_PRE = sizeof(T) == 2;
-  const bool pre = CAN_PRE && D == 16 && w <= 1024;
+  constexpr int NJ = 4 * HO_VPT;                          // columns per thread of the next step's input projection
+  const bool pre = CAN_PRE && D == 16 && w <= 256 * NJ;
   const T* W = (const T*)a.w_out;
   const T* w_in = (const T*)a.w_in;
   bf16x8 wq[HO_VPT][4][2];
-  T wvn[4][16];
-  float bjn[4] = {0.f, 0.f, 0.f, 0.f};
+  T wvn[NJ][16];
+  float bjn[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) bjn[j] = 0.f;
   float p_xt = 0.f, p_eps = 0.f, p_bout = 0.f;
   size_t p_oi = 0;
   if constexpr (CAN_PRE) {
@@ -1008,7 +1025,7 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
       }
       if (!a.last) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NJ; ++j) {
           const int c = ((int)threadIdx.x + 256 * j < w) ? (int)threadIdx.x + 256 * j : (int)threadIdx.x;
           bjn[j] = a.b_in[c];
 #pragma unroll
@@ -1087,7 +1104,7 @@ __global__ __launch_bounds__(256) void head_out_kernel(HeadStepArgs a) {
   // input projection of the next step
   if (CAN_PRE && pre) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int c = threadIdx.x + 256 * j;
       if (c >= w) continue;
       float v = bjn[j];
