@@ -313,22 +313,33 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnSplit sp, int n_hea
   for (long idx = (long)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (long)gridDim.x * 256) {
     const int d8 = (int)(idx % d8n);
     const long rh = idx / d8n;                             // row * n_heads + head
+    // every split's triple and output piece are requested before the first is used (split by split the kernel waited
+    // for memory once per split)
+    constexpr int NS = 8;                                  // sp.n <= 8 (checked at launch)
+    f32x4 t[NS], lo[NS], hi[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const size_t slot = (size_t)(s < sp.n ? s : 0) * sp.rows * n_heads + rh;
+      t[s] = *(const f32x4*)(sp.mla + slot * 4);
+      lo[s] = *(const f32x4*)(sp.o + slot * dh + d8 * 8);
+      hi[s] = *(const f32x4*)(sp.o + slot * dh + d8 * 8 + 4);
+    }
     float mstar = -INFINITY;
-    for (int s = 0; s < sp.n; ++s) mstar = fmaxf(mstar, sp.mla[((size_t)s * sp.rows * n_heads + rh) * 4]);
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      if (s < sp.n) mstar = fmaxf(mstar, t[s][0]);
     float lstar = 0.f, astar = 0.f;
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int s = 0; s < sp.n; ++s) {
-      const size_t slot = (size_t)s * sp.rows * n_heads + rh;
-      const f32x4 t = *(const f32x4*)(sp.mla + slot * 4);
-      if (t[0] == -INFINITY) continue;                     // a split that saw no visible key
-      const float dl = t[0] - mstar, f = __expf(dl);
-      lstar += f * t[1];
-      astar += f * (t[2] + dl * t[1]);
-      const f32x4 lo = *(const f32x4*)(sp.o + slot * dh + d8 * 8), hi = *(const f32x4*)(sp.o + slot * dh + d8 * 8 + 4);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { acc[i] += f * lo[i]; acc[4 + i] += f * hi[i]; }
+    for (int s = 0; s < NS; ++s) {
+      if (s >= sp.n || t[s][0] == -INFINITY) continue;     // (a split that saw no visible key)
+      const float dl = t[s][0] - mstar, f = __expf(dl);
+      lstar += f * t[s][1];
+      astar += f * (t[s][2] + dl * t[s][1]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { acc[i] += f * lo[s][i]; acc[4 + i] += f * hi[s][i]; }
     }
     const float inv = 1.0f / lstar;
     const int row = (int)(rh / n_heads), head = (int)(rh - (long)row * n_heads);
@@ -414,7 +425,8 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
   AttnSplit sp{};
   sp.n = 1;
   if (split != nullptr && split->n > 1) {
-    if (append || n_pass != 1 || split->o == nullptr || split->mla == nullptr || M > split->rows || M < 1) return hipErrorInvalidValue;
+    if (append || n_pass != 1 || split->o == nullptr || split->mla == nullptr || M > split->rows || M < 1 || split->n > 8)
+      return hipErrorInvalidValue;                          // (the merge kernel holds at most 8 splits in registers)
     sp = *split;
   }
   const dim3 grid(B * kv.n_kv_heads, n_pass, sp.n);
