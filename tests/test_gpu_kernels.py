@@ -327,6 +327,28 @@ def test_diffhead_decode_matches_oracle(fix, request):
     assert not mu2.cpu().numpy()[4:].any()
 
 
+@pytest.mark.parametrize("shift,n", [(2.0, 11), (4.0, 15), (8.0, 7)])   # in units of the rows' standard deviation (about 0.1)
+def test_diffhead_decode_with_rows_far_from_zero_mean(shift, n):
+    """The head's residual rows get a mean of `shift` standard deviations (bias of the input projection): from the
+    second block of a step on the modulated norm is folded into the block's first GEMM (up to 64 rows), which
+    subtracts mean x (1 + scale) W1 from a product of rounded rows."""
+    from oracle import head as ohd
+    case = build_case("ln-gelu-bf16", seed=5)
+    rc = case.rc
+    w = rc.head.width
+    case.W["head.in.b"] = gen.bf16_round((np.asarray(case.W["head.in.b"], dtype=np.float32) + 0.1 * shift).astype(np.float32))
+    ctx = make_ctx(case)
+    D, S = rc.head.d_latent, rc.head.n_steps
+    z = gen.normal(12, "zs", (n, rc.head.d_cond), 1.0, rc.dtype)
+    eps = gen.noise(12, "es", (S + 1, n, D))
+    mu, x = ctx.diffhead_decode(ctx.dev_store(z), ctx.dev_f32(eps))
+    ctx.sync()
+    mu_o, x_o = ohd.decode(rc.head, case.W, z, eps)
+    assert rel_inf(mu.cpu().numpy(), mu_o) < 2e-2
+    assert rel_inf(x.cpu().numpy(), x_o) < 2e-2
+    ctx.close()
+
+
 def test_head_closed_form_zero_weights():
     """All head weights zero except the output bias: mu = temperature*eps0 - b_out (1 step)."""
     case = build_case("ln-gelu-bf16", seed=1)
