@@ -569,8 +569,9 @@ bool routes_narrow(int M, int N, int K, int epi) {
   // a few dozen rows against a weight matrix that 16-column tiles spread over enough workgroups: the
   // narrow-tile kernel finishes in one memory round trip
   if (M <= 64 && K <= 2048 && N <= 8192) return true;
-  // a few hundred rows against a small square-ish matrix: still ahead of the split-K kernels (measured)
-  if (M <= 640 && K <= 1536 && N <= 1536) return true;
+  // up to about 300 rows against a small square-ish matrix: still ahead of the streaming kernel's 32-row tiles
+  // (measured at 288 x 1024 x 1024: 6.0-6.4 us against 6.2-6.9; at 576 x 1280 x 1280 13 us against 8-9)
+  if (M <= 320 && K <= 1536 && N <= 1536) return true;
   // ... or a wide one with a store epilogue, through 64-column workgroups
   if (M <= 640 && K <= 1024 && N <= 8192 && N % 64 == 0 && (epi == EPI_STORE || epi == EPI_STORE_F32)) return true;
   return false;

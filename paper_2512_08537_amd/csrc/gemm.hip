@@ -709,6 +709,15 @@ hipError_t launch_wm(hipStream_t s, const GemmArgs& a) {
     // (128x256), 8256 x 5120 x 1280 624 -> 890, 4128 x 3072 x 1024 447 -> 761 and 2304 x 5120 x 1280 685 -> 807
     // (64x128), 576 x 5120 x 1280 442 -> 540 (96x128).
     auto t = [&](int bm, int bn) { return ((a.N + bn - 1) / bn) * ((a.M + bm - 1) / bm); };
+    // A few hundred rows against a matrix whose 96-row tiles would leave half the chip idle: 32 x 128 tiles (136
+    // registers: three workgroups per compute unit), for residual epilogues with K split over enough workgroups to
+    // cover the chip (measured: 288 x 3072 x 1024 11.9 -> 7.4 us, 576 x 1280 x 1280 15.8 -> 8.9 us with 2 splits,
+    // 288 x 1024 x 4096 13.9 -> 10.8-11.1 us, 576 x 1280 x 5120 22.3 -> 18.8 us)
+    if (a.epi != EPI_SWIGLU && a.M > 96 && t(96, 128) < 128 && t(32, 128) >= 64) {
+      int sp = 1;
+      if (resid) sp = std::min(std::max((256 + t(32, 128) - 1) / t(32, 128), 1), std::min(total_chunks, 4));
+      return launch_cfg<1, 1, 1, 8, 256>(s, a, sp);
+    }
     if (a.epi == EPI_SWIGLU) {
       if (tiles(256) >= 512) return launch_cfg<4, 2, 1, 8, 256>(s, a, 1);
     } else if (!resid || t(64, 128) >= 512 || (t(64, 128) >= 256 && a.K <= 2048)) {
