@@ -39,11 +39,12 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
-  // merge area: one slab of partial O^T per wave when the four fit (SLABS), else one shared accumulator
-  constexpr bool SLABS = 4 * DH * (NCOL + 1) * 4 <= 40 * 1024;
-  constexpr int OLD = SLABS ? NCOL + 1 : NCOL;             // padded row: conflict-free column-major reads
+  // merge area: one slab of partial O^T per wave (4 DH (NCOL + 1) floats of dynamic LDS: 17-133 KB), so that the
+  // four waves meet behind one barrier; with one shared accumulator and a read-modify-write round per wave the merge was
+  // 5.3 us of a 15.8 us launch at DH = 128 with 64 columns
+  constexpr int OLD = NCOL + 1;                            // padded row: conflict-free column-major reads
   __shared__ float s_m[4][NCOL], s_l[4][NCOL], s_a[4][NCOL];
-  __shared__ float s_o[(SLABS ? 4 : 1) * DH * OLD];
+  extern __shared__ __attribute__((aligned(16))) float s_o[];
 
   const int Hk = kv.n_kv_heads;
   const int G = n_heads / Hk;
@@ -211,9 +212,6 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
       s_a[wave][cl + 32 * qb] = a_run[qb];
     }
   }
-  if constexpr (!SLABS) {
-    for (int i = tid; i < DH * NCOL; i += 256) s_o[i] = 0.f;
-  }
   __syncthreads();
   float f_me[NQB];
 #pragma unroll
@@ -223,35 +221,18 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
     for (int w = 0; w < 4; ++w) mstar = fmaxf(mstar, s_m[w][c]);
     f_me[qb] = (m_run[qb] == -INFINITY) ? 0.f : __expf(m_run[qb] - mstar);
   }
-  if constexpr (SLABS) {
-    // every wave lays its rescaled partial O^T down in its own slab: one barrier, no read-modify-write rounds
-    float* slab = s_o + (size_t)wave * DH * OLD;
+  // every wave lays its rescaled partial O^T down in its own slab: one barrier, no read-modify-write rounds
+  float* slab = s_o + (size_t)wave * DH * OLD;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
+  for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
-          slab[dim * OLD + cl + 32 * qb] = o[db][qb][e] * f_me[qb];
-        }
-    __syncthreads();
-  } else {
-    for (int w = 0; w < 4; ++w) {
-      if (wave == w) {
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
-              s_o[dim * OLD + cl + 32 * qb] += o[db][qb][e] * f_me[qb];
-            }
+      for (int e = 0; e < 16; ++e) {
+        const int dim = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);   // O^T row
+        slab[dim * OLD + cl + 32 * qb] = o[db][qb][e] * f_me[qb];
       }
-      __syncthreads();
-    }
-  }
+  __syncthreads();
   // ---- normalise and write: thread -> (column, 8 consecutive dims)
   constexpr int D8 = DH / 8;
   for (int idx = tid; idx < NCOL * D8; idx += 256) {
@@ -277,10 +258,8 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         float acc = s_o[(d8 * 8 + i) * OLD + c];
-        if constexpr (SLABS) {
 #pragma unroll
-          for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
-        }
+        for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
         if (i < 4) lo[i] = acc; else hi[i - 4] = acc;
       }
       *(f32x4*)(sp.o + slot * DH + d8 * 8) = lo;
@@ -293,10 +272,8 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float acc = s_o[(d8 * 8 + i) * OLD + c];
-      if constexpr (SLABS) {
 #pragma unroll
-        for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
-      }
+      for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
       v[i] = (bf16)(acc * inv);
     }
     *(bf16x8*)(out + (size_t)(r0 + j) * ldo + (size_t)head * DH + d8 * 8) = v;
@@ -434,7 +411,21 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
   const bf16* q = (const bf16*)qkv;
   bf16* o = (bf16*)out;
   float* eh = sp.n > 1 ? nullptr : ent_heads;              // with split keys the merge writes the entropies
-#define FARD_ATT(DHV, NQBV) attn_bf16_kernel<DHV, NQBV><<<grid, 256, 0, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, eh, append, ps, sp)
+#define FARD_ATT(DHV, NQBV)                                                                                          \
+  do {                                                                                                               \
+    constexpr int lds = 4 * DHV * (32 * NQBV + 1) * 4;     /* the four waves' slabs of partial O^T */                 \
+    if constexpr (lds > 64 * 1024) {                                                                                 \
+      static bool attr_set = false;                                                                                  \
+      if (!attr_set) {                                                                                               \
+        hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel<DHV, NQBV>,                                 \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);                         \
+        if (e != hipSuccess) return e;                                                                               \
+        attr_set = true;                                                                                             \
+      }                                                                                                              \
+    }                                                                                                                \
+    attn_bf16_kernel<DHV, NQBV><<<grid, 256, lds, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, eh, \
+                                                       append, ps, sp);                                              \
+  } while (0)
   if (kv.d_head == 64) {
     if (cols <= 32) FARD_ATT(64, 1); else FARD_ATT(64, 2);
   } else if (kv.d_head == 128) {
