@@ -591,6 +591,7 @@ struct GemmExtra {
   const float *ada_mom = nullptr, *ada_c1 = nullptr, *ada_c0 = nullptr;
   int ada_mom_ld = 0, ada_ld = 0;
   float ada_eps = 0.f;
+  int a_tiled = 0, out_tiled = 0;
 };
 
 hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, void* out, int ldo, int M,
@@ -604,7 +605,7 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
     a.copy_bf16 = ex->copy_bf16; a.ln_cs = ex->ln_cs; a.ln_eps = ex->ln_eps; a.ln_rms = ex->ln_rms;
     a.copy_scale = ex->copy_scale; a.copy_ld = ex->copy_ld; a.mom_out = ex->mom_out; a.mom_ld = ex->mom_ld;
     a.ada_mom = ex->ada_mom; a.ada_mom_ld = ex->ada_mom_ld; a.ada_c1 = ex->ada_c1; a.ada_c0 = ex->ada_c0; a.ada_ld = ex->ada_ld;
-    a.ada_eps = ex->ada_eps;
+    a.ada_eps = ex->ada_eps; a.a_tiled = ex->a_tiled; a.out_tiled = ex->out_tiled;
   }
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
@@ -788,8 +789,8 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<float>(c, &c->xt, (size_t)M * D))) return rc;
   if ((rc = dalloc_bytes(c, &c->sc, (size_t)g.head.n_steps * M * w * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->a1, (size_t)M * w * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->a2, (size_t)M * w * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->hv, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->a2, (size_t)((M + 15) / 16 * 16) * w * c->esz))) return rc;   // (whole 16-row tiles)
+  if ((rc = dalloc_bytes(c, &c->hv, (size_t)((M + 15) / 16 * 16) * w * c->esz))) return rc;
   if ((rc = dalloc<float>(c, &c->hmom, (size_t)(w / 16 + 1) * M * 2))) return rc;
   if ((rc = dalloc<int>(c, &c->alive, g.max_batch))) return rc;
   if ((rc = dalloc<int>(c, &c->act_idx, g.max_batch))) return rc;
@@ -1072,12 +1073,20 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
     for (int j = 0; j < Nb; ++j) {
       const float* mj = modk + (size_t)3 * w * j;
       const bool folded = fold && j > 0;
+      // (with the fold, the bf16 rows between the narrow-kernel GEMMs -- a2, and v in hv -- are kept in tile order)
       if (!folded) {
         { Bracket br(c, CLS_OTHER);
           HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1)); }
-        HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
+        if (fold) {
+          GemmExtra ex;
+          ex.out_tiled = 1;
+          HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU, nullptr, 0, &ex));
+        } else {
+          HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
+        }
       } else {
         GemmExtra ex;
+        ex.a_tiled = 1; ex.out_tiled = 1;
         ex.ada_mom = c->hmom; ex.ada_mom_ld = w / 16;
         ex.ada_c0 = modk + (size_t)hw.fold_base + (size_t)2 * w * j; ex.ada_c1 = ex.ada_c0 + w; ex.ada_ld = hw.mod_n;
         ex.ada_eps = 1e-6f;
@@ -1085,8 +1094,13 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
       }
       if (fold && j + 1 < Nb) {
         GemmExtra ex;
+        ex.a_tiled = 1; ex.out_tiled = 1;
         ex.copy_bf16 = c->hv; ex.copy_scale = modk + (size_t)3 * w * (j + 1) + w; ex.copy_ld = hw.mod_n;
         ex.mom_out = c->hmom; ex.mom_ld = w / 16;
+        HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n, &ex));
+      } else if (fold) {
+        GemmExtra ex;
+        ex.a_tiled = 1;
         HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n, &ex));
       } else {
         HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n));

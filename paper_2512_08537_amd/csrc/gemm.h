@@ -55,6 +55,13 @@ struct GemmArgs {
   const float* ada_c0 = nullptr;
   int ada_ld = 0;
   float ada_eps = 0.f;
+  // Tile order for bf16 activations that pass from one narrow-kernel GEMM to the next (a_tiled: the A operand;
+  // out_tiled: what EPI_STORE stores and copy_bf16 receives): element (r, k) of a [rows, K] matrix at
+  //   ((((r / 16) (K / 32) + k / 32) 4 + k / 8 % 4) 16 + r % 16) 8 + k % 8,
+  // i.e. the 16-byte pieces a lane of the 16 x 16 x 32 MFMA reads, rows innermost, so that a wave's operand load
+  // reads 1 KiB of consecutive memory (lanes whose pieces lie a row apart are served one by one: measured 0.4 us of
+  // a 3.9 us launch at 8-16 rows, 0.8 us at 32).  Whole 16-row tiles must be allocated.
+  int a_tiled = 0, out_tiled = 0;
 };
 
 // Packed bf16 weight size in elements for a [K, N] matrix (K % 16 == 0, N % 32 == 0).

@@ -162,11 +162,14 @@ struct NarrowEpi {
       if constexpr (ADA) { if (a.ada_mom != nullptr) v = (v - c1[i] * rowstat[row * 2]) * rowstat[row * 2 + 1] + c0[i]; }
       v += bias4;
       const size_t o = (size_t)(m0 + row) * a.ldo + n0 + ec;
+      // the same 4 columns in tile order (GemmArgs::out_tiled): half a 16-byte piece
+      const int gr = m0 + row, gc = n0 + ec;
+      const size_t ot = ((((size_t)(gr >> 4) * (a.N >> 5) + (gc >> 5)) * 4 + ((gc >> 3) & 3)) * 16 + (gr & 15)) * 8 + (gc & 7);
       if (a.epi == EPI_STORE) {
         bf16x4 t;
 #pragma unroll
         for (int e = 0; e < 4; ++e) t[e] = (bf16)apply_act(v[e], a.act);
-        *(bf16x4*)((bf16*)a.out + o) = t;
+        *(bf16x4*)((bf16*)a.out + (a.out_tiled ? ot : o)) = t;
       } else if (a.epi == EPI_STORE_F32) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = apply_act(v[e], a.act);
@@ -185,7 +188,7 @@ struct NarrowEpi {
 #pragma unroll
             for (int e = 0; e < 4; ++e) t[e] = (bf16)nv[e];
           }
-          *(bf16x4*)((bf16*)a.copy_bf16 + o) = t;
+          *(bf16x4*)((bf16*)a.copy_bf16 + (a.out_tiled ? ot : o)) = t;
         }
         if (ADA && a.mom_out != nullptr) {
           // moments of the updated row over this 16-column tile: its 4 threads are one quad of lanes (the quad
@@ -240,11 +243,16 @@ __global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_na
                (lane & 15);
   }
   const bf16* __restrict__ abase[MT];
+  const int a_step = a.a_tiled ? 512 : 32;                 // elements between a lane's pieces of consecutive 32-k steps
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     int r = m0 + 16 * i + (lane & 15);
-    r = r < M ? r : M - 1;
-    abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
+    if (a.a_tiled) {                                       // tile order (GemmArgs::a_tiled): rows past M are allocated
+      abase[i] = (const bf16*)a.A + (((size_t)(r >> 4) * (a.K >> 5) * 4 + kg) * 16 + (r & 15)) * 8;
+    } else {
+      r = r < M ? r : M - 1;
+      abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
+    }
   }
   bf16x8 breg[NS][NT], areg[NS][MT];
   auto load_ab = [&](int t, int p) {
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_na
 #pragma unroll
     for (int j = 0; j < NT; ++j) breg[p][j] = bbase[j][(size_t)s * 128];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * 32);
+    for (int i = 0; i < MT; ++i) areg[p][i] = *(const bf16x8*)(abase[i] + (size_t)s * a_step);
   };
 #pragma unroll
   for (int p = 0; p < NS; ++p) load_ab(p, p);
@@ -333,6 +341,8 @@ bool narrow_supported(const GemmArgs& a) {
   if (a.ln_cs != nullptr && (a.epi == EPI_PARTIAL || a.k_slices > 1)) return false;
   if (a.copy_bf16 != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
   if (a.copy_scale != nullptr && a.copy_bf16 == nullptr) return false;
+  if (a.out_tiled && !(a.epi == EPI_STORE || a.copy_bf16 != nullptr)) return false;
+  if ((a.a_tiled || a.out_tiled) && (a.k_slices > 1 || a.ln_cs != nullptr)) return false;
   if (a.mom_out != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
   if (a.ada_mom != nullptr && ((a.epi != EPI_STORE && a.epi != EPI_STORE_F32) || a.ln_cs != nullptr || a.K > 2048 ||
                                a.ada_c1 == nullptr || a.ada_c0 == nullptr))
