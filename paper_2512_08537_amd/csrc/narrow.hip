@@ -221,9 +221,11 @@ __global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_na
   // not cost the 32 x 64 tile its second workgroup per compute unit: 16 registers over the limit otherwise)
   using Epi = NarrowEpi<MT, NT, ADA>;
   extern __shared__ __attribute__((aligned(16))) float red[];   // 4 * 16 * MT * Epi::LDT floats (+ 4 * 16 * MT * 2 if LNF) + 16 * MT * 2
-  const int M = eff_rows(a.M, a.m_dev);
+  // The operand loads are clamped by the host's row bound; the device-side row count, a dependent read, is only waited
+  // for when the loads are in flight (a launch would otherwise spend one more memory round trip before its first load).
+  const int Mh = a.M;
   const int m0 = blockIdx.y * 16 * MT;                     // row slab of this workgroup
-  if (m0 >= M) return;
+  if (m0 >= Mh) return;
   const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
   const int kb16 = a.K >> 4;
   // K slice of this workgroup (blockIdx.z; the whole K unless EPI_PARTIAL): 32-k steps [s0, s0 + kb32)
@@ -250,7 +252,7 @@ __global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_na
     if (a.a_tiled) {                                       // tile order (GemmArgs::a_tiled): rows past M are allocated
       abase[i] = (const bf16*)a.A + (((size_t)(r >> 4) * (a.K >> 5) * 4 + kg) * 16 + (r & 15)) * 8;
     } else {
-      r = r < M ? r : M - 1;
+      r = r < Mh ? r : Mh - 1;
       abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
     }
   }
@@ -267,7 +269,9 @@ __global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_na
   for (int p = 0; p < NS; ++p) load_ab(p, p);
 
   Epi epi;
-  epi.prefetch(a, M, m0, n0);
+  epi.prefetch(a, Mh, m0, n0);
+  const int M = eff_rows(a.M, a.m_dev);
+  if (m0 >= M) return;                                     // (uniform over the workgroup)
   __builtin_amdgcn_sched_barrier(0);
 
   f32x4 acc[MT][NT];
