@@ -198,3 +198,28 @@ def test_forward_of_72_rows_through_k_slice_planes():
         print(f"72 rows through planes, n_q {n_q.tolist()}: z {ez:.2e} shallow {es:.2e}")
         assert ez < 2e-2 and es < 2e-2
     ctx.close()
+
+
+def test_forward_of_72_rows_with_a_split_k_residual_product():
+    """72 rows through 1024-wide LayerNorm / GELU layers with a 4096-wide MLP: the down-projection (K = 4096, 8 MB of
+    weights: too small for planes, too long for the narrow kernel) runs in the streaming kernel with K split over
+    workgroups, one row tile, partial sums added to the residual stream with atomics from the LDS-staged epilogue."""
+    from synth.configs import RoundCfg, TfCfg, HeadCfg
+    tgt = TfCfg(n_layers=2, d_model=1024, n_heads=16, n_kv_heads=16, d_head=64, d_ff=4096, max_pos=64)
+    drf = TfCfg(n_layers=1, d_model=256, n_heads=4, n_kv_heads=4, d_head=64, d_ff=512, d_out=1024, max_pos=64)
+    rc = RoundCfg(name="split-72", target=tgt, draft=drf, head=HeadCfg(1, 128, 1024, n_steps=1), K=8, max_batch=8,
+                  max_ctx=64, entropy_layer=1, batch=8, n_ctx=40)
+    case = build_case(rc, seed=46)
+    ctx = make_ctx(case)
+    B, D = 8, 16
+    rng = np.random.default_rng(13)
+    for n_q in (np.full(B, 9), np.array([9, 2, 9, 9, 0, 9, 9, 5])):
+        xs = [gen.bf16_round(rng.normal(size=(n, D)).astype(np.float32)) for n in n_q]
+        z, sh, _ = ctx.spec_forward(0, ctx.dev_f32(_pack(xs)), n_q, commit=False, want_shallow=True, nq_max=9)
+        ctx.sync()
+        zo, sho, _ = _oracle_forward(case, 0, xs, shallow=1)
+        ez = rel_inf(z.float().cpu().numpy()[:int(n_q.sum())], np.concatenate(zo))
+        es = rel_inf(sh.cpu().numpy()[:int(n_q.sum())], np.concatenate(sho))
+        print(f"72 rows, split-K residual product, n_q {n_q.tolist()}: z {ez:.2e} shallow {es:.2e}")
+        assert ez < 2e-2 and es < 2e-2
+    ctx.close()
