@@ -610,6 +610,7 @@ hipError_t gemm(fard_ctx* c, const void* A, int lda, const void* W, const float*
   const double fl = 2.0 * M * (double)N * K;
   const double by = (double)K * N * c->esz + (double)M * K * c->esz + (double)M * (epi == EPI_SWIGLU ? N / 2 : N) * 4;
   const bool narrow = c->bf16 && routes_narrow(M, N, K, epi) && narrow_supported(a);
+  if (ex && !narrow) return hipErrorInvalidValue;
   Bracket br(c, narrow ? CLS_GEMM_NARROW : CLS_GEMM, fl, by);
   if (!c->bf16) return launch_gemm_f32(c->stream, a);
   if (narrow) return launch_gemm_narrow(c->stream, a);
@@ -768,10 +769,11 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<float>(c, &c->x_in, (size_t)MR * 16))) return rc;
   if ((rc = dalloc<float>(c, &c->ent_heads, (size_t)MR * hmax))) return rc;
   if ((rc = dalloc<float>(c, &c->h_row, (size_t)MR))) return rc;
-  if ((rc = dalloc_bytes(c, &c->u, (size_t)MR * dmax * c->esz))) return rc;
+  const size_t MRt = ((size_t)MR + 15) / 16 * 16;          // whole 16-row tiles for the buffers that may hold tile order
+  if ((rc = dalloc_bytes(c, &c->u, MRt * dmax * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->qkv, (size_t)MR * qmax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->ao, (size_t)MR * hdmax * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->ff, (size_t)MR * fmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ao, MRt * hdmax * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->ff, MRt * fmax * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->z, (size_t)MR * omax * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->ztmp, (size_t)MR * dmax * c->esz))) return rc;
   if ((rc = dalloc<int>(c, &c->maps.row_start, g.max_batch + 2))) return rc;
@@ -788,7 +790,7 @@ int alloc_workspace(fard_ctx* c) {
   if ((rc = dalloc<float>(c, &c->mod, (size_t)g.head.n_steps * M * c->head.mod_n))) return rc;
   if ((rc = dalloc<float>(c, &c->xt, (size_t)M * D))) return rc;
   if ((rc = dalloc_bytes(c, &c->sc, (size_t)g.head.n_steps * M * w * c->esz))) return rc;
-  if ((rc = dalloc_bytes(c, &c->a1, (size_t)M * w * c->esz))) return rc;
+  if ((rc = dalloc_bytes(c, &c->a1, (size_t)((M + 15) / 16 * 16) * w * c->esz))) return rc;
   if ((rc = dalloc_bytes(c, &c->a2, (size_t)((M + 15) / 16 * 16) * w * c->esz))) return rc;   // (whole 16-row tiles)
   if ((rc = dalloc_bytes(c, &c->hv, (size_t)((M + 15) / 16 * 16) * w * c->esz))) return rc;
   if ((rc = dalloc<float>(c, &c->hmom, (size_t)(w / 16 + 1) * M * 2))) return rc;
@@ -879,11 +881,13 @@ bool parts_eligible(const fard_ctx* c, int M, int N, int K) {
 
 // out planes <- A W (+ bias in plane 0); *n_planes and *stride describe them.  The planes are c->parts.
 hipError_t gemm_planes(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
-                       const int* m_dev, int* n_planes, size_t* stride) {
+                       const int* m_dev, int* n_planes, size_t* stride, int a_tiled = 0) {
   GemmArgs a;
   a.A = A; a.lda = lda; a.W = W; a.bias = bias; a.out = c->parts; a.ldo = N; a.gate = nullptr; a.ldg = 0;
   a.M = M; a.N = N; a.K = K; a.m_dev = m_dev; a.act = ACT_NONE; a.epi = EPI_PARTIAL;
   const int wide = plane_splits(c, M, N, K);
+  if (a_tiled && wide > 0) return hipErrorInvalidValue;      // (only the narrow kernel reads tile order)
+  a.a_tiled = a_tiled;
   a.k_slices = wide > 0 ? wide : (K + 1023) / 1024;
   a.part_stride = (size_t)M * N;
   if ((size_t)a.k_slices * a.part_stride > c->parts_cap) return hipErrorInvalidValue;   // never launch past the planes
@@ -900,10 +904,10 @@ hipError_t gemm_planes(fard_ctx* c, const void* A, int lda, const void* W, const
 
 // A residual update left as pending planes: the next norm adds them to the stream.
 hipError_t gemm_parts(fard_ctx* c, const void* A, int lda, const void* W, const float* bias, int M, int N, int K,
-                      const int* m_dev) {
+                      const int* m_dev, int a_tiled = 0) {
   int n = 0;
   size_t stride = 0;
-  hipError_t e = gemm_planes(c, A, lda, W, bias, M, N, K, m_dev, &n, &stride);
+  hipError_t e = gemm_planes(c, A, lda, W, bias, M, N, K, m_dev, &n, &stride, a_tiled);
   if (e == hipSuccess) {
     c->pend_n = n;
     c->pend_stride = stride;
@@ -919,6 +923,17 @@ int flush_parts(fard_ctx* c, int d, int M, const int* m_dev) {
   return FARD_OK;
 }
 
+// The bf16 activations that a narrow-tile GEMM reads (first-norm rows for QKV, attention output for the output
+// projection, second-norm rows and the MLP's hidden rows) are written in tile order (common.h: tile_offset) by their
+// producers; whether a buffer is tiled is a function of the consumer's route, i.e. of the shapes alone.
+bool qkv_reads_tiles(fard_ctx* c, const Model& m, int M) {
+  const fard_tf_cfg& t = m.c;
+  if (!c->bf16) return false;
+  const bool fused_append = t.pos != FARD_POS_ROPE;
+  if (!fused_append && plane_splits(c, M, m.qkv_n(), t.d_model) > 0) return false;
+  return routes_narrow(M, m.qkv_n(), t.d_model, EPI_STORE);
+}
+
 // Layers [l0, l1) of one model over the packed rows described by c->maps (h in, h out).
 // first_norm_done: c->u already holds the first norm of layer l0 (the embedding kernel wrote it).
 int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max, const int* m_dev, int ent_layer,
@@ -927,12 +942,18 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
   const fard_tf_cfg& t = m.c;
   hipStream_t s = c->stream;
   const int d = t.d_model, F = t.d_ff, HD = t.n_heads * t.d_head, QN = m.qkv_n();
+  // tile order of the bf16 buffers between the kernels (see qkv_reads_tiles): by the routes of the GEMMs that read them
+  const bool gelu = t.act == FARD_ACT_GELU;
+  const bool u1_tiled = qkv_reads_tiles(c, m, M);
+  const bool up_narrow = c->bf16 && gelu && routes_narrow(M, F, d, EPI_STORE);
+  const bool down_narrow = c->bf16 && (parts_eligible(c, M, d, F) ? plane_splits(c, M, d, F) == 0 : routes_narrow(M, d, F, EPI_RESID));
+  const bool ff_tiled = up_narrow && down_narrow;
   for (int l = l0; l < l1; ++l) {
     const LayerW& L = m.L[l];
     if (!(first_norm_done && l == l0 && c->pend_n == 0)) {
       Bracket br(c, CLS_OTHER);
       HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, nullptr, nullptr, 0, nullptr, c->u,
-                            c->parts, c->pend_n, c->pend_stride, c->h));
+                            c->parts, c->pend_n, c->pend_stride, c->h, u1_tiled));
       c->pend_n = 0;
     }
     KvGeom kg = kv_geom(c, m, l);
@@ -947,13 +968,22 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
       HIPCHK(c, launch_rope_append_planes(s, c->parts, n_pl, pl_stride, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE,
                                           t.rope_theta, c->maps.row_sample, c->maps.row_pos, M, m_dev));
     } else {
-      HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
+      if (u1_tiled) {
+        GemmExtra ex;
+        ex.a_tiled = 1;
+        HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE, nullptr, 0, &ex));
+      } else {
+        HIPCHK(c, gemm(c, c->u, d, L.wqkv, L.bqkv, c->qkv, QN, M, QN, d, m_dev, EPI_STORE, ACT_NONE));
+      }
       if (!fused_append) {
         Bracket br(c, CLS_OTHER);
         HIPCHK(c, launch_rope_append(s, c->qkv, QN, t.n_heads, kg, t.pos == FARD_POS_ROPE, t.rope_theta, c->maps.row_sample,
                                      c->maps.row_pos, M, m_dev));
       }
     }
+    const bool fold2 = c->bf16 && L.w1f != nullptr && gelu && routes_narrow(M, d, HD, EPI_RESID) &&
+                       routes_narrow(M, F, d, EPI_STORE);
+    const bool ao_tiled = fold2 || (c->bf16 && plane_splits(c, M, d, HD) == 0 && routes_narrow(M, d, HD, EPI_RESID));
     const int acap = cap_nq(c, which);
     if (nq_max <= acap) {
       // few samples x kv heads against a long cache: the key blocks of each are dealt to several workgroups (the
@@ -967,7 +997,7 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
       Bracket br(c, CLS_ATTN);
       HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, m.len, c->maps.row_start, B, nq_max, c->ao, HD,
                                  (l + 1 == ent_layer) ? c->ent_heads : nullptr, fused_append ? 1 : 0, nullptr, 1,
-                                 sp.n > 1 ? &sp : nullptr, M, m_dev));
+                                 sp.n > 1 ? &sp : nullptr, M, m_dev, ao_tiled));
     } else {
       // more rows per sample than one attention workgroup holds: passes of acap rows (c->ap_* hold their row ranges
       // and first positions), all in one launch once every row's K / V is in the cache
@@ -978,35 +1008,53 @@ int run_layers(fard_ctx* c, int which, int l0, int l1, int B, int M, int nq_max,
       }
       Bracket br(c, CLS_ATTN);
       HIPCHK(c, launch_attention(s, c->qkv, QN, t.n_heads, kg, c->ap_len, c->ap_start, B, acap, c->ao, HD,
-                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, 0, c->ap_cnt, n_pass));
+                                 (l + 1 == ent_layer) ? c->ent_heads : nullptr, 0, c->ap_cnt, n_pass, nullptr, 0, nullptr, ao_tiled));
     }
     // norm 2 without a launch of its own, when both GEMMs around it run in the narrow kernel: the output
     // projection also leaves the updated stream as bf16, and the up-projection (weights pre-scaled by the norm's
     // gain) sums the row statistics from its activation fragments and applies them in its epilogue
-    const bool fold2 = c->bf16 && L.w1f != nullptr && t.act == FARD_ACT_GELU && routes_narrow(M, d, HD, EPI_RESID) &&
-                       routes_narrow(M, F, d, EPI_STORE);
     if (fold2) {
       GemmExtra ex_o, ex_1;
       ex_o.copy_bf16 = c->u;
+      ex_o.a_tiled = 1; ex_o.out_tiled = 1;                // (ao and the bf16 copy of the stream in tile order)
+      ex_1.a_tiled = 1; ex_1.out_tiled = ff_tiled;
       HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE, nullptr, 0, &ex_o));
       ex_1.ln_cs = L.cs1; ex_1.ln_eps = t.norm_eps; ex_1.ln_rms = t.norm == FARD_NORM_RMS;
       HIPCHK(c, gemm(c, c->u, d, L.w1f, L.b1f, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU, nullptr, 0, &ex_1));
     } else {
       // (the output projection of the wide 72-row layers also leaves planes, which the second norm adds to the stream)
-      if (plane_splits(c, M, d, HD) > 0) HIPCHK(c, gemm_parts(c, c->ao, HD, L.wo, L.bo, M, d, HD, m_dev));
-      else HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
+      if (plane_splits(c, M, d, HD) > 0) {
+        HIPCHK(c, gemm_parts(c, c->ao, HD, L.wo, L.bo, M, d, HD, m_dev));
+      } else if (ao_tiled) {
+        GemmExtra ex;
+        ex.a_tiled = 1;
+        HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE, nullptr, 0, &ex));
+      } else {
+        HIPCHK(c, gemm(c, c->ao, HD, L.wo, L.bo, c->h, d, M, d, HD, m_dev, EPI_RESID, ACT_NONE));
+      }
       { Bracket br(c, CLS_OTHER);
         HIPCHK(c, launch_norm(s, c->bf16, c->h, d, M, m_dev, t.norm, t.norm_eps, L.n2g, L.n2b, nullptr, nullptr, 0, nullptr, c->u,
-                              c->parts, c->pend_n, c->pend_stride, c->h));
+                              c->parts, c->pend_n, c->pend_stride, c->h, up_narrow));
         c->pend_n = 0; }
-      if (t.act == FARD_ACT_GELU) {
+      if (up_narrow) {
+        GemmExtra ex;
+        ex.a_tiled = 1; ex.out_tiled = ff_tiled;
+        HIPCHK(c, gemm(c, c->u, d, L.w1, L.b1, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU, nullptr, 0, &ex));
+      } else if (gelu) {
         HIPCHK(c, gemm(c, c->u, d, L.w1, L.b1, c->ff, F, M, F, d, m_dev, EPI_STORE, ACT_GELU));
       } else {
         HIPCHK(c, gemm(c, c->u, d, L.w1, nullptr, c->ff, F, M, 2 * F, d, m_dev, EPI_SWIGLU, ACT_NONE));
       }
     }
-    if (parts_eligible(c, M, d, F)) HIPCHK(c, gemm_parts(c, c->ff, F, L.w2, L.b2, M, d, F, m_dev));
-    else HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
+    if (parts_eligible(c, M, d, F)) {
+      HIPCHK(c, gemm_parts(c, c->ff, F, L.w2, L.b2, M, d, F, m_dev, ff_tiled));
+    } else if (ff_tiled) {
+      GemmExtra ex;
+      ex.a_tiled = 1;
+      HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE, nullptr, 0, &ex));
+    } else {
+      HIPCHK(c, gemm(c, c->ff, F, L.w2, L.b2, c->h, d, M, d, F, m_dev, EPI_RESID, ACT_NONE));
+    }
   }
   return FARD_OK;
 }
@@ -1018,7 +1066,7 @@ hipError_t embed_first_norm(fard_ctx* c, int which, const float* x, int ldx, con
   const LayerW& L = m.L[0];
   Bracket br(c, CLS_OTHER);
   return launch_embed_norm(c->stream, c->bf16, x, ldx, t.d_latent, m.in_w, m.in_b, m.pos, c->maps.row_pos, m.cond, cond_id, c->h,
-                           t.d_model, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, c->u);
+                           t.d_model, M, m_dev, t.norm, t.norm_eps, L.n1g, L.n1b, c->u, qkv_reads_tiles(c, m, M));
 }
 
 // Final norm (optionally gathering rows through in_map) and up-projection -> z [n, d_out] storage type.
@@ -1063,6 +1111,9 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
   // c1_j = (1 + scale_j) W1_j and c0_j = shift_j W1_j (columns fold_base.. of the mod GEMM, computed only then).
   const bool fold = hw.fold_base > 0 && n <= 64 && routes_narrow(n, w, w, EPI_GATE_RESID) && routes_narrow(n, w, w, EPI_STORE) &&
                     w / 32 <= 48;
+  // the bf16 rows a narrow-tile GEMM of a block reads are in tile order: a1 (norm -> first GEMM), a2 and, with the fold, v
+  const bool g1_narrow = c->bf16 && routes_narrow(n, w, w, EPI_STORE), g2_narrow = c->bf16 && routes_narrow(n, w, w, EPI_GATE_RESID);
+  const bool a2_tiled = g1_narrow && g2_narrow;
   // the modulations of all S steps in one GEMM over S n rows (rows past the device-side count are unused)
   const int mod_cols = fold ? hw.mod_n : (hw.fold_base > 0 ? hw.fold_base : hw.mod_n);
   HIPCHK(c, gemm(c, c->sc, w, hw.mod_all, hw.mod_b_all, c->mod, hw.mod_n, S * n, mod_cols, w, nullptr, EPI_STORE_F32, ACT_NONE));
@@ -1073,13 +1124,13 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
     for (int j = 0; j < Nb; ++j) {
       const float* mj = modk + (size_t)3 * w * j;
       const bool folded = fold && j > 0;
-      // (with the fold, the bf16 rows between the narrow-kernel GEMMs -- a2, and v in hv -- are kept in tile order)
       if (!folded) {
         { Bracket br(c, CLS_OTHER);
-          HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1)); }
-        if (fold) {
+          HIPCHK(c, launch_norm(s, c->bf16, c->hh, w, n, n_dev, 0, 1e-6f, nullptr, nullptr, mj, mj + w, hw.mod_n, nullptr, c->a1,
+                                nullptr, 0, 0, nullptr, g1_narrow)); }
+        if (g1_narrow) {
           GemmExtra ex;
-          ex.out_tiled = 1;
+          ex.a_tiled = 1; ex.out_tiled = a2_tiled;
           HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU, nullptr, 0, &ex));
         } else {
           HIPCHK(c, gemm(c, c->a1, w, hw.B[j].w1, hw.B[j].b1, c->a2, w, n, w, w, n_dev, EPI_STORE, ACT_SILU));
@@ -1098,7 +1149,7 @@ int run_head(fard_ctx* c, const void* z, int n, const int* n_dev, const float* e
         ex.copy_bf16 = c->hv; ex.copy_scale = modk + (size_t)3 * w * (j + 1) + w; ex.copy_ld = hw.mod_n;
         ex.mom_out = c->hmom; ex.mom_ld = w / 16;
         HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n, &ex));
-      } else if (fold) {
+      } else if (a2_tiled) {
         GemmExtra ex;
         ex.a_tiled = 1;
         HIPCHK(c, gemm(c, c->a2, w, hw.B[j].w2, hw.B[j].b2, c->hh, w, n, w, w, n_dev, EPI_GATE_RESID, ACT_NONE, mj + 2 * w, hw.mod_n, &ex));

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
                                                         const int* __restrict__ cache_len,
                                                         const int* __restrict__ row_start, const int* __restrict__ row_cnt,
                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads,
-                                                        int append, int pass_stride, AttnSplit sp) {
+                                                        int append, int pass_stride, AttnSplit sp, int out_tiled) {
   constexpr int DC = DH / 16;      // k16 chunks of the head dim (QK^T)
   constexpr int DB = DH / 32;      // 32-dim row blocks of O^T
   constexpr int NCOL = 32 * NQB;
@@ -276,14 +276,16 @@ __global__ __launch_bounds__(256, ATTN_MIN_WG(DH, NQB)) void attn_bf16_kernel(co
       for (int w = 1; w < 4; ++w) acc += s_o[((size_t)w * DH + d8 * 8 + i) * OLD + c];
       v[i] = (bf16)(acc * inv);
     }
-    *(bf16x8*)(out + (size_t)(r0 + j) * ldo + (size_t)head * DH + d8 * 8) = v;
+    // (out_tiled: the rows in the tile order the output projection's narrow-tile GEMM reads; 8 dims are one piece)
+    *(bf16x8*)(out + (out_tiled ? tile_offset(r0 + j, head * DH + d8 * 8, ldo) : (size_t)(r0 + j) * ldo + (size_t)head * DH + d8 * 8)) = v;
     if (ent_heads != nullptr && d8 == 0) ent_heads[(size_t)(r0 + j) * n_heads + head] = logf(lstar) - astar * inv;
   }
 }
 
 // Folds the per-split results of attn_bf16_kernel: thread -> (row, head, 8 dims).
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnSplit sp, int n_heads, int dh, int M, const int* __restrict__ m_dev,
-                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads) {
+                                                         bf16* __restrict__ out, int ldo, float* __restrict__ ent_heads,
+                                                         int out_tiled) {
   const int Me = eff_rows(M, m_dev);
   const int d8n = dh >> 3;
   const long total = (long)Me * n_heads * d8n;
@@ -323,7 +325,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnSplit sp, int n_hea
     bf16x8 v;
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = (bf16)(acc[i] * inv);
-    *(bf16x8*)(out + (size_t)row * ldo + (size_t)head * dh + d8 * 8) = v;
+    *(bf16x8*)(out + (out_tiled ? tile_offset(row, head * dh + d8 * 8, ldo) : (size_t)row * ldo + (size_t)head * dh + d8 * 8)) = v;
     if (ent_heads != nullptr && d8 == 0) ent_heads[rh] = logf(lstar) - astar * inv;
   }
 }
@@ -383,10 +385,11 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float* __restrict__ 
 
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv, const int* cache_len,
                             const int* row_start, int B, int nq_max, void* out, int ldo, float* ent_heads, int append,
-                            const int* row_cnt, int n_pass, const AttnSplit* split, int M, const int* m_dev) {
+                            const int* row_cnt, int n_pass, const AttnSplit* split, int M, const int* m_dev, int out_tiled) {
   if (B <= 0 || nq_max <= 0 || n_pass <= 0) return hipSuccess;
   // several passes at once read rows that an earlier pass of the same launch would have had to store
   if (n_pass > 1 && (append || row_cnt == nullptr || n_pass > 65535 || (long)B * n_pass > 65535)) return hipErrorInvalidValue;
+  if (out_tiled && (!kv.is_bf16 || ldo % 32 != 0)) return hipErrorInvalidValue;
   if (!kv.is_bf16) {
     if (append) return hipErrorInvalidValue;
     dim3 grid(n_heads, nq_max, B * n_pass);
@@ -424,7 +427,7 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
       }                                                                                                              \
     }                                                                                                                \
     attn_bf16_kernel<DHV, NQBV><<<grid, 256, lds, s>>>(q, ld, n_heads, kv, cache_len, row_start, row_cnt, o, ldo, eh, \
-                                                       append, ps, sp);                                              \
+                                                       append, ps, sp, out_tiled);                                   \
   } while (0)
   if (kv.d_head == 64) {
     if (cols <= 32) FARD_ATT(64, 1); else FARD_ATT(64, 2);
@@ -440,7 +443,7 @@ hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads,
   if (e != hipSuccess || sp.n <= 1) return e;
   const long total = (long)M * n_heads * (kv.d_head / 8);
   const unsigned blocks = (unsigned)std::min<long>((total + 255) / 256, 2048);
-  attn_merge_kernel<<<blocks, 256, 0, s>>>(sp, n_heads, kv.d_head, M, m_dev, o, ldo, ent_heads);
+  attn_merge_kernel<<<blocks, 256, 0, s>>>(sp, n_heads, kv.d_head, M, m_dev, o, ldo, ent_heads, out_tiled);
   return hipGetLastError();
 }
 

@@ -104,6 +104,14 @@ __device__ __forceinline__ float xor16_sum(float v) {
   return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
+// Tile order of a bf16 activation matrix [rows, K] (K % 32 == 0) that a narrow-tile GEMM reads as its A operand: the
+// 16-byte pieces a lane of the 16 x 16 x 32 MFMA takes (8 consecutive k of one row), rows innermost inside a block of
+// 16 rows x 32 k, so that a wave's operand load reads 1 KiB of consecutive memory (GemmArgs::a_tiled).  Offset in
+// elements of (r, k); 4 or 8 consecutive k starting at a multiple of 4 or 8 stay contiguous.
+__device__ __host__ __forceinline__ size_t tile_offset(int r, int k, int K) {
+  return ((((size_t)(r >> 4) * (size_t)(K >> 5) + (size_t)(k >> 5)) * 4 + (size_t)((k >> 3) & 3)) * 16 + (size_t)(r & 15)) * 8 + (size_t)(k & 7);
+}
+
 // effective row count: host upper bound clipped by an optional device-side count
 __device__ __forceinline__ int eff_rows(int m_host, const int* m_dev) {
   if (m_dev == nullptr) return m_host;

@@ -43,7 +43,8 @@ hipError_t launch_embed(hipStream_t s, int is_bf16, const float* x, int ldx, int
 // one launch.
 hipError_t launch_embed_norm(hipStream_t s, int is_bf16, const float* x, int ldx, int D, const void* w_in, const float* b_in,
                              const void* pos_table, const int* row_pos, const void* cond_table, const int* cond_id, float* h,
-                             int d, int M, const int* m_dev, int norm_type, float eps, const float* g, const float* b, void* u);
+                             int d, int M, const int* m_dev, int norm_type, float eps, const float* g, const float* b, void* u,
+                             int u_tiled = 0);
 
 // out_T[r, :] = norm(h[r, :]) with optional affine (g, b) and optional AdaLN modulation
 // (1 + scale[r, :]) / shift[r, :] read with row stride ldm.  norm_type 0 LayerNorm, 1 RMSNorm.
@@ -51,7 +52,8 @@ hipError_t launch_embed_norm(hipStream_t s, int is_bf16, const float* x, int ldx
 hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M, const int* m_dev,
                        int norm_type, float eps, const float* g, const float* b, const float* shift,
                        const float* scale, int ldm, const int* in_map, void* out,
-                       const float* parts = nullptr, int n_parts = 0, size_t part_stride = 0, float* h_wb = nullptr);
+                       const float* parts = nullptr, int n_parts = 0, size_t part_stride = 0, float* h_wb = nullptr,
+                       int out_tiled = 0);
 // parts / n_parts / part_stride: K-slice partial sums [n_parts][M, d] that a preceding GEMM left for the
 // residual stream; the norm adds them to its input row first and writes the completed row to h_wb (if given).
 hipError_t launch_add_parts(hipStream_t s, float* h, const float* parts, int n_parts, size_t part_stride, int d,
@@ -112,7 +114,8 @@ struct AttnSplit {
 hipError_t launch_attention(hipStream_t s, const void* qkv, int ld, int n_heads, KvGeom kv,
                             const int* cache_len, const int* row_start, int B, int nq_max,
                             void* out, int ldo, float* ent_heads, int append, const int* row_cnt = nullptr,
-                            int n_pass = 1, const AttnSplit* split = nullptr, int M = 0, const int* m_dev = nullptr);
+                            int n_pass = 1, const AttnSplit* split = nullptr, int M = 0, const int* m_dev = nullptr,
+                            int out_tiled = 0);
 
 // Shallow-feature entropy + threshold + prefix rule + compaction.  feat: [B, K, L] storage type.
 // Up to ENT_SAMPLE_MODE_MIN_B samples: a wave per row, then one workgroup thresholds and compacts.  Above: a

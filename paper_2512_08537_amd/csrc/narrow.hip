@@ -249,10 +249,10 @@ __global__ __launch_bounds__(256, (LNF && NS == 8 && !ADA) ? 2 : 1) void gemm_na
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     int r = m0 + 16 * i + (lane & 15);
-    if (a.a_tiled) {                                       // tile order (GemmArgs::a_tiled): rows past M are allocated
+    r = r < Mh ? r : Mh - 1;                               // (a workgroup's last row tiles may lie past the matrix)
+    if (a.a_tiled) {                                       // tile order (GemmArgs::a_tiled)
       abase[i] = (const bf16*)a.A + (((size_t)(r >> 4) * (a.K >> 5) * 4 + kg) * 16 + (r & 15)) * 8;
     } else {
-      r = r < Mh ? r : Mh - 1;
       abase[i] = (const bf16*)a.A + (size_t)r * a.lda + kg * 8;
     }
   }
@@ -346,7 +346,8 @@ bool narrow_supported(const GemmArgs& a) {
   if (a.copy_bf16 != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
   if (a.copy_scale != nullptr && a.copy_bf16 == nullptr) return false;
   if (a.out_tiled && !(a.epi == EPI_STORE || a.copy_bf16 != nullptr)) return false;
-  if ((a.a_tiled || a.out_tiled) && (a.k_slices > 1 || a.ln_cs != nullptr)) return false;
+  if (a.out_tiled && a.k_slices > 1) return false;
+  if ((a.a_tiled && a.K % 32 != 0) || (a.out_tiled && a.N % 32 != 0)) return false;
   if (a.mom_out != nullptr && a.epi != EPI_RESID && a.epi != EPI_GATE_RESID) return false;
   if (a.ada_mom != nullptr && ((a.epi != EPI_STORE && a.epi != EPI_STORE_F32) || a.ln_cs != nullptr || a.K > 2048 ||
                                a.ada_c1 == nullptr || a.ada_c0 == nullptr))

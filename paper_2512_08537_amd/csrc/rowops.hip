@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
                                                    const float* __restrict__ scale, int ldm,
                                                    const int* __restrict__ in_map, T* __restrict__ out,
                                                    const float* __restrict__ parts, int n_parts, size_t part_stride,
-                                                   float* __restrict__ h_wb) {
+                                                   float* __restrict__ h_wb, int out_tiled) {
   __shared__ float red[8];
   const int Me = eff_rows(M, m_dev);
   const int r = blockIdx.x;
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ h, 
     if (g) { const f32x4 v = ((const f32x4*)g)[c4]; y *= v; }
     if (b) { const f32x4 v = ((const f32x4*)b)[c4]; y += v; }
     if (scale) y = y * (1.0f + scv[i]) + shv[i];
-    store4<T>(out + (size_t)r * d + c4 * 4, y[0], y[1], y[2], y[3]);
+    store4<T>(out + (out_tiled ? tile_offset(r, c4 * 4, d) : (size_t)r * d + c4 * 4), y[0], y[1], y[2], y[3]);
   }
 }
 
@@ -1274,7 +1274,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const float* __restrict
                                                          const int* __restrict__ row_pos, const T* __restrict__ cond_table,
                                                          const int* __restrict__ cond_id, float* __restrict__ h, int d, int M,
                                                          const int* m_dev, int norm_type, float eps, const float* __restrict__ g,
-                                                         const float* __restrict__ b, T* __restrict__ u) {
+                                                         const float* __restrict__ b, T* __restrict__ u, int u_tiled) {
   __shared__ float red[8];
   const int Me = eff_rows(M, m_dev);
   const int r = blockIdx.x;
@@ -1328,25 +1328,26 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const float* __restrict
     for (int e = 0; e < 4; ++e) y[e] = (v[i][e] - mean) * rstd;
     if (g) y *= ((const f32x4*)g)[c4];
     if (b) y += ((const f32x4*)b)[c4];
-    store4<T>(u + (size_t)r * d + c4 * 4, y[0], y[1], y[2], y[3]);
+    store4<T>(u + (u_tiled ? tile_offset(r, c4 * 4, d) : (size_t)r * d + c4 * 4), y[0], y[1], y[2], y[3]);
   }
 }
 
 hipError_t launch_embed_norm(hipStream_t s, int is_bf16, const float* x, int ldx, int D, const void* w_in, const float* b_in,
                              const void* pos_table, const int* row_pos, const void* cond_table, const int* cond_id, float* h,
-                             int d, int M, const int* m_dev, int norm_type, float eps, const float* g, const float* b, void* u) {
+                             int d, int M, const int* m_dev, int norm_type, float eps, const float* g, const float* b, void* u,
+                             int u_tiled) {
   if (M <= 0) return hipSuccess;
-  if (d % 4 != 0 || d > 256 * 4 * NORM_VPT) return hipErrorInvalidValue;
+  if (d % 4 != 0 || d > 256 * 4 * NORM_VPT || (u_tiled && (!is_bf16 || d % 32 != 0))) return hipErrorInvalidValue;
 #define FARD_EN(VPT)                                                                                                       \
   do {                                                                                                                     \
     if (is_bf16)                                                                                                           \
       embed_norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(x, ldx, D, (const bf16*)w_in, b_in, (const bf16*)pos_table, row_pos,  \
                                                      (const bf16*)cond_table, cond_id, h, d, M, m_dev, norm_type, eps, g, b, \
-                                                     (bf16*)u);                                                            \
+                                                     (bf16*)u, u_tiled);                                                   \
     else                                                                                                                   \
       embed_norm_kernel<float, VPT><<<M, 256, 0, s>>>(x, ldx, D, (const float*)w_in, b_in, (const float*)pos_table, row_pos, \
                                                       (const float*)cond_table, cond_id, h, d, M, m_dev, norm_type, eps, g, b, \
-                                                      (float*)u);                                                          \
+                                                      (float*)u, 0);                                                       \
   } while (0)
   const int n4 = d >> 2;
   if (n4 <= 256) FARD_EN(1);
@@ -1366,15 +1367,16 @@ hipError_t launch_add_parts(hipStream_t s, float* h, const float* parts, int n_p
 
 hipError_t launch_norm(hipStream_t s, int is_bf16, const float* h, int d, int M, const int* m_dev, int norm_type,
                        float eps, const float* g, const float* b, const float* shift, const float* scale, int ldm,
-                       const int* in_map, void* out, const float* parts, int n_parts, size_t part_stride, float* h_wb) {
+                       const int* in_map, void* out, const float* parts, int n_parts, size_t part_stride, float* h_wb,
+                       int out_tiled) {
   if (M <= 0) return hipSuccess;
-  if (d % 4 != 0 || d > 256 * 4 * NORM_VPT || ldm % 4 != 0) return hipErrorInvalidValue;
+  if (d % 4 != 0 || d > 256 * 4 * NORM_VPT || ldm % 4 != 0 || (out_tiled && (!is_bf16 || d % 32 != 0))) return hipErrorInvalidValue;
 #define FARD_NORM(VPT)                                                                                                 \
   do {                                                                                                                 \
     if (is_bf16)                                                                                                       \
-      norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out, parts, n_parts, part_stride, h_wb);  \
+      norm_kernel<bf16, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (bf16*)out, parts, n_parts, part_stride, h_wb, out_tiled);  \
     else                                                                                                               \
-      norm_kernel<float, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out, parts, n_parts, part_stride, h_wb); \
+      norm_kernel<float, VPT><<<M, 256, 0, s>>>(h, d, M, m_dev, norm_type, eps, g, b, shift, scale, ldm, in_map, (float*)out, parts, n_parts, part_stride, h_wb, 0); \
   } while (0)
   if (d <= 1024) FARD_NORM(1);
   else if (d <= 2048) FARD_NORM(2);
