@@ -349,6 +349,27 @@ def test_diffhead_decode_with_rows_far_from_zero_mean(shift, n):
     ctx.close()
 
 
+def test_diffhead_decode_of_72_rows_in_tile_order():
+    """72 rows (not a multiple of the narrow kernel's 32-row workgroups) through a 256-wide head: the rows between the
+    norm and the GEMMs are in tile order, and the last workgroup's second row tile lies past the matrix."""
+    from oracle import head as ohd
+    from synth.configs import RoundCfg, TfCfg, HeadCfg
+    tf = TfCfg(n_layers=1, d_model=128, n_heads=2, n_kv_heads=2, d_head=64, d_ff=256, max_pos=32)
+    rc = RoundCfg(name="head-72", target=tf, draft=tf, head=HeadCfg(3, 256, 128, n_steps=2), K=8, max_batch=8, max_ctx=32,
+                  entropy_layer=1, batch=8, n_ctx=8)
+    case = build_case(rc, seed=7)
+    ctx = make_ctx(case)
+    n, D, S = 72, rc.head.d_latent, rc.head.n_steps
+    z = gen.normal(14, "z72", (n, rc.head.d_cond), 1.0, rc.dtype)
+    eps = gen.noise(14, "e72", (S + 1, n, D))
+    mu, x = ctx.diffhead_decode(ctx.dev_store(z), ctx.dev_f32(eps))
+    ctx.sync()
+    mu_o, x_o = ohd.decode(rc.head, case.W, z, eps)
+    assert rel_inf(mu.cpu().numpy(), mu_o) < 2e-2
+    assert rel_inf(x.cpu().numpy(), x_o) < 2e-2
+    ctx.close()
+
+
 def test_head_closed_form_zero_weights():
     """All head weights zero except the output bias: mu = temperature*eps0 - b_out (1 step)."""
     case = build_case("ln-gelu-bf16", seed=1)
